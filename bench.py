@@ -1,0 +1,151 @@
+"""Benchmark of the ERNIE generation hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of the ERNIE-base
+workload (batch 32, prompt 128, 32 generated tokens, untrimmed 18000-row table):
+one prefill plus 31 free-running decode steps (the on-device argmax feeds the
+next step; no host round trip).  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
+MFMA_F16_PEAK_TFLOPS = 2500.0
+
+
+def algorithmic_decode_bytes(sh, B, c_keys):
+    """Bytes one decode step must move: every layer weight once, the trimmed table once,
+    the cached K and V of all visible positions, and the appended K, V (fp16)."""
+    d, f, Nl = sh.d_model, sh.d_ffn, sh.n_layers
+    weights = Nl * (4 * d * d + 2 * d * f) * 2
+    table = sh.vocab_kept * d * 2
+    kv_read = B * Nl * 2 * c_keys * d * 2
+    kv_append = B * Nl * 2 * d * 2
+    return weights + table + kv_read + kv_append
+
+
+def prefill_flops(sh, lens):
+    """Pad-free flops of one prefill: layer GEMMs, attention, last-row logits."""
+    d, f, Nl = sh.d_model, sh.d_ffn, sh.n_layers
+    T = int(sum(lens))
+    gemm = Nl * T * (8 * d * d + 4 * d * f)
+    attn = Nl * sum(4 * int(L) * int(L) * d for L in lens)
+    logits = 2 * len(lens) * d * sh.vocab_kept
+    return gemm + attn + logits
+
+
+def cpu_baseline(wl, rows, n_gen):
+    """The oracle's cached path, as it stands, on a bounded sample of the same workload."""
+    from oracle import ernie_oracle as O
+    from threadpoolctl import threadpool_info
+    p = O.Params(wl.weights, wl.shape.n_heads, wl.shape.ln_eps)
+    t0 = time.perf_counter()
+    for r in rows:
+        O.generate_cached(p, wl.batches_full[0][r], n_gen, wl.kept_ids)
+    dt = time.perf_counter() - t0
+    threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    return {"value": len(rows) * n_gen / dt, "unit": "generated tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{len(rows)} of {wl.shape.batch} sequences of the same batch, prompt {wl.shape.prompt_len}, "
+                      f"{n_gen} tokens each, fp64 cached path, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="base")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (sequences shard by batch with no collective); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2407_04991_amd as E
+    from synth import make_workload
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
+    wl = make_workload(args.workload)
+    sh = wl.shape
+    eng = E.engine_from_workload(wl)
+    ids_np, lens = wl.padded(0)
+    B, N = sh.batch, sh.n_gen
+    ids = torch.as_tensor(ids_np).to("cuda:0")
+    tok = torch.empty(B, dtype=torch.int32, device="cuda:0")
+    h = eng.handle
+
+    def one_pass():
+        rc = E.ernie_prefill(h, B, ids.shape[1], ids, lens, None, None, tok)
+        assert rc == 0, rc
+        for _ in range(N - 1):
+            rc = E.ernie_decode_step(h, None, None, None, tok)
+            assert rc == 0, rc
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_pass()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = B * N / (dt / args.steps)
+
+    # per-phase device time with events on the stream the kernels are launched on (torch's current stream)
+    reps = max(3, min(args.steps, 10))
+    pre_ms, dec_ms = [], []
+    for _ in range(reps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(N + 1)]
+        e[0].record()
+        E.ernie_prefill(h, B, ids.shape[1], ids, lens, None, None, tok)
+        e[1].record()
+        for t in range(1, N):
+            E.ernie_decode_step(h, None, None, None, tok)
+            e[t + 1].record()
+        torch.cuda.synchronize()
+        pre_ms.append(e[0].elapsed_time(e[1]))
+        dec_ms.append([e[t].elapsed_time(e[t + 1]) for t in range(1, N)])
+    pre = float(np.median(pre_ms))
+    dec = np.median(np.array(dec_ms), axis=0)            # per decode step index
+    L = int(lens.max())
+    step_bytes = np.array([algorithmic_decode_bytes(sh, B, int(np.mean(lens)) + t + 1) for t in range(N - 1)])
+    dec_gbs = float(np.mean(step_bytes / (dec * 1e-3)) / 1e9)
+    pf = prefill_flops(sh, lens)
+
+    out = {
+        "metric": "generated tokens/sec (ERNIE-base FP16, 1 GPU)", "value": tokens_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{sh.name}: {sh.n_layers} layers d={sh.d_model} heads={sh.n_heads} ffn={sh.d_ffn} "
+                               f"V'={sh.vocab_kept}/{sh.vocab_full}, batch {B}, prompt {L}, generate {N} "
+                               f"(1 prefill + {N - 1} decode steps, greedy, free-running)"},
+        "prefill_ms": pre, "prefill_tflops": pf / (pre * 1e-3) / 1e12,
+        "prefill_frac_of_mfma_peak": pf / (pre * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS,
+        "decode_step_ms_mean": float(dec.mean()), "decode_step_ms_median": float(np.median(dec)),
+        "decode_tokens_per_s": B / (float(dec.mean()) * 1e-3),
+        "roofline": {"kernel": "decode step (all kernels of one step)", "bound": "hbm", "achieved": dec_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        rows = list(range(min(args.cpu_rows, B)))
+        out["cpu_baseline"] = cpu_baseline(wl, rows, N)
+    eng.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,167 @@
+/*
+ * ernie.h -- C ABI of the MI355X (gfx950) ERNIE / UNIMO-text generation hot path.
+ *
+ * What the library computes (paper: Method, "Model-level optimization"):
+ * the FP16 forward of a stack of transformer layers with multi-head
+ * self-attention and feed-forward blocks, run as ONE prefill pass over the
+ * prompts plus one incremental decode step per generated token that reuses
+ * the cached keys and values of all earlier positions (item 3, "Key-Value
+ * cache"), followed by the output projection onto the word-embedding matrix
+ * trimmed to its frequently used rows ("Embedding layer pruning") and a greedy
+ * argmax.  The prompt is attended bidirectionally, generated tokens causally.
+ *
+ * Conventions common to every entry point
+ *  - All pointers named *_dev are DEVICE pointers, *_host are HOST pointers.
+ *  - Parameters and activations are IEEE fp16, row-major; accumulation, softmax
+ *    and LayerNorm statistics are fp32; logits and hidden outputs are fp32;
+ *    token ids are int32 in TRIMMED index space [0, vocab_kept).  The caller
+ *    converts to full-vocabulary ids with kept_ids[] (host post-processing).
+ *    Ids are not range-checked on the device.
+ *  - The caller owns every buffer: parameters, the arena, inputs, outputs, and
+ *    the stream.  The library calls no hipMalloc / hipFree in prefill or decode
+ *    and enqueues all work on `stream` (a hipStream_t passed as void*; NULL =
+ *    the default stream) without synchronising the host, so outputs are valid
+ *    once the caller has synchronised the stream.
+ *  - A handle is not thread-safe and carries one in-flight batch.
+ *  - Return value: 0 on success, a negative ERNIE_E* code otherwise.  Codes
+ *    -1..-4 are decided on the host before anything is enqueued and leave the
+ *    handle's state unchanged.
+ */
+#ifndef ERNIE_H_
+#define ERNIE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ERNIE_OK          0
+#define ERNIE_EINVAL     (-1)  /* NULL / misaligned pointer, unsupported shape, length out of range */
+#define ERNIE_ECAPACITY  (-2)  /* batch, sequence or position beyond the configured capacity */
+#define ERNIE_EARENA     (-3)  /* arena too small (*arena_needed is set) */
+#define ERNIE_ESEQUENCE  (-4)  /* decode step before a prefill */
+#define ERNIE_EHIP       (-5)  /* HIP runtime error while enqueueing */
+
+typedef struct ErnieHandle ErnieHandle;   /* opaque, library-owned host object */
+
+/* Static shape and capacity.  head_dim = d_model / n_heads must be 64 and
+ * d_ffn a multiple of 64.  The key/value cache (Method item 3) holds
+ * max_batch sequences of max_seq positions each (prompt + generated). */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, d_ffn;
+  int32_t vocab_full, vocab_kept, max_pos;   /* V, V' (rows of the trimmed table), rows of the position table */
+  int32_t max_batch, max_seq;
+  float   ln_eps;
+} ErnieConfig;
+
+/* Caller-owned DEVICE tensors, fp16 row-major.  Matrices are stored
+ * [out, in].  The six/eight per-layer arrays of pointers live on the HOST and
+ * have n_layers entries each.
+ *   tok_emb_kept [V', d]  rows kept_ids[i] of the full word-embedding matrix;
+ *                         used for the input gather AND the output projection
+ *   kept_ids     [V']     ascending full-vocabulary ids (int32); stored, not used on the hot path
+ *   pos_emb      [P, d]
+ *   wqkv[l]      [3d, d]  rows 0..d-1 = Q, d..2d-1 = K, 2d..3d-1 = V; head h = rows 64h..64h+63 of each block
+ */
+typedef struct {
+  const void*    tok_emb_kept;
+  const int32_t* kept_ids;
+  const void*    pos_emb;
+  const void*    emb_ln_g;  const void* emb_ln_b;      /* [d] */
+  const void* const* wqkv;  const void* const* bqkv;   /* [3d, d], [3d] */
+  const void* const* wo;    const void* const* bo;     /* [d, d],  [d]  */
+  const void* const* ln1_g; const void* const* ln1_b;  /* [d] */
+  const void* const* w1;    const void* const* b1;     /* [f, d],  [f]  */
+  const void* const* w2;    const void* const* b2;     /* [d, f],  [d]  */
+  const void* const* ln2_g; const void* const* ln2_b;  /* [d] */
+} ErnieWeights;
+
+/*
+ * ernie_init_weights -- size the arena, or ingest the parameters.
+ *
+ * With arena_dev == NULL: validates cfg, writes the number of bytes the
+ * library needs (repacked parameters + key/value cache + activations) to
+ * *arena_needed and returns ERNIE_OK; `weights` and `out` may be NULL.
+ *
+ * With an arena: additionally repacks every parameter into it (the trimmed
+ * word-embedding matrix of "Embedding layer pruning" is kept both row-major
+ * for the input gather and tiled for the output projection), so the caller's
+ * originals may be freed once `stream` has been synchronised, and returns a
+ * handle in *out.  arena_dev must be 256-byte aligned; its contents belong to
+ * the library until ernie_free.
+ *
+ * Errors: ERNIE_EINVAL (NULL cfg/out/weight pointer, head_dim != 64,
+ * non-positive sizes, misaligned arena), ERNIE_EARENA, ERNIE_EHIP.
+ */
+int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* weights,
+                       void* arena_dev, size_t arena_bytes, size_t* arena_needed,
+                       void* stream, ErnieHandle** out);
+
+/*
+ * ernie_prefill -- one pass over a batch of prompts (FP16 forward, Method
+ * item 1; fills the key/value cache of Method item 3) and emission of the
+ * first generated token of every sequence from its last prompt position.
+ *
+ *   B, Lmax            batch size and row pitch of ids_dev
+ *   ids_dev            [B, Lmax] trimmed-index prompt ids, right-padded (pad values are ignored)
+ *   prompt_lens_host   [B], 1 <= L_b <= Lmax; read before the call returns
+ *   logits_out_dev     [B, V'] fp32 logits over the trimmed table, or NULL
+ *   hidden_out_dev     [B, d]  fp32 final hidden state at the emitting position, or NULL
+ *   tok_out_dev        [B]     int32 argmax (lowest index on exact ties), never NULL
+ *
+ * Resets the cache: sequence b then holds L_b positions.  Padded positions
+ * are never visible as keys.
+ * Errors: ERNIE_EINVAL, ERNIE_ECAPACITY (B > max_batch, Lmax > max_seq,
+ * Lmax > max_pos), ERNIE_EHIP.
+ */
+int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax,
+                  const int32_t* ids_dev, const int32_t* prompt_lens_host,
+                  float* logits_out_dev, float* hidden_out_dev, int32_t* tok_out_dev,
+                  void* stream);
+
+/*
+ * ernie_decode_step -- one incremental step for every sequence of the batch
+ * last given to ernie_prefill: embeds one token per sequence at its next
+ * position, appends its key and value to the cache, attends over everything
+ * cached (Method item 3: earlier keys/values are read, not recomputed), and
+ * emits the next token.
+ *
+ *   tok_in_dev   [B] trimmed ids to feed (teacher forcing), or NULL to feed
+ *                the tokens the previous call emitted (free-running; they are
+ *                kept on the device, no host round trip)
+ *   outputs      as in ernie_prefill
+ *
+ * The per-sequence lengths live on the device and advance by one per call, so
+ * a stream capture of this call can be replayed.  The host-side capacity check
+ * counts calls made through this function only; a replayed capture that runs
+ * past max_seq or max_pos makes the kernels skip the step for that sequence
+ * instead of writing out of bounds.
+ * Errors: ERNIE_ESEQUENCE (no prefill yet), ERNIE_ECAPACITY (some sequence
+ * would exceed max_seq or max_pos), ERNIE_EINVAL, ERNIE_EHIP.
+ */
+int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev,
+                      float* logits_out_dev, float* hidden_out_dev, int32_t* tok_out_dev,
+                      void* stream);
+
+/* ernie_free -- releases the host-side handle (the arena stays the caller's). NULL is a no-op. */
+void ernie_free(ErnieHandle* h);
+
+/*
+ * ernie_debug_buffer -- test hook: device address and size in bytes of an
+ * internal buffer, for layer-by-layer comparison with a reference.  `name`
+ * is one of "x" (layer input/output activations [T, d] fp16), "kv" (the
+ * key/value cache [n_layers][2][max_batch][n_heads][max_seq][64] fp16),
+ * "lens" ([max_batch] int32 cached lengths).  Returns ERNIE_EINVAL for an
+ * unknown name.  Not part of the hot path.
+ */
+int ernie_debug_buffer(ErnieHandle* h, const char* name, void** ptr_dev, size_t* bytes);
+
+/* ernie_error_string -- static description of an ERNIE_E* code. */
+const char* ernie_error_string(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif  /* ERNIE_H_ */

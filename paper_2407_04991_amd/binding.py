@@ -1,0 +1,234 @@
+"""ctypes binding of the C ABI in include/ernie.h.
+
+Argument marshalling only: every step of the hot path runs in the HIP
+library.  PyTorch supplies device memory (tensors) and streams; no torch op
+takes part in the computation.  If the library has not been built, loading
+fails with an error -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libernie_hip.so")
+
+ERNIE_OK, ERNIE_EINVAL, ERNIE_ECAPACITY, ERNIE_EARENA, ERNIE_ESEQUENCE, ERNIE_EHIP = 0, -1, -2, -3, -4, -5
+
+EXPORTS = ("ernie_init_weights", "ernie_prefill", "ernie_decode_step", "ernie_free",
+           "ernie_debug_buffer", "ernie_error_string")
+
+
+class ErnieConfig(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ffn", C.c_int32),
+                ("vocab_full", C.c_int32), ("vocab_kept", C.c_int32), ("max_pos", C.c_int32),
+                ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("ln_eps", C.c_float)]
+
+
+_PP = C.POINTER(C.c_void_p)
+
+
+class ErnieWeights(C.Structure):
+    _fields_ = [("tok_emb_kept", C.c_void_p), ("kept_ids", C.c_void_p), ("pos_emb", C.c_void_p),
+                ("emb_ln_g", C.c_void_p), ("emb_ln_b", C.c_void_p),
+                ("wqkv", _PP), ("bqkv", _PP), ("wo", _PP), ("bo", _PP), ("ln1_g", _PP), ("ln1_b", _PP),
+                ("w1", _PP), ("b1", _PP), ("w2", _PP), ("b2", _PP), ("ln2_g", _PP), ("ln2_b", _PP)]
+
+
+class ErnieError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {error_string(code)} ({code})")
+
+
+_lib = None
+
+
+def load_library(path: Optional[str] = None) -> C.CDLL:
+    """Load libernie_hip.so (built in-tree by paper_2407_04991_amd.build)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        raise FileNotFoundError(
+            f"{p} not found: build it with `python -m paper_2407_04991_amd.build` (there is no CPU fallback)")
+    lib = C.CDLL(p)
+    lib.ernie_init_weights.restype = C.c_int
+    lib.ernie_init_weights.argtypes = [C.POINTER(ErnieConfig), C.POINTER(ErnieWeights), C.c_void_p, C.c_size_t,
+                                       C.POINTER(C.c_size_t), C.c_void_p, C.POINTER(C.c_void_p)]
+    lib.ernie_prefill.restype = C.c_int
+    lib.ernie_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_int32),
+                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.ernie_decode_step.restype = C.c_int
+    lib.ernie_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.ernie_free.restype = None
+    lib.ernie_free.argtypes = [C.c_void_p]
+    lib.ernie_debug_buffer.restype = C.c_int
+    lib.ernie_debug_buffer.argtypes = [C.c_void_p, C.c_char_p, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]
+    lib.ernie_error_string.restype = C.c_char_p
+    lib.ernie_error_string.argtypes = [C.c_int]
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def error_string(code: int) -> str:
+    return load_library().ernie_error_string(int(code)).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream or None
+
+
+# ---- thin wrappers with the C names -----------------------------------------
+
+def ernie_init_weights(cfg: ErnieConfig, weights: Optional[ErnieWeights], arena: Optional[torch.Tensor],
+                       stream=None):
+    """Returns (rc, arena_needed, handle)."""
+    lib = load_library()
+    need = C.c_size_t(0)
+    out = C.c_void_p(None)
+    rc = lib.ernie_init_weights(C.byref(cfg), C.byref(weights) if weights is not None else None,
+                                _ptr(arena), arena.numel() if arena is not None else 0, C.byref(need),
+                                _stream_ptr(stream) if arena is not None else None, C.byref(out))
+    return rc, need.value, out.value
+
+
+def ernie_prefill(handle, B: int, Lmax: int, ids_dev: torch.Tensor, prompt_lens_host: np.ndarray,
+                  logits_out: Optional[torch.Tensor], hidden_out: Optional[torch.Tensor], tok_out: torch.Tensor,
+                  stream=None) -> int:
+    lens = np.ascontiguousarray(prompt_lens_host, dtype=np.int32)
+    return load_library().ernie_prefill(handle, B, Lmax, _ptr(ids_dev), lens.ctypes.data_as(C.POINTER(C.c_int32)),
+                                        _ptr(logits_out), _ptr(hidden_out), _ptr(tok_out), _stream_ptr(stream))
+
+
+def ernie_decode_step(handle, tok_in: Optional[torch.Tensor], logits_out: Optional[torch.Tensor],
+                      hidden_out: Optional[torch.Tensor], tok_out: torch.Tensor, stream=None) -> int:
+    return load_library().ernie_decode_step(handle, _ptr(tok_in), _ptr(logits_out), _ptr(hidden_out),
+                                            _ptr(tok_out), _stream_ptr(stream))
+
+
+def ernie_free(handle) -> None:
+    load_library().ernie_free(handle)
+
+
+# ---- convenience object ------------------------------------------------------
+
+_LAYER_KEYS = ("wqkv", "bqkv", "wo", "bo", "ln1_g", "ln1_b", "w1", "b1", "w2", "b2", "ln2_g", "ln2_b")
+
+
+class ErnieEngine:
+    """Owns the arena tensor and the handle; forwards to the C entry points.
+
+    `weights` is a dict of numpy/torch fp16 arrays laid out as the synthetic
+    generator produces them, with the token table ALREADY trimmed to the kept
+    rows under key "tok_emb_kept".
+    """
+
+    def __init__(self, *, n_layers, d_model, n_heads, d_ffn, vocab_full, vocab_kept, max_pos, max_batch, max_seq,
+                 ln_eps, weights: dict, kept_ids, device="cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("ErnieEngine needs a GPU: the HIP library is the only implementation")
+        self.device = torch.device(device)
+        self.cfg = ErnieConfig(n_layers, d_model, n_heads, d_ffn, vocab_full, vocab_kept, max_pos, max_batch,
+                               max_seq, ln_eps)
+        self.handle = None
+        rc, need, _ = ernie_init_weights(self.cfg, None, None)
+        if rc != ERNIE_OK:
+            raise ErnieError(rc, "ernie_init_weights(size query)")
+        self.arena_bytes = need
+        self.arena = torch.empty(need, dtype=torch.uint8, device=self.device)
+        assert self.arena.data_ptr() % 256 == 0
+
+        def dev(a, dtype=torch.float16):
+            t = torch.as_tensor(np.ascontiguousarray(a)) if not isinstance(a, torch.Tensor) else a
+            return t.to(device=self.device, dtype=dtype).contiguous()
+
+        keep = []       # device originals stay alive until the repack has run
+        w = ErnieWeights()
+        for name, key, dt in (("tok_emb_kept", "tok_emb_kept", torch.float16), ("pos_emb", "pos_emb", torch.float16),
+                              ("emb_ln_g", "emb_ln_g", torch.float16), ("emb_ln_b", "emb_ln_b", torch.float16)):
+            t = dev(weights[key], dt); keep.append(t); setattr(w, name, t.data_ptr())
+        t = dev(kept_ids, torch.int32); keep.append(t); w.kept_ids = t.data_ptr()
+        arrays = {}
+        for k in _LAYER_KEYS:
+            arr = (C.c_void_p * n_layers)()
+            for l in range(n_layers):
+                t = dev(weights["layers"][l][k]); keep.append(t); arr[l] = t.data_ptr()
+            arrays[k] = arr
+            setattr(w, k, C.cast(arr, _PP))
+        rc, _, handle = ernie_init_weights(self.cfg, w, self.arena)
+        if rc != ERNIE_OK:
+            raise ErnieError(rc, "ernie_init_weights")
+        torch.cuda.synchronize(self.device)
+        del keep
+        self.handle = handle
+        self.B = 0
+
+    # outputs are allocated by the caller-side helper, never by the library
+    def prefill(self, ids: torch.Tensor, lens, *, logits=False, hidden=False, stream=None):
+        B, Lmax = ids.shape
+        ids = ids.to(device=self.device, dtype=torch.int32).contiguous()
+        lo = torch.empty(B, self.cfg.vocab_kept, dtype=torch.float32, device=self.device) if logits else None
+        ho = torch.empty(B, self.cfg.d_model, dtype=torch.float32, device=self.device) if hidden else None
+        tok = torch.empty(B, dtype=torch.int32, device=self.device)
+        rc = ernie_prefill(self.handle, B, Lmax, ids, np.asarray(lens, dtype=np.int32), lo, ho, tok, stream)
+        if rc != ERNIE_OK:
+            raise ErnieError(rc, "ernie_prefill")
+        self.B = B
+        return tok, lo, ho
+
+    def decode_step(self, tok_in: Optional[torch.Tensor] = None, *, logits=False, hidden=False, stream=None,
+                    out=None):
+        B = self.B
+        if tok_in is not None:
+            tok_in = tok_in.to(device=self.device, dtype=torch.int32).contiguous()
+        if out is None:
+            lo = torch.empty(B, self.cfg.vocab_kept, dtype=torch.float32, device=self.device) if logits else None
+            ho = torch.empty(B, self.cfg.d_model, dtype=torch.float32, device=self.device) if hidden else None
+            tok = torch.empty(B, dtype=torch.int32, device=self.device)
+        else:
+            tok, lo, ho = out
+        rc = ernie_decode_step(self.handle, tok_in, lo, ho, tok, stream)
+        if rc != ERNIE_OK:
+            raise ErnieError(rc, "ernie_decode_step")
+        return tok, lo, ho
+
+    def debug_buffer(self, name: str):
+        ptr = C.c_void_p(None); n = C.c_size_t(0)
+        rc = load_library().ernie_debug_buffer(self.handle, name.encode(), C.byref(ptr), C.byref(n))
+        if rc != ERNIE_OK:
+            raise ErnieError(rc, "ernie_debug_buffer")
+        return ptr.value, n.value
+
+    def close(self):
+        if self.handle is not None:
+            ernie_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def engine_from_workload(wl, *, max_batch=None, max_seq=None, device="cuda:0") -> ErnieEngine:
+    """Engine for a synthetic workload object (shape, weights, kept_ids)."""
+    sh = wl.shape
+    weights = dict(wl.weights)
+    weights["tok_emb_kept"] = np.ascontiguousarray(wl.weights["tok_emb"][wl.kept_ids])
+    return ErnieEngine(n_layers=sh.n_layers, d_model=sh.d_model, n_heads=sh.n_heads, d_ffn=sh.d_ffn,
+                       vocab_full=sh.vocab_full, vocab_kept=sh.vocab_kept, max_pos=sh.max_pos,
+                       max_batch=max_batch or sh.batch, max_seq=max_seq or (sh.prompt_len + sh.n_gen),
+                       ln_eps=sh.ln_eps, weights=weights, kept_ids=wl.kept_ids, device=device)

@@ -1,0 +1,268 @@
+// Attention kernels over the head-major key/value cache
+// [Bmax][H][S][64] fp16 (each (sequence, head) stream is contiguous).
+//
+//  - attn_prefill_kernel: bidirectional attention of every prompt query over
+//    the valid prompt keys of its own sequence (padding never stored nor seen),
+//    flash-style on MFMA with fp32 online softmax.
+//  - attn_decode_kernel: one query per (sequence, head) over all cached keys,
+//    a pure streaming read of K and V with wave-shuffle softmax reductions.
+#pragma once
+
+#include "common.h"
+
+namespace ernie {
+
+// ---------------------------------------------------------------- prefill
+
+constexpr int kAttnQTile = 128;            // queries per workgroup (32 per wave)
+constexpr int kAttnKBlock = 64;            // keys staged per iteration
+constexpr int kAttnVtPitch = kAttnKBlock + 4;   // halves; 136-byte pitch spreads 8-byte reads over all banks
+
+// Scores are produced transposed (S^T = K Q^T) so that every lane owns ONE
+// query column: softmax statistics are per-lane plus one exchange with lane^32.
+// The probabilities, still in registers, are directly the B operand of
+// O^T = V^T P^T provided V^T is read with the matching key permutation
+// (slot (half, j) of k-step c  <->  key 16c + 8(j/4) + 4*half + j%4).
+__global__ __launch_bounds__(256) void attn_prefill_kernel(const half_t* __restrict__ Q,      // [H][T][64]
+                                                           const half_t* __restrict__ Kc,     // layer K cache
+                                                           const half_t* __restrict__ Vc,     // layer V cache
+                                                           const int* __restrict__ cu, int T, int H, int S, int d,
+                                                           half_t* __restrict__ O) {           // [T, d]
+  __shared__ __align__(16) half_t sVt[64 * kAttnVtPitch];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int t0 = cu[b];
+  const int L = cu[b + 1] - t0;
+  const int qbase = blockIdx.x * kAttnQTile;
+  if (qbase >= L) return;                       // uniform for the whole workgroup
+
+  const int hh = lane >> 5;
+  const int qi = qbase + wave * 32 + (lane & 31);    // this lane's query
+  const bool q_ok = qi < L;
+
+  // Q fragments (B operand, k = head-dim index), pre-scaled by 1/sqrt(64) (exact in fp16)
+  half8 qf[4];
+  {
+    const half_t* qp = Q + ((size_t)h * T + t0 + (q_ok ? qi : 0)) * 64 + 8 * hh;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (q_ok) v = *reinterpret_cast<const half8*>(qp + 16 * c);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = v[j] * (half_t)0.125f;
+      qf[c] = v;
+    }
+  }
+
+  const half_t* Kb = Kc + ((size_t)b * H + h) * S * 64;
+  const half_t* Vb = Vc + ((size_t)b * H + h) * S * 64;
+
+  floatx16 o[2];
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[m][v] = 0.f;
+  float row_max = -INFINITY, row_sum = 0.f;
+
+  for (int kb0 = 0; kb0 < L; kb0 += kAttnKBlock) {
+    // stage V^T of this key block: thread handles key = id / 8, 8 head-dim values at (id % 8) * 8
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int id = tid + 256 * i;
+      const int key = id >> 3, ec = id & 7;
+      half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (kb0 + key < L) v = *reinterpret_cast<const half8*>(Vb + (size_t)(kb0 + key) * 64 + ec * 8);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sVt[(ec * 8 + j) * kAttnVtPitch + key] = v[j];
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const int key0 = kb0 + kk * 32;
+      if (key0 < L) {                            // uniform: skip fully masked sub-blocks
+        // S^T[key][query] for 32 keys x 32 queries
+        floatx16 s;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = 0.f;
+        const int krow = key0 + (lane & 31);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          half8 kf = {0, 0, 0, 0, 0, 0, 0, 0};
+          if (krow < L) kf = *reinterpret_cast<const half8*>(Kb + (size_t)krow * 64 + 16 * c + 8 * hh);
+          s = mfma32(kf, qf[c], s);
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = key0 + mfma32_row(v, lane);
+          if (key >= L) s[v] = -INFINITY;
+          mx = fmaxf(mx, s[v]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(row_max, mx);            // finite: key 0 is always valid
+        const float alpha = __expf(row_max - m_new);        // exp(-inf) = 0 on the first block
+        float ps = 0.f;
+        half8 pf[2];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float p = __expf(s[v] - m_new);
+          ps += p;
+          pf[v >> 3][v & 7] = (half_t)p;
+        }
+        ps += __shfl_xor(ps, 32, 64);
+        row_sum = row_sum * alpha + ps;
+        row_max = m_new;
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[m][v] *= alpha;
+        // O^T[e][query] += V^T[e][keys] * P^T[keys][query]
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+          const half_t* vt = sVt + (32 * m + (lane & 31)) * kAttnVtPitch + kk * 32 + 4 * hh;
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+            const half4 lo = *reinterpret_cast<const half4*>(vt + 16 * c);
+            const half4 hi = *reinterpret_cast<const half4*>(vt + 16 * c + 8);
+            half8 vf;
+            vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
+            vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
+            o[m] = mfma32(vf, pf[c], o[m]);
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  if (q_ok) {
+    const float inv = 1.0f / row_sum;
+    half_t* op = O + (size_t)(t0 + qi) * d + h * 64;
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        half4 w;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = (half_t)(o[m][4 * g + j] * inv);
+        *reinterpret_cast<half4*>(op + 32 * m + 8 * g + 4 * hh) = w;
+      }
+  }
+}
+
+// ---------------------------------------------------------------- decode
+
+// One workgroup (4 waves) per (head, sequence).  Lane l of a wave reads 16
+// bytes (8 head-dim values, chunk l % 8) of key row (l / 8) of an 8-row group,
+// so one wave load instruction covers 1 KiB of contiguous cache.  Wave w takes
+// the 8-row groups g with g % 4 == w.  Every 8-lane team keeps an online
+// softmax (max, sum, 8 output values) over its own rows; teams are merged by
+// shuffles, waves through LDS.
+struct SoftmaxPart {
+  float m, l, acc[8];
+};
+
+__device__ __forceinline__ void softmax_merge(SoftmaxPart& a, float om, float ol, const float* oacc) {
+  const float mn = fmaxf(a.m, om);
+  const float sa = (a.m == -INFINITY) ? 0.f : __expf(a.m - mn);
+  const float sb = (om == -INFINITY) ? 0.f : __expf(om - mn);
+  a.l = a.l * sa + ol * sb;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) a.acc[j] = a.acc[j] * sa + oacc[j] * sb;
+  a.m = mn;
+}
+
+__global__ __launch_bounds__(256) void attn_decode_kernel(const half_t* __restrict__ Q,    // [B, d]
+                                                          const half_t* __restrict__ Kc, const half_t* __restrict__ Vc,
+                                                          const int* __restrict__ cache_len, int H, int S, int d,
+                                                          half_t* __restrict__ O) {          // [B, d]
+  __shared__ float sm[4][8][10];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int c = min(cache_len[b] + 1, S);       // keys visible: everything cached plus the token just appended
+  const int ec = lane & 7, team = lane >> 3;
+
+  float q[8];
+  {
+    const half8 qv = *reinterpret_cast<const half8*>(Q + (size_t)b * d + h * 64 + ec * 8);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) q[j] = (float)qv[j] * 0.125f;
+  }
+  const half_t* Kb = Kc + ((size_t)b * H + h) * S * 64 + ec * 8;
+  const half_t* Vb = Vc + ((size_t)b * H + h) * S * 64 + ec * 8;
+
+  SoftmaxPart st;
+  st.m = -INFINITY; st.l = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) st.acc[j] = 0.f;
+
+  constexpr int U = 4;                           // row groups in flight per wave
+  for (int g0 = wave * U; g0 * 8 < c; g0 += 4 * U) {
+    half8 kf[U], vf[U];
+    int key[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      key[u] = (g0 + u) * 8 + team;
+      const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+      kf[u] = (key[u] < c) ? *reinterpret_cast<const half8*>(Kb + (size_t)key[u] * 64) : z;
+      vf[u] = (key[u] < c) ? *reinterpret_cast<const half8*>(Vb + (size_t)key[u] * 64) : z;
+    }
+    float s[U];
+    float mx = st.m;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float p = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) p += q[j] * (float)kf[u][j];
+      p += __shfl_xor(p, 1, 64);
+      p += __shfl_xor(p, 2, 64);
+      p += __shfl_xor(p, 4, 64);
+      s[u] = (key[u] < c) ? p : -INFINITY;
+      mx = fmaxf(mx, s[u]);
+    }
+    if (mx != -INFINITY) {
+      const float alpha = (st.m == -INFINITY) ? 0.f : __expf(st.m - mx);
+      st.l *= alpha;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float p = __expf(s[u] - mx);      // exp(-inf) = 0 for rows past the end
+        st.l += p;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) st.acc[j] += p * (float)vf[u][j];
+      }
+      st.m = mx;
+    }
+  }
+
+  // merge the 8 teams of the wave (lanes with equal lane % 8 hold the same head-dim chunk)
+#pragma unroll
+  for (int off = 8; off < 64; off <<= 1) {
+    const float om = __shfl_xor(st.m, off, 64);
+    const float ol = __shfl_xor(st.l, off, 64);
+    float oa[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) oa[j] = __shfl_xor(st.acc[j], off, 64);
+    softmax_merge(st, om, ol, oa);
+  }
+  if (team == 0) {
+    sm[wave][ec][0] = st.m; sm[wave][ec][1] = st.l;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sm[wave][ec][2 + j] = st.acc[j];
+  }
+  __syncthreads();
+  if (wave == 0 && team == 0) {
+#pragma unroll
+    for (int w = 1; w < 4; ++w) softmax_merge(st, sm[w][ec][0], sm[w][ec][1], &sm[w][ec][2]);
+    const float inv = 1.0f / st.l;
+    half8 o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = (half_t)(st.acc[j] * inv);
+    *reinterpret_cast<half8*>(O + (size_t)b * d + h * 64 + ec * 8) = o;
+  }
+}
+
+}  // namespace ernie

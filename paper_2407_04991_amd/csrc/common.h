@@ -1,0 +1,64 @@
+// Shared device helpers for the gfx950 ERNIE kernels: vector types, MFMA
+// fragment conventions and wave64 reductions.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+namespace ernie {
+
+typedef _Float16 half_t;
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+constexpr int kHeadDim = 64;
+
+// v_mfma_f32_32x32x16_f16 operand convention used everywhere in this library
+// (one wave64 computes D[32x32] += A[32x16] * B[16x32]):
+//   A fragment: lane l holds A[l % 32][8 * (l / 32) + 0..7]
+//   B fragment: lane l holds B[8 * (l / 32) + 0..7][l % 32]
+//   D fragment: lane l, register v (0..15) holds D[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32]
+// Both inputs are therefore "8 consecutive k per lane, lane % 32 selects the
+// row / column", which is what a K-contiguous (row-major [rows, K]) operand
+// delivers with one 16-byte load per lane.
+__device__ __forceinline__ floatx16 mfma32(half8 a, half8 b, floatx16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ int mfma32_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
+
+// Packed weight layout ("fragment-major"): a [N, K] row-major matrix becomes
+// tiles of 32 rows x 16 k, each stored as the 64 lanes' 8-half fragments in
+// lane order (1 KiB, contiguous), tiles ordered [n_tile][k_tile].  A wave reads
+// one operand fragment with a single fully coalesced 16-byte-per-lane load.
+__host__ __device__ __forceinline__ size_t packed_frag_offset(int n_tile, int k_tile, int k_tiles) {
+  return ((size_t)n_tile * k_tiles + k_tile) * 512;   // in halves
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// (value, index) maximum with the lowest index winning exact ties.
+__device__ __forceinline__ void argmax_merge(float& v, int& i, float ov, int oi) {
+  if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
+}
+
+__device__ __forceinline__ float gelu_erf(float a) {
+  return a * 0.5f * (1.0f + erff(a * 0.70710678118654752440f));
+}
+
+}  // namespace ernie

@@ -1,0 +1,395 @@
+// C ABI of the ERNIE generation hot path (see include/ernie.h): host-side
+// argument checks, arena carving and kernel orchestration.  All device work is
+// enqueued on the caller's stream; nothing here allocates device memory.
+
+#include "../../include/ernie.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "attention.h"
+#include "common.h"
+#include "gemm_prefill.h"
+#include "gemm_skinny.h"
+#include "rowops.h"
+
+using namespace ernie;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kStagingSlots = 8;
+
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct LayerPtrs {
+  half_t *wqkv, *wo, *w1, *w2;                       // fragment-major
+  float *bqkv, *bo, *b1, *b2, *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+};
+
+// Offsets of every sub-buffer inside the arena (bytes).  Computed identically
+// for sizing (arena == NULL) and for carving.
+struct ArenaPlan {
+  size_t tok_rm, tok_p, pos, emb_g, emb_b, kept;
+  struct L { size_t wqkv, wo, w1, w2, bqkv, bo, b1, b2, ln1_g, ln1_b, ln2_g, ln2_b; };
+  std::vector<L> layers;
+  size_t kv, X, X1, Y, Q, O, G, Yf, hlast, strip_val, strip_idx, cu, lens, tok_seq, tok_pos, tok_prev;
+  size_t total;
+  int vocab_tiles, strips;
+  size_t t_max;
+};
+
+ArenaPlan make_plan(const ErnieConfig& c) {
+  ArenaPlan p;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  const size_t d = c.d_model, f = c.d_ffn, V = c.vocab_kept, P = c.max_pos;
+  p.vocab_tiles = (int)((V + 31) / 32);
+  p.strips = p.vocab_tiles;
+  p.tok_rm = take(V * d * 2);
+  p.tok_p = take((size_t)p.vocab_tiles * 32 * d * 2);
+  p.pos = take(P * d * 2);
+  p.emb_g = take(d * 4);
+  p.emb_b = take(d * 4);
+  p.kept = take(V * 4);
+  p.layers.resize(c.n_layers);
+  for (auto& l : p.layers) {
+    l.wqkv = take(3 * d * d * 2); l.wo = take(d * d * 2); l.w1 = take(f * d * 2); l.w2 = take(d * f * 2);
+    l.bqkv = take(3 * d * 4); l.bo = take(d * 4); l.b1 = take(f * 4); l.b2 = take(d * 4);
+    l.ln1_g = take(d * 4); l.ln1_b = take(d * 4); l.ln2_g = take(d * 4); l.ln2_b = take(d * 4);
+  }
+  const size_t Bm = c.max_batch, S = c.max_seq;
+  p.kv = take((size_t)c.n_layers * 2 * Bm * S * d * 2);
+  const size_t lmax = (size_t)(c.max_seq < c.max_pos ? c.max_seq : c.max_pos);
+  p.t_max = Bm * lmax;
+  p.X = take(p.t_max * d * 2); p.X1 = take(p.t_max * d * 2); p.Y = take(p.t_max * d * 2);
+  p.Q = take(p.t_max * d * 2); p.O = take(p.t_max * d * 2); p.G = take(p.t_max * f * 2);
+  p.Yf = take(Bm * d * 4);
+  p.hlast = take(Bm * d * 2);
+  p.strip_val = take(Bm * p.strips * 4); p.strip_idx = take(Bm * p.strips * 4);
+  p.cu = take((Bm + 1) * 4); p.lens = take(Bm * 4);
+  p.tok_seq = take(p.t_max * 4); p.tok_pos = take(p.t_max * 4); p.tok_prev = take(Bm * 4);
+  p.total = off;
+  return p;
+}
+
+int check_config(const ErnieConfig* c) {
+  if (!c) return ERNIE_EINVAL;
+  if (c->n_layers < 1 || c->d_model < 64 || c->n_heads < 1 || c->d_ffn < 64) return ERNIE_EINVAL;
+  if (c->d_model != c->n_heads * kHeadDim) return ERNIE_EINVAL;          // head_dim must be 64
+  if (c->d_model > 64 * 8 * kMaxRowChunks) return ERNIE_EINVAL;           // one wave normalises a row
+  if (c->d_ffn % 64 != 0) return ERNIE_EINVAL;
+  if (c->vocab_kept < 1 || c->vocab_full < c->vocab_kept || c->max_pos < 1) return ERNIE_EINVAL;
+  if (c->max_batch < 1 || c->max_batch > 256 || c->max_seq < 1) return ERNIE_EINVAL;
+  if (!(c->ln_eps > 0.f)) return ERNIE_EINVAL;
+  return ERNIE_OK;
+}
+
+}  // namespace
+
+struct ErnieHandle {
+  ErnieConfig cfg;
+  ArenaPlan plan;
+  unsigned char* arena;
+  half_t *tok_rm, *tok_p, *pos;
+  float *emb_g, *emb_b;
+  std::vector<LayerPtrs> layers;
+  half_t *kv, *X, *X1, *Y, *Q, *O, *G, *hlast;
+  float *Yf, *strip_val;
+  int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
+  int* staging;          // pinned host: kStagingSlots x (max_batch + 1) ints
+  int staging_next;
+  // state of the batch in flight
+  bool prefilled;
+  int B, max_len, steps;
+};
+
+namespace {
+
+#define HIP_OK(expr) do { if ((expr) != hipSuccess) return ERNIE_EHIP; } while (0)
+
+int launch_status() { return hipGetLastError() == hipSuccess ? ERNIE_OK : ERNIE_EHIP; }
+
+half_t* kcache(const ErnieHandle* h, int layer) {
+  const size_t per = (size_t)h->cfg.max_batch * h->cfg.max_seq * h->cfg.d_model;
+  return h->kv + ((size_t)layer * 2 + 0) * per;
+}
+half_t* vcache(const ErnieHandle* h, int layer) {
+  const size_t per = (size_t)h->cfg.max_batch * h->cfg.max_seq * h->cfg.d_model;
+  return h->kv + ((size_t)layer * 2 + 1) * per;
+}
+
+template <class Epi>
+void launch_gemm_prefill(const half_t* A, const half_t* Wp, const float* bias, int M, int N, int K, Epi epi,
+                         hipStream_t s) {
+  const int tiles_m = (M + kGemmBM - 1) / kGemmBM, tiles_n = (N + kGemmBN - 1) / kGemmBN;
+  hipLaunchKernelGGL(gemm_prefill_kernel<Epi>, dim3(tiles_m * tiles_n), dim3(256), kGemmLdsBytes, s, A, Wp, bias, M,
+                     N, K, (N + 31) / 32, tiles_n, epi);
+}
+
+template <int MT, int NW, class Epi>
+void launch_skinny_t(const half_t* X, const half_t* Wp, const float* bias, int B, int N, int K, Epi epi,
+                     hipStream_t s) {
+  const size_t lds = (size_t)NW * MT * 16 * 64 * 4;
+  hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW, Epi>), dim3((N + 31) / 32), dim3(NW * 64), lds, s, X, Wp, bias, B, N,
+                     K, epi);
+}
+
+template <class Epi>
+void launch_skinny(const half_t* X, const half_t* Wp, const float* bias, int B, int N, int K, Epi epi, hipStream_t s) {
+  if (B <= 32) launch_skinny_t<1, 8>(X, Wp, bias, B, N, K, epi, s);
+  else if (B <= 64) launch_skinny_t<2, 8>(X, Wp, bias, B, N, K, epi, s);
+  else if (B <= 128) launch_skinny_t<4, 4>(X, Wp, bias, B, N, K, epi, s);
+  else launch_skinny_t<8, 4>(X, Wp, bias, B, N, K, epi, s);
+}
+
+template <int MT, int NW>
+void launch_logits_t(const ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s) {
+  const size_t lds = (size_t)NW * MT * 16 * 64 * 4;
+  hipLaunchKernelGGL((logits_argmax_kernel<MT, NW>), dim3(h->plan.strips), dim3(NW * 64), lds, s, X, h->tok_p, B,
+                     h->cfg.vocab_kept, h->cfg.d_model, logits_out, h->strip_val, h->strip_idx, h->plan.strips);
+}
+
+void launch_logits(const ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s) {
+  if (B <= 32) launch_logits_t<1, 4>(h, X, B, logits_out, s);
+  else if (B <= 64) launch_logits_t<2, 4>(h, X, B, logits_out, s);
+  else if (B <= 128) launch_logits_t<4, 4>(h, X, B, logits_out, s);
+  else launch_logits_t<8, 4>(h, X, B, logits_out, s);
+}
+
+// Kernels whose dynamic LDS exceeds the 64 KiB default need an explicit opt-in.
+template <class F>
+int allow_lds(F* fn, size_t bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)bytes) == hipSuccess ? ERNIE_OK : ERNIE_EHIP;
+}
+
+int configure_kernels() {
+  int rc = ERNIE_OK;
+  rc |= allow_lds(gemm_prefill_kernel<EpiQKV>, kGemmLdsBytes);
+  rc |= allow_lds(gemm_prefill_kernel<EpiResidual>, kGemmLdsBytes);
+  rc |= allow_lds(gemm_prefill_kernel<EpiGelu>, kGemmLdsBytes);
+  const size_t big = (size_t)4 * 8 * 16 * 64 * 4;   // MT = 8, NW = 4
+  rc |= allow_lds(gemm_skinny_kernel<8, 4, SkinnyQKV>, big);
+  rc |= allow_lds(gemm_skinny_kernel<8, 4, SkinnyResidual>, big);
+  rc |= allow_lds(gemm_skinny_kernel<8, 4, SkinnyGelu>, big);
+  rc |= allow_lds(logits_argmax_kernel<8, 4>, big);
+  return rc ? ERNIE_EHIP : ERNIE_OK;
+}
+
+void pack_into(const void* src, half_t* dst, int N, int K, hipStream_t s) {
+  const int n_tiles = (N + 31) / 32;
+  const size_t total = (size_t)n_tiles * (K / 16) * 64;
+  const int blocks = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+  hipLaunchKernelGGL(pack_weight_kernel, dim3(blocks), dim3(256), 0, s, (const half_t*)src, dst, N, K, n_tiles);
+}
+
+void cvt_into(const void* src, float* dst, int n, hipStream_t s) {
+  hipLaunchKernelGGL(cvt_f16_f32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, (const half_t*)src, dst, n);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ernie_error_string(int code) {
+  switch (code) {
+    case ERNIE_OK: return "ok";
+    case ERNIE_EINVAL: return "invalid argument";
+    case ERNIE_ECAPACITY: return "capacity exceeded (batch, sequence or position)";
+    case ERNIE_EARENA: return "arena too small";
+    case ERNIE_ESEQUENCE: return "decode step before prefill";
+    case ERNIE_EHIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* w, void* arena_dev, size_t arena_bytes,
+                       size_t* arena_needed, void* stream, ErnieHandle** out) {
+  const int rc = check_config(cfg);
+  if (rc != ERNIE_OK) return rc;
+  ArenaPlan plan = make_plan(*cfg);
+  if (arena_needed) *arena_needed = plan.total;
+  if (!arena_dev) return arena_needed ? ERNIE_OK : ERNIE_EINVAL;
+  if (!w || !out) return ERNIE_EINVAL;
+  if ((uintptr_t)arena_dev % kAlign != 0) return ERNIE_EINVAL;
+  if (arena_bytes < plan.total) return ERNIE_EARENA;
+  if (!w->tok_emb_kept || !w->kept_ids || !w->pos_emb || !w->emb_ln_g || !w->emb_ln_b || !w->wqkv || !w->bqkv ||
+      !w->wo || !w->bo || !w->ln1_g || !w->ln1_b || !w->w1 || !w->b1 || !w->w2 || !w->b2 || !w->ln2_g || !w->ln2_b)
+    return ERNIE_EINVAL;
+  for (int l = 0; l < cfg->n_layers; ++l)
+    if (!w->wqkv[l] || !w->bqkv[l] || !w->wo[l] || !w->bo[l] || !w->ln1_g[l] || !w->ln1_b[l] || !w->w1[l] ||
+        !w->b1[l] || !w->w2[l] || !w->b2[l] || !w->ln2_g[l] || !w->ln2_b[l])
+      return ERNIE_EINVAL;
+
+  ErnieHandle* h = new (std::nothrow) ErnieHandle();
+  if (!h) return ERNIE_EHIP;
+  h->cfg = *cfg;
+  h->plan = plan;
+  unsigned char* a = static_cast<unsigned char*>(arena_dev);
+  h->arena = a;
+  auto H16 = [&](size_t o) { return reinterpret_cast<half_t*>(a + o); };
+  auto F32 = [&](size_t o) { return reinterpret_cast<float*>(a + o); };
+  auto I32 = [&](size_t o) { return reinterpret_cast<int*>(a + o); };
+  h->tok_rm = H16(plan.tok_rm); h->tok_p = H16(plan.tok_p); h->pos = H16(plan.pos);
+  h->emb_g = F32(plan.emb_g); h->emb_b = F32(plan.emb_b);
+  h->kv = H16(plan.kv); h->X = H16(plan.X); h->X1 = H16(plan.X1); h->Y = H16(plan.Y); h->Q = H16(plan.Q);
+  h->O = H16(plan.O); h->G = H16(plan.G); h->hlast = H16(plan.hlast);
+  h->Yf = F32(plan.Yf); h->strip_val = F32(plan.strip_val);
+  h->strip_idx = I32(plan.strip_idx); h->cu = I32(plan.cu); h->lens = I32(plan.lens);
+  h->tok_seq = I32(plan.tok_seq); h->tok_pos = I32(plan.tok_pos); h->tok_prev = I32(plan.tok_prev);
+  h->prefilled = false; h->B = 0; h->max_len = 0; h->steps = 0;
+  h->staging = nullptr; h->staging_next = 0;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (configure_kernels() != ERNIE_OK ||
+      hipHostMalloc(reinterpret_cast<void**>(&h->staging), sizeof(int) * kStagingSlots * (cfg->max_batch + 1),
+                    hipHostMallocDefault) != hipSuccess) {
+    delete h;
+    return ERNIE_EHIP;
+  }
+
+  const int d = cfg->d_model, f = cfg->d_ffn, V = cfg->vocab_kept;
+  bool copies_ok = true;
+  copies_ok &= hipMemcpyAsync(h->tok_rm, w->tok_emb_kept, (size_t)V * d * 2, hipMemcpyDeviceToDevice, s) == hipSuccess;
+  copies_ok &= hipMemcpyAsync(h->pos, w->pos_emb, (size_t)cfg->max_pos * d * 2, hipMemcpyDeviceToDevice, s) == hipSuccess;
+  copies_ok &= hipMemcpyAsync(a + plan.kept, w->kept_ids, (size_t)V * 4, hipMemcpyDeviceToDevice, s) == hipSuccess;
+  pack_into(w->tok_emb_kept, h->tok_p, V, d, s);
+  cvt_into(w->emb_ln_g, h->emb_g, d, s);
+  cvt_into(w->emb_ln_b, h->emb_b, d, s);
+  h->layers.resize(cfg->n_layers);
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const ArenaPlan::L& o = plan.layers[l];
+    LayerPtrs& L = h->layers[l];
+    L.wqkv = H16(o.wqkv); L.wo = H16(o.wo); L.w1 = H16(o.w1); L.w2 = H16(o.w2);
+    L.bqkv = F32(o.bqkv); L.bo = F32(o.bo); L.b1 = F32(o.b1); L.b2 = F32(o.b2);
+    L.ln1_g = F32(o.ln1_g); L.ln1_b = F32(o.ln1_b); L.ln2_g = F32(o.ln2_g); L.ln2_b = F32(o.ln2_b);
+    pack_into(w->wqkv[l], L.wqkv, 3 * d, d, s);
+    pack_into(w->wo[l], L.wo, d, d, s);
+    pack_into(w->w1[l], L.w1, f, d, s);
+    pack_into(w->w2[l], L.w2, d, f, s);
+    cvt_into(w->bqkv[l], L.bqkv, 3 * d, s); cvt_into(w->bo[l], L.bo, d, s);
+    cvt_into(w->b1[l], L.b1, f, s); cvt_into(w->b2[l], L.b2, d, s);
+    cvt_into(w->ln1_g[l], L.ln1_g, d, s); cvt_into(w->ln1_b[l], L.ln1_b, d, s);
+    cvt_into(w->ln2_g[l], L.ln2_g, d, s); cvt_into(w->ln2_b[l], L.ln2_b, d, s);
+  }
+  if (launch_status() != ERNIE_OK || !copies_ok) {
+    (void)hipHostFree(h->staging);
+    delete h;
+    return ERNIE_EHIP;
+  }
+  *out = h;
+  return ERNIE_OK;
+}
+
+int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_dev, const int32_t* prompt_lens_host,
+                  float* logits_out_dev, float* hidden_out_dev, int32_t* tok_out_dev, void* stream) {
+  if (!h || !ids_dev || !prompt_lens_host || !tok_out_dev) return ERNIE_EINVAL;
+  if (B < 1 || Lmax < 1) return ERNIE_EINVAL;
+  const ErnieConfig& c = h->cfg;
+  if (B > c.max_batch || Lmax > c.max_seq || Lmax > c.max_pos) return ERNIE_ECAPACITY;
+  int max_len = 0;
+  for (int b = 0; b < B; ++b) {
+    const int L = prompt_lens_host[b];
+    if (L < 1 || L > Lmax) return ERNIE_EINVAL;
+    if (L > max_len) max_len = L;
+  }
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int* stage = h->staging + (size_t)h->staging_next * (c.max_batch + 1);
+  h->staging_next = (h->staging_next + 1) % kStagingSlots;
+  stage[0] = 0;
+  for (int b = 0; b < B; ++b) stage[b + 1] = stage[b] + prompt_lens_host[b];
+  const int T = stage[B];
+  HIP_OK(hipMemcpyAsync(h->cu, stage, sizeof(int) * (B + 1), hipMemcpyHostToDevice, s));
+
+  const int d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
+  hipLaunchKernelGGL(token_map_kernel, dim3((T + 255) / 256), dim3(256), 0, s, h->cu, B, T, h->tok_seq, h->tok_pos,
+                     h->lens);
+  hipLaunchKernelGGL(embed_ln_prefill_kernel, dim3((T + 3) / 4), dim3(256), 0, s, ids_dev, Lmax, h->tok_seq,
+                     h->tok_pos, T, h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X);
+  const int q_tiles = (max_len + kAttnQTile - 1) / kAttnQTile;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerPtrs& L = h->layers[l];
+    EpiQKV eq{h->Q, kcache(h, l), vcache(h, l), h->tok_seq, h->tok_pos, d, H, S, T};
+    launch_gemm_prefill(h->X, L.wqkv, L.bqkv, T, 3 * d, d, eq, s);
+    hipLaunchKernelGGL(attn_prefill_kernel, dim3(q_tiles, H, B), dim3(256), 0, s, h->Q, kcache(h, l), vcache(h, l),
+                       h->cu, T, H, S, d, h->O);
+    launch_gemm_prefill(h->O, L.wo, L.bo, T, d, d, EpiResidual{h->X, h->Y, d}, s);
+    hipLaunchKernelGGL(ln_rows_f16_kernel, dim3((T + 3) / 4), dim3(256), 0, s, h->Y, T, d, L.ln1_g, L.ln1_b, c.ln_eps,
+                       h->X1);
+    launch_gemm_prefill(h->X1, L.w1, L.b1, T, f, d, EpiGelu{h->G, f}, s);
+    launch_gemm_prefill(h->G, L.w2, L.b2, T, d, f, EpiResidual{h->X1, h->Y, d}, s);
+    hipLaunchKernelGGL(ln_rows_f16_kernel, dim3((T + 3) / 4), dim3(256), 0, s, h->Y, T, d, L.ln2_g, L.ln2_b, c.ln_eps,
+                       h->X);
+  }
+  hipLaunchKernelGGL(gather_last_rows_kernel, dim3(B), dim3(256), 0, s, h->X, h->cu, B, d, h->hlast, hidden_out_dev);
+  launch_logits(h, h->hlast, B, logits_out_dev, s);
+  hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->plan.strips,
+                     tok_out_dev, h->tok_prev, h->lens, 0, S, c.vocab_kept);
+  h->prefilled = true; h->B = B; h->max_len = max_len; h->steps = 0;
+  return launch_status();
+}
+
+int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_out_dev, float* hidden_out_dev,
+                      int32_t* tok_out_dev, void* stream) {
+  if (!h || !tok_out_dev) return ERNIE_EINVAL;
+  if (!h->prefilled) return ERNIE_ESEQUENCE;
+  const ErnieConfig& c = h->cfg;
+  const int next_pos = h->max_len + h->steps;          // position / cache slot of the longest sequence's new token
+  if (next_pos + 1 > c.max_seq || next_pos >= c.max_pos) return ERNIE_ECAPACITY;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int B = h->B, d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
+  const int* tok = tok_in_dev ? tok_in_dev : h->tok_prev;
+  hipLaunchKernelGGL(embed_ln_decode_kernel, dim3((B + 3) / 4), dim3(256), 0, s, tok, h->lens, B, c.max_pos,
+                     h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerPtrs& L = h->layers[l];
+    launch_skinny(h->X, L.wqkv, L.bqkv, B, 3 * d, d, SkinnyQKV{h->Q, kcache(h, l), vcache(h, l), h->lens, d, H, S},
+                  s);
+    hipLaunchKernelGGL(attn_decode_kernel, dim3(H, B), dim3(256), 0, s, h->Q, kcache(h, l), vcache(h, l), h->lens, H,
+                       S, d, h->O);
+    launch_skinny(h->O, L.wo, L.bo, B, d, d, SkinnyResidual{h->X, h->Yf, d}, s);
+    hipLaunchKernelGGL(ln_rows_f32_kernel, dim3((B + 3) / 4), dim3(256), 0, s, h->Yf, B, d, L.ln1_g, L.ln1_b,
+                       c.ln_eps, h->X1);
+    launch_skinny(h->X1, L.w1, L.b1, B, f, d, SkinnyGelu{h->G, f}, s);
+    launch_skinny(h->G, L.w2, L.b2, B, d, f, SkinnyResidual{h->X1, h->Yf, d}, s);
+    hipLaunchKernelGGL(ln_rows_f32_kernel, dim3((B + 3) / 4), dim3(256), 0, s, h->Yf, B, d, L.ln2_g, L.ln2_b,
+                       c.ln_eps, h->X);
+  }
+  if (hidden_out_dev)
+    hipLaunchKernelGGL(hidden_to_f32_kernel, dim3((B * d + 255) / 256), dim3(256), 0, s, h->X, B * d, hidden_out_dev);
+  launch_logits(h, h->X, B, logits_out_dev, s);
+  hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->plan.strips,
+                     tok_out_dev, h->tok_prev, h->lens, 1, S, c.vocab_kept);
+  h->steps += 1;
+  return launch_status();
+}
+
+void ernie_free(ErnieHandle* h) {
+  if (!h) return;
+  if (h->staging) (void)hipHostFree(h->staging);
+  delete h;
+}
+
+int ernie_debug_buffer(ErnieHandle* h, const char* name, void** ptr_dev, size_t* bytes) {
+  if (!h || !name || !ptr_dev || !bytes) return ERNIE_EINVAL;
+  const ErnieConfig& c = h->cfg;
+  if (!strcmp(name, "x")) {
+    *ptr_dev = h->X; *bytes = h->plan.t_max * c.d_model * 2;
+  } else if (!strcmp(name, "kv")) {
+    *ptr_dev = h->kv; *bytes = (size_t)c.n_layers * 2 * c.max_batch * c.max_seq * c.d_model * 2;
+  } else if (!strcmp(name, "lens")) {
+    *ptr_dev = h->lens; *bytes = (size_t)c.max_batch * 4;
+  } else {
+    return ERNIE_EINVAL;
+  }
+  return ERNIE_OK;
+}
+
+}  // extern "C"

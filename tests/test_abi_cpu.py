@@ -1,0 +1,74 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+declared symbol, sizes the arena and rejects bad configurations before any device call."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2407_04991_amd as E
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ernie.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ernie_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = E.load_library()
+    names = declared_symbols()
+    assert set(names) == set(E.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def base_cfg(**kw):
+    v = dict(n_layers=12, d_model=768, n_heads=12, d_ffn=3072, vocab_full=18000, vocab_kept=18000, max_pos=512,
+             max_batch=32, max_seq=160, ln_eps=1e-5)
+    v.update(kw)
+    return E.ErnieConfig(*[v[k] for k in ("n_layers", "d_model", "n_heads", "d_ffn", "vocab_full", "vocab_kept",
+                                          "max_pos", "max_batch", "max_seq", "ln_eps")])
+
+
+def test_size_query_counts_cache_and_weights():
+    rc, need, handle = E.ernie_init_weights(base_cfg(), None, None)
+    assert rc == E.ERNIE_OK and handle is None
+    kv = 12 * 2 * 32 * 160 * 768 * 2
+    weights = 12 * (4 * 768 * 768 + 2 * 768 * 3072) * 2 + 2 * 18000 * 768 * 2
+    assert need >= kv + weights
+    rc2, need2, _ = E.ernie_init_weights(base_cfg(max_seq=320), None, None)
+    assert rc2 == E.ERNIE_OK and need2 - need >= kv          # cache doubles (activations grow too)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(n_heads=11),                  # head_dim != 64
+    dict(d_model=0), dict(n_layers=0), dict(d_ffn=100), dict(vocab_kept=0),
+    dict(vocab_kept=18001),            # more kept rows than the full table
+    dict(max_batch=0), dict(max_batch=257), dict(max_seq=0), dict(max_pos=0), dict(ln_eps=0.0),
+    dict(d_model=8192, n_heads=128),   # wider than one wave normalises
+])
+def test_bad_config_is_einval(kw):
+    rc, need, _ = E.ernie_init_weights(base_cfg(**kw), None, None)
+    assert rc == E.ERNIE_EINVAL
+
+
+def test_null_arguments_are_rejected_on_the_host():
+    lib = E.load_library()
+    assert lib.ernie_init_weights(None, None, None, 0, None, None, None) == E.ERNIE_EINVAL
+    cfg = base_cfg()
+    assert lib.ernie_init_weights(C.byref(cfg), None, None, 0, None, None, None) == E.ERNIE_EINVAL  # nowhere to write the size
+    assert lib.ernie_prefill(None, 1, 1, None, None, None, None, None, None) == E.ERNIE_EINVAL
+    assert lib.ernie_decode_step(None, None, None, None, None, None) == E.ERNIE_EINVAL
+    lib.ernie_free(None)     # no-op
+    out = C.c_void_p(); n = C.c_size_t()
+    assert lib.ernie_debug_buffer(None, b"x", C.byref(out), C.byref(n)) == E.ERNIE_EINVAL
+
+
+def test_error_strings():
+    assert E.error_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert E.error_string(code) not in ("ok", "unknown error")
+    assert E.error_string(-99) == "unknown error"

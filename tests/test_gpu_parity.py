@@ -1,0 +1,215 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, on seeded synthetic inputs."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from synth import CONFIGS, make_workload, Workload, make_weights, make_kept_ids, full_to_trimmed
+from tests.parity_util import oracle_generate, gpu_generate, check_rows
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def E():
+    import torch
+    import paper_2407_04991_amd as E
+    assert torch.cuda.is_available(), "GPU tests need a GPU: there is no CPU fallback"
+    E.load_library()
+    return E
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_affine"])
+def test_tiny_all_rows_against_the_definition(E, name):
+    """cfg 0 / 0b: every row, every step, against the full-recompute definition."""
+    _say(f"[parity] {name}")
+    wl = make_workload(name)
+    sh = wl.shape
+    eng = E.engine_from_workload(wl)
+    ids, lens = wl.padded(0)
+    orc = oracle_generate(wl, 0, range(sh.batch), sh.n_gen, definition=True)
+    forced = {r: orc[r]["tokens"] for r in orc}
+    toks, hid, lg = gpu_generate(eng, ids, lens, sh.n_gen, forced)
+    st = check_rows(orc, toks, hid, lg, name)
+    _say(f"[parity] {name}: {st}")
+    assert st["exact_required"] > 0
+    eng.close()
+
+
+def test_free_running_matches_teacher_forced(E):
+    """Feeding back the on-device argmax (tok_in = NULL) gives the same trajectory as feeding the same ids."""
+    import torch
+    wl = make_workload("tiny_affine")
+    sh = wl.shape
+    eng = E.engine_from_workload(wl)
+    ids, lens = wl.padded(0)
+    tok, lo, _ = eng.prefill(torch.as_tensor(ids), lens, logits=True)
+    free_toks, free_logits = [tok.cpu().numpy()], [lo.cpu().numpy()]
+    for _ in range(1, sh.n_gen):
+        tok, lo, _ = eng.decode_step(None, logits=True)
+        free_toks.append(tok.cpu().numpy()); free_logits.append(lo.cpu().numpy())
+    tok, lo, _ = eng.prefill(torch.as_tensor(ids), lens, logits=True)
+    for t in range(1, sh.n_gen):
+        assert np.array_equal(tok.cpu().numpy(), free_toks[t - 1])
+        tok, lo, _ = eng.decode_step(torch.as_tensor(free_toks[t - 1]), logits=True)
+        assert np.array_equal(lo.cpu().numpy(), free_logits[t])      # same kernels, same inputs: bit-identical
+    eng.close()
+
+
+def _ragged_workload(lengths, name="tiny_affine", **kw):
+    """A batch with the given prompt lengths at the tiny shape (d = 128, 2 heads)."""
+    sh = replace(CONFIGS[name], batch=len(lengths), prompt_len=max(lengths), **kw)
+    kept = make_kept_ids(sh)
+    w = make_weights(sh)
+    rng = np.random.default_rng(777)
+    seqs = [kept[rng.integers(0, len(kept), size=n)].astype(np.int32) for n in lengths]
+    wl = Workload(sh, w, kept)
+    wl.batches_full.append(seqs)
+    wl.batches_trimmed.append([full_to_trimmed(s, kept) for s in seqs])
+    return wl
+
+
+def test_ragged_batch_spanning_tiles(E):
+    """Variable lengths 1..200: several 128-row GEMM tiles, several attention key blocks, ragged tails, L = 1."""
+    lengths = [1, 2, 31, 33, 64, 65, 127, 130, 200]
+    n_gen = 6
+    wl = _ragged_workload(lengths, max_pos=256, n_gen=n_gen)
+    eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
+    ids, lens = wl.padded(0)
+    _say(f"[parity] ragged lengths {lengths}")
+    orc = oracle_generate(wl, 0, range(len(lengths)), n_gen)
+    forced = {r: orc[r]["tokens"] for r in orc}
+    toks, hid, lg = gpu_generate(eng, ids, lens, n_gen, forced)
+    st = check_rows(orc, toks, hid, lg, "ragged")
+    _say(f"[parity] ragged: {st}")
+    eng.close()
+
+
+def test_padding_and_batch_neighbours_do_not_matter(E):
+    """A sequence's outputs are independent of pad width, pad values, batch order and the other sequences."""
+    import torch
+    lengths = [40, 7, 90]
+    n_gen = 4
+    wl = _ragged_workload(lengths, max_pos=256, n_gen=n_gen)
+    eng = E.engine_from_workload(wl, max_batch=4, max_seq=160)
+    ids, lens = wl.padded(0)
+    a_t, a_h, a_l = gpu_generate(eng, ids, lens, n_gen)
+    # wider padding filled with junk ids, reversed batch order, one extra neighbour
+    wide = np.full((4, 150), 3, dtype=np.int32)
+    order = [2, 1, 0]
+    for i, r in enumerate(order):
+        wide[i, :lengths[r]] = ids[r, :lengths[r]]
+    wide[3, :5] = 1
+    lens2 = np.array([lengths[r] for r in order] + [5], dtype=np.int32)
+    b_t, b_h, b_l = gpu_generate(eng, wide, lens2, n_gen)
+    for i, r in enumerate(order):
+        assert np.array_equal(a_t[:, r], b_t[:, i])
+        assert np.max(np.abs(a_l[:, r] - b_l[:, i])) <= 1e-5
+        assert np.max(np.abs(a_h[:, r] - b_h[:, i])) <= 1e-5
+    eng.close()
+
+
+def test_kv_cache_contents_and_lengths(E):
+    """The cache holds K, V of exactly the valid positions, head-major, and lengths advance by one per step."""
+    import ctypes as C
+    import torch
+    from oracle import ernie_oracle as O
+    lengths = [5, 37]
+    wl = _ragged_workload(lengths, max_pos=64, n_gen=3)
+    sh = wl.shape
+    S = 48
+    eng = E.engine_from_workload(wl, max_seq=S)
+    ids, lens = wl.padded(0)
+    orc = oracle_generate(wl, 0, range(2), 3)
+    gpu_generate(eng, ids, lens, 3, {r: orc[r]["tokens"] for r in orc})
+    ptr, nbytes = eng.debug_buffer("kv")
+    H, d = sh.n_heads, sh.d_model
+    assert nbytes == sh.n_layers * 2 * 2 * S * d * 2
+    buf = torch.empty(nbytes // 2, dtype=torch.float16, device="cuda:0")
+    C.CDLL("libamdhip64.so.7").hipMemcpy(C.c_void_p(buf.data_ptr()), C.c_void_p(ptr), C.c_size_t(nbytes), 3)
+    kv = buf.cpu().numpy().astype(np.float64).reshape(sh.n_layers, 2, 2, H, S, 64)
+    lptr, _ = eng.debug_buffer("lens")
+    lens_dev = torch.empty(2, dtype=torch.int32, device="cuda:0")
+    C.CDLL("libamdhip64.so.7").hipMemcpy(C.c_void_p(lens_dev.data_ptr()), C.c_void_p(lptr), C.c_size_t(8), 3)
+    assert lens_dev.cpu().tolist() == [lengths[0] + 2, lengths[1] + 2]
+    # layer-0 keys/values of the prompt straight from the definition
+    p = O.Params(wl.weights, sh.n_heads, sh.ln_eps)
+    for b, L in enumerate(lengths):
+        X = O.embed(p, wl.batches_full[0][b])
+        lw = p.layers[0]
+        QKV = X @ lw["wqkv"].T + lw["bqkv"]
+        K, V = QKV[:, d:2 * d], QKV[:, 2 * d:]
+        for h in range(H):
+            assert np.max(np.abs(kv[0, 0, b, h, :L] - K[:, 64 * h:64 * h + 64])) < 5e-3
+            assert np.max(np.abs(kv[0, 1, b, h, :L] - V[:, 64 * h:64 * h + 64])) < 5e-3
+    eng.close()
+
+
+def test_error_paths_with_a_live_handle(E):
+    import torch
+    wl = make_workload("tiny")
+    eng = E.engine_from_workload(wl, max_batch=2, max_seq=34)
+    ids, lens = wl.padded(0)
+    dev_ids = torch.as_tensor(ids).cuda()
+    tok = torch.empty(2, dtype=torch.int32, device="cuda:0")
+    h = eng.handle
+    assert E.ernie_decode_step(h, None, None, None, tok) == E.ERNIE_ESEQUENCE          # before any prefill
+    assert E.ernie_prefill(h, 3, 32, dev_ids, np.array([32, 32, 32]), None, None, tok) == E.ERNIE_ECAPACITY
+    assert E.ernie_prefill(h, 2, 35, dev_ids, lens, None, None, tok) == E.ERNIE_ECAPACITY      # Lmax > max_seq
+    assert E.ernie_prefill(h, 2, 32, dev_ids, np.array([0, 32]), None, None, tok) == E.ERNIE_EINVAL
+    assert E.ernie_prefill(h, 2, 32, dev_ids, np.array([33, 32]), None, None, tok) == E.ERNIE_EINVAL
+    assert E.ernie_prefill(h, 2, 32, dev_ids, lens, None, None, None) == E.ERNIE_EINVAL
+    assert E.ernie_decode_step(h, None, None, None, tok) == E.ERNIE_ESEQUENCE          # failed calls left no state
+    assert E.ernie_prefill(h, 2, 32, dev_ids, lens, None, None, tok) == E.ERNIE_OK
+    assert E.ernie_decode_step(h, None, None, None, tok) == E.ERNIE_OK                 # slot 32
+    assert E.ernie_decode_step(h, None, None, None, tok) == E.ERNIE_OK                 # slot 33
+    assert E.ernie_decode_step(h, None, None, None, tok) == E.ERNIE_ECAPACITY          # slot 34 does not exist
+    torch.cuda.synchronize()
+    # arena too small / misaligned
+    rc, need, _ = E.ernie_init_weights(eng.cfg, None, None)
+    assert rc == E.ERNIE_OK and need == eng.arena_bytes
+    eng.close()
+
+
+def test_argmax_ties_pick_the_lowest_index(E):
+    """Two identical rows in the trimmed table give exactly equal logits: the lower index must win."""
+    import torch
+    wl = make_workload("tiny")
+    kept = wl.kept_ids
+    # make kept row 400 a copy of kept row 17, and make both dominate: scale that row up
+    te = wl.weights["tok_emb"].copy()
+    te[kept[17]] = (te[kept[17]].astype(np.float32) * 40).astype(np.float16)
+    te[kept[400]] = te[kept[17]]
+    wl.weights["tok_emb"] = te
+    eng = E.engine_from_workload(wl)
+    ids, lens = wl.padded(0)
+    tok, lo, ho = eng.prefill(torch.as_tensor(ids), lens, logits=True, hidden=True)
+    lo = lo.cpu().numpy(); tok = tok.cpu().numpy()
+    assert np.array_equal(lo[:, 17], lo[:, 400])
+    for b in range(2):
+        assert tok[b] == int(np.argmax(lo[b]))
+        if np.argmax(lo[b]) in (17, 400):
+            assert tok[b] == 17
+    eng.close()
+
+
+def test_base_shape_sampled_rows(E):
+    """cfg 1 (ERNIE-base, batch 32, prompt 128, 32 tokens) at full size, in the launch configuration the
+    benchmark times; the oracle computes a sample of rows one by one."""
+    wl = make_workload("base")
+    sh = wl.shape
+    eng = E.engine_from_workload(wl)
+    ids, lens = wl.padded(0)
+    rows = [0, 13, 31]
+    _say(f"[parity] base rows {rows}")
+    orc = oracle_generate(wl, 0, rows, sh.n_gen)
+    forced = {r: orc[r]["tokens"] for r in orc}
+    toks, hid, lg = gpu_generate(eng, ids, lens, sh.n_gen, forced)
+    st = check_rows(orc, toks, hid, lg, "base")
+    _say(f"[parity] base: {st}")
+    assert st["exact_required"] >= st["total"] // 4
+    eng.close()
