@@ -158,6 +158,15 @@ void ernie_free(ErnieHandle* h);
  */
 int ernie_debug_buffer(ErnieHandle* h, const char* name, void** ptr_dev, size_t* bytes);
 
+/*
+ * ernie_debug_tune -- test hook: override a decode-path tuning knob of this handle.
+ *   "fused_decode" 0/1  use the small-batch path (row-wise work fused into GEMM prologues) when it fits
+ *   "sk_out", "sk_f2"   split of the contraction of the attention-output / second FFN GEMM over workgroups
+ * Results are deterministic for any fixed setting.  Returns ERNIE_EINVAL for an unknown key or a split
+ * that does not divide the k-tile count.
+ */
+int ernie_debug_tune(ErnieHandle* h, const char* key, int value);
+
 /* ernie_error_string -- static description of an ERNIE_E* code. */
 const char* ernie_error_string(int code);
 

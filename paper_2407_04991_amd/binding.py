@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libernie_hip.so")
 ERNIE_OK, ERNIE_EINVAL, ERNIE_ECAPACITY, ERNIE_EARENA, ERNIE_ESEQUENCE, ERNIE_EHIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("ernie_init_weights", "ernie_prefill", "ernie_decode_step", "ernie_free",
-           "ernie_debug_buffer", "ernie_error_string")
+           "ernie_debug_buffer", "ernie_debug_tune", "ernie_error_string")
 
 
 class ErnieConfig(C.Structure):
@@ -70,6 +70,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ernie_free.argtypes = [C.c_void_p]
     lib.ernie_debug_buffer.restype = C.c_int
     lib.ernie_debug_buffer.argtypes = [C.c_void_p, C.c_char_p, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]
+    lib.ernie_debug_tune.restype = C.c_int
+    lib.ernie_debug_tune.argtypes = [C.c_void_p, C.c_char_p, C.c_int]
     lib.ernie_error_string.restype = C.c_char_p
     lib.ernie_error_string.argtypes = [C.c_int]
     if path is None:
@@ -210,6 +212,11 @@ class ErnieEngine:
         if rc != ERNIE_OK:
             raise ErnieError(rc, "ernie_debug_buffer")
         return ptr.value, n.value
+
+    def tune(self, key: str, value: int):
+        rc = load_library().ernie_debug_tune(self.handle, key.encode(), int(value))
+        if rc != ERNIE_OK:
+            raise ErnieError(rc, f"ernie_debug_tune({key}, {value})")
 
     def close(self):
         if self.handle is not None:

@@ -13,6 +13,7 @@
 
 #include "attention.h"
 #include "common.h"
+#include "decode_fused.h"
 #include "gemm_prefill.h"
 #include "gemm_skinny.h"
 #include "rowops.h"
@@ -23,6 +24,9 @@ namespace {
 
 constexpr size_t kAlign = 256;
 constexpr int kStagingSlots = 8;
+constexpr int kFusedMaxBatch = 64;     // the fused-prologue decode path keeps the whole batch in LDS
+constexpr int kMaxSplitK = 8;
+constexpr size_t kMaxLds = 160 * 1024;
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -37,6 +41,7 @@ struct ArenaPlan {
   size_t tok_rm, tok_p, pos, emb_g, emb_b, kept;
   struct L { size_t wqkv, wo, w1, w2, bqkv, bo, b1, b2, ln1_g, ln1_b, ln2_g, ln2_b; };
   std::vector<L> layers;
+  size_t r_qkv, r_out, r_f1, r_f2;
   size_t kv, X, X1, Y, Q, O, G, Yf, hlast, strip_val, strip_idx, cu, lens, tok_seq, tok_pos, tok_prev;
   size_t total;
   int vocab_tiles, strips;
@@ -69,6 +74,9 @@ ArenaPlan make_plan(const ErnieConfig& c) {
   p.X = take(p.t_max * d * 2); p.X1 = take(p.t_max * d * 2); p.Y = take(p.t_max * d * 2);
   p.Q = take(p.t_max * d * 2); p.O = take(p.t_max * d * 2); p.G = take(p.t_max * f * 2);
   p.Yf = take(Bm * d * 4);
+  const size_t Bf = Bm < (size_t)kFusedMaxBatch ? Bm : (size_t)kFusedMaxBatch;
+  p.r_qkv = take(Bf * 3 * d * 4); p.r_out = take(kMaxSplitK * Bf * d * 4);
+  p.r_f1 = take(Bf * f * 4); p.r_f2 = take(kMaxSplitK * Bf * d * 4);
   p.hlast = take(Bm * d * 2);
   p.strip_val = take(Bm * p.strips * 4); p.strip_idx = take(Bm * p.strips * 4);
   p.cu = take((Bm + 1) * 4); p.lens = take(Bm * 4);
@@ -99,7 +107,8 @@ struct ErnieHandle {
   float *emb_g, *emb_b;
   std::vector<LayerPtrs> layers;
   half_t *kv, *X, *X1, *Y, *Q, *O, *G, *hlast;
-  float *Yf, *strip_val;
+  float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2;
+  int sk_out, sk_f2, fused_decode;   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   int* staging;          // pinned host: kStagingSlots x (max_batch + 1) ints
   int staging_next;
@@ -109,6 +118,9 @@ struct ErnieHandle {
 };
 
 namespace {
+
+// Row-kernel instantiation by model width: RC chunks of 512 features per wave.
+#define ROW_DISPATCH(d, CALL) do { if ((d) <= 1024) { constexpr int RC = 2; CALL; } else if ((d) <= 2048) { constexpr int RC = 4; CALL; } else { constexpr int RC = 8; CALL; } } while (0)
 
 #define HIP_OK(expr) do { if ((expr) != hipSuccess) return ERNIE_EHIP; } while (0)
 
@@ -181,6 +193,119 @@ int configure_kernels() {
   return rc ? ERNIE_EHIP : ERNIE_OK;
 }
 
+
+// Split of the contraction over `gridDim.y` workgroups for the GEMMs with few
+// column strips: the smallest divisor of the k-tile count that brings the grid
+// to about 96 workgroups, capped so that the consumer does not pay for many partials.
+int pick_split_k(int strips, int k_tiles, int cap) {
+  int best = 1;
+  for (int sk = 1; sk <= cap; ++sk) {
+    if (k_tiles % sk != 0 || k_tiles / sk < 8) continue;
+    best = sk;
+    if (strips * sk >= 96) break;
+  }
+  return best;
+}
+
+size_t dec_lds_bytes(int MT, int NW, int kslice) {
+  const size_t a = (size_t)MT * 32 * (kslice + 8) * 2, r = (size_t)NW * MT * 16 * 64 * 4;
+  return a > r ? a : r;
+}
+
+template <int PRO, int EPI>
+int launch_gemm_dec(DecGemmArgs a, int sk, hipStream_t s) {
+  constexpr int NW = 8;
+  const int MT = (a.B + 31) / 32;
+  const int kslice = a.K / sk;
+  const size_t lds = dec_lds_bytes(MT, NW, kslice);
+  if (MT > 2 || lds > kMaxLds || (a.K / 16) % sk != 0) return ERNIE_EINVAL;
+  const dim3 grid((a.N + 31) / 32, sk), block(NW * 64);
+  if constexpr (PRO == PRO_LN) {
+    const int d = a.K;
+    if (MT == 1) ROW_DISPATCH(d, hipLaunchKernelGGL((gemm_dec_kernel<1, NW, PRO, EPI, RC>), grid, block, lds, s, a));
+    else ROW_DISPATCH(d, hipLaunchKernelGGL((gemm_dec_kernel<2, NW, PRO, EPI, RC>), grid, block, lds, s, a));
+  } else {
+    if (MT == 1) hipLaunchKernelGGL((gemm_dec_kernel<1, NW, PRO, EPI, 2>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((gemm_dec_kernel<2, NW, PRO, EPI, 2>), grid, block, lds, s, a);
+  }
+  return ERNIE_OK;
+}
+
+
+// Small batches: every GEMM input fits in LDS, row-wise work lives in consumer prologues (5 launches per layer).
+bool fused_decode_fits(const ErnieHandle* h, int B) {
+  if (!h->fused_decode || B > kFusedMaxBatch) return false;
+  const int MT = (B + 31) / 32, d = h->cfg.d_model, f = h->cfg.d_ffn;
+  return dec_lds_bytes(MT, 8, d) <= kMaxLds && dec_lds_bytes(MT, 8, f / h->sk_f2) <= kMaxLds &&
+         (d / 16) % h->sk_out == 0 && (f / 16) % h->sk_f2 == 0;
+}
+
+int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hipStream_t s) {
+  const ErnieConfig& c = h->cfg;
+  const int B = h->B, d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
+  int rc = ERNIE_OK;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerPtrs& L = h->layers[l];
+    DecGemmArgs a{};
+    a.B = B; a.eps = c.ln_eps;
+    // QKV: layer 0 reads the embedding rows; later layers normalise the previous FFN2 output on the fly
+    a.Wp = L.wqkv; a.N = 3 * d; a.K = d; a.rout = h->r_qkv;
+    if (l == 0) {
+      a.a16 = h->X;
+      rc |= launch_gemm_dec<PRO_PLAIN, EPI_RAW>(a, 1, s);
+    } else {
+      const LayerPtrs& P = h->layers[l - 1];
+      a.r32 = h->r_f2; a.sk_in = h->sk_f2; a.bias = P.b2; a.res = h->X1; a.gamma = P.ln2_g; a.beta = P.ln2_b;
+      a.xout = h->X;
+      rc |= launch_gemm_dec<PRO_LN, EPI_RAW>(a, 1, s);
+    }
+    hipLaunchKernelGGL(attn_decode_fused_kernel, dim3(H, B), dim3(256), 0, s, h->r_qkv, L.bqkv, kcache(h, l),
+                       vcache(h, l), h->lens, H, S, d, h->O);
+    DecGemmArgs o{};
+    o.B = B; o.Wp = L.wo; o.N = d; o.K = d; o.a16 = h->O; o.rout = h->r_out;
+    rc |= launch_gemm_dec<PRO_PLAIN, EPI_RAW>(o, h->sk_out, s);
+    DecGemmArgs f1{};
+    f1.B = B; f1.eps = c.ln_eps; f1.Wp = L.w1; f1.N = f; f1.K = d; f1.r32 = h->r_out; f1.sk_in = h->sk_out;
+    f1.bias = L.bo; f1.res = h->X; f1.gamma = L.ln1_g; f1.beta = L.ln1_b; f1.xout = h->X1; f1.rout = h->r_f1;
+    rc |= launch_gemm_dec<PRO_LN, EPI_RAW>(f1, 1, s);
+    DecGemmArgs f2{};
+    f2.B = B; f2.Wp = L.w2; f2.N = d; f2.K = f; f2.r32 = h->r_f1; f2.sk_in = 1; f2.bias = L.b1; f2.rout = h->r_f2;
+    rc |= launch_gemm_dec<PRO_GELU, EPI_RAW>(f2, h->sk_f2, s);
+  }
+  const LayerPtrs& P = h->layers[c.n_layers - 1];
+  ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_f2, h->sk_f2, P.b2, h->X1, B, d,
+                     P.ln2_g, P.ln2_b, c.ln_eps, h->X, hidden_out));
+  DecGemmArgs z{};
+  z.B = B; z.Wp = h->tok_p; z.N = c.vocab_kept; z.K = d; z.a16 = h->X; z.logits_out = logits_out;
+  z.strip_val = h->strip_val; z.strip_idx = h->strip_idx; z.strips = h->plan.strips;
+  rc |= launch_gemm_dec<PRO_PLAIN, EPI_ARGMAX>(z, 1, s);
+  return rc ? ERNIE_EHIP : ERNIE_OK;
+}
+
+// Larger batches: one kernel per operation (weights are a small share of the step's bytes there).
+int decode_layers_multi(ErnieHandle* h, float* logits_out, float* hidden_out, hipStream_t s) {
+  const ErnieConfig& c = h->cfg;
+  const int B = h->B, d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerPtrs& L = h->layers[l];
+    launch_skinny(h->X, L.wqkv, L.bqkv, B, 3 * d, d, SkinnyQKV{h->Q, kcache(h, l), vcache(h, l), h->lens, d, H, S},
+                  s);
+    hipLaunchKernelGGL(attn_decode_kernel, dim3(H, B), dim3(256), 0, s, h->Q, kcache(h, l), vcache(h, l), h->lens, H,
+                       S, d, h->O);
+    launch_skinny(h->O, L.wo, L.bo, B, d, d, SkinnyResidual{h->X, h->Yf, d}, s);
+    ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f32_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->Yf, B, d, L.ln1_g, L.ln1_b,
+                       c.ln_eps, h->X1));
+    launch_skinny(h->X1, L.w1, L.b1, B, f, d, SkinnyGelu{h->G, f}, s);
+    launch_skinny(h->G, L.w2, L.b2, B, d, f, SkinnyResidual{h->X1, h->Yf, d}, s);
+    ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f32_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->Yf, B, d, L.ln2_g, L.ln2_b,
+                       c.ln_eps, h->X));
+  }
+  if (hidden_out)
+    hipLaunchKernelGGL(hidden_to_f32_kernel, dim3((B * d + 255) / 256), dim3(256), 0, s, h->X, B * d, hidden_out);
+  launch_logits(h, h->X, B, logits_out, s);
+  return ERNIE_OK;
+}
+
 void pack_into(const void* src, half_t* dst, int N, int K, hipStream_t s) {
   const int n_tiles = (N + 31) / 32;
   const size_t total = (size_t)n_tiles * (K / 16) * 64;
@@ -240,6 +365,10 @@ int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* w, void* aren
   h->kv = H16(plan.kv); h->X = H16(plan.X); h->X1 = H16(plan.X1); h->Y = H16(plan.Y); h->Q = H16(plan.Q);
   h->O = H16(plan.O); h->G = H16(plan.G); h->hlast = H16(plan.hlast);
   h->Yf = F32(plan.Yf); h->strip_val = F32(plan.strip_val);
+  h->r_qkv = F32(plan.r_qkv); h->r_out = F32(plan.r_out); h->r_f1 = F32(plan.r_f1); h->r_f2 = F32(plan.r_f2);
+  h->fused_decode = 1;
+  h->sk_out = pick_split_k(cfg->d_model / 32, cfg->d_model / 16, 2);
+  h->sk_f2 = pick_split_k(cfg->d_model / 32, cfg->d_ffn / 16, 4);
   h->strip_idx = I32(plan.strip_idx); h->cu = I32(plan.cu); h->lens = I32(plan.lens);
   h->tok_seq = I32(plan.tok_seq); h->tok_pos = I32(plan.tok_pos); h->tok_prev = I32(plan.tok_prev);
   h->prefilled = false; h->B = 0; h->max_len = 0; h->steps = 0;
@@ -310,8 +439,8 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
   const int d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
   hipLaunchKernelGGL(token_map_kernel, dim3((T + 255) / 256), dim3(256), 0, s, h->cu, B, T, h->tok_seq, h->tok_pos,
                      h->lens);
-  hipLaunchKernelGGL(embed_ln_prefill_kernel, dim3((T + 3) / 4), dim3(256), 0, s, ids_dev, Lmax, h->tok_seq,
-                     h->tok_pos, T, h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X);
+  ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_prefill_kernel<RC>, dim3((T + 3) / 4), dim3(256), 0, s, ids_dev, Lmax, h->tok_seq,
+                     h->tok_pos, T, h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X));
   const int q_tiles = (max_len + kAttnQTile - 1) / kAttnQTile;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerPtrs& L = h->layers[l];
@@ -320,12 +449,12 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
     hipLaunchKernelGGL(attn_prefill_kernel, dim3(q_tiles, H, B), dim3(256), 0, s, h->Q, kcache(h, l), vcache(h, l),
                        h->cu, T, H, S, d, h->O);
     launch_gemm_prefill(h->O, L.wo, L.bo, T, d, d, EpiResidual{h->X, h->Y, d}, s);
-    hipLaunchKernelGGL(ln_rows_f16_kernel, dim3((T + 3) / 4), dim3(256), 0, s, h->Y, T, d, L.ln1_g, L.ln1_b, c.ln_eps,
-                       h->X1);
+    ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f16_kernel<RC>, dim3((T + 3) / 4), dim3(256), 0, s, h->Y, T, d, L.ln1_g, L.ln1_b, c.ln_eps,
+                       h->X1));
     launch_gemm_prefill(h->X1, L.w1, L.b1, T, f, d, EpiGelu{h->G, f}, s);
     launch_gemm_prefill(h->G, L.w2, L.b2, T, d, f, EpiResidual{h->X1, h->Y, d}, s);
-    hipLaunchKernelGGL(ln_rows_f16_kernel, dim3((T + 3) / 4), dim3(256), 0, s, h->Y, T, d, L.ln2_g, L.ln2_b, c.ln_eps,
-                       h->X);
+    ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f16_kernel<RC>, dim3((T + 3) / 4), dim3(256), 0, s, h->Y, T, d, L.ln2_g, L.ln2_b, c.ln_eps,
+                       h->X));
   }
   hipLaunchKernelGGL(gather_last_rows_kernel, dim3(B), dim3(256), 0, s, h->X, h->cu, B, d, h->hlast, hidden_out_dev);
   launch_logits(h, h->hlast, B, logits_out_dev, s);
@@ -344,29 +473,15 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_o
   if (next_pos + 1 > c.max_seq || next_pos >= c.max_pos) return ERNIE_ECAPACITY;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const int B = h->B, d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
+  const int B = h->B, d = c.d_model;
   const int* tok = tok_in_dev ? tok_in_dev : h->tok_prev;
-  hipLaunchKernelGGL(embed_ln_decode_kernel, dim3((B + 3) / 4), dim3(256), 0, s, tok, h->lens, B, c.max_pos,
-                     h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X);
-  for (int l = 0; l < c.n_layers; ++l) {
-    const LayerPtrs& L = h->layers[l];
-    launch_skinny(h->X, L.wqkv, L.bqkv, B, 3 * d, d, SkinnyQKV{h->Q, kcache(h, l), vcache(h, l), h->lens, d, H, S},
-                  s);
-    hipLaunchKernelGGL(attn_decode_kernel, dim3(H, B), dim3(256), 0, s, h->Q, kcache(h, l), vcache(h, l), h->lens, H,
-                       S, d, h->O);
-    launch_skinny(h->O, L.wo, L.bo, B, d, d, SkinnyResidual{h->X, h->Yf, d}, s);
-    hipLaunchKernelGGL(ln_rows_f32_kernel, dim3((B + 3) / 4), dim3(256), 0, s, h->Yf, B, d, L.ln1_g, L.ln1_b,
-                       c.ln_eps, h->X1);
-    launch_skinny(h->X1, L.w1, L.b1, B, f, d, SkinnyGelu{h->G, f}, s);
-    launch_skinny(h->G, L.w2, L.b2, B, d, f, SkinnyResidual{h->X1, h->Yf, d}, s);
-    hipLaunchKernelGGL(ln_rows_f32_kernel, dim3((B + 3) / 4), dim3(256), 0, s, h->Yf, B, d, L.ln2_g, L.ln2_b,
-                       c.ln_eps, h->X);
-  }
-  if (hidden_out_dev)
-    hipLaunchKernelGGL(hidden_to_f32_kernel, dim3((B * d + 255) / 256), dim3(256), 0, s, h->X, B * d, hidden_out_dev);
-  launch_logits(h, h->X, B, logits_out_dev, s);
+  ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_decode_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, tok, h->lens, B, c.max_pos,
+                     h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X));
+  const int rc = fused_decode_fits(h, B) ? decode_layers_fused(h, logits_out_dev, hidden_out_dev, s)
+                                         : decode_layers_multi(h, logits_out_dev, hidden_out_dev, s);
+  if (rc != ERNIE_OK) return rc;
   hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->plan.strips,
-                     tok_out_dev, h->tok_prev, h->lens, 1, S, c.vocab_kept);
+                     tok_out_dev, h->tok_prev, h->lens, 1, c.max_seq, c.vocab_kept);
   h->steps += 1;
   return launch_status();
 }
@@ -390,6 +505,18 @@ int ernie_debug_buffer(ErnieHandle* h, const char* name, void** ptr_dev, size_t*
     return ERNIE_EINVAL;
   }
   return ERNIE_OK;
+}
+
+int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
+  if (!h || !key) return ERNIE_EINVAL;
+  if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
+  if (!strcmp(key, "sk_out") || !strcmp(key, "sk_f2")) {
+    const int k_tiles = (!strcmp(key, "sk_out") ? h->cfg.d_model : h->cfg.d_ffn) / 16;
+    if (value < 1 || value > kMaxSplitK || k_tiles % value != 0) return ERNIE_EINVAL;
+    (!strcmp(key, "sk_out") ? h->sk_out : h->sk_f2) = value;
+    return ERNIE_OK;
+  }
+  return ERNIE_EINVAL;
 }
 
 }  // extern "C"

@@ -7,6 +7,8 @@
 namespace ernie {
 
 constexpr int kMaxRowChunks = 8;   // one wave normalises a row of up to 64 * 8 * 8 = 4096 features
+// Row kernels are instantiated for RC = 2, 4, 8 chunks of 512 features per wave (d <= 1024, 2048, 4096)
+// so that narrow models do not pay registers for the widest case.
 
 // ---------------------------------------------------------------- init-time
 
@@ -39,30 +41,32 @@ __global__ void cvt_f16_f32_kernel(const half_t* __restrict__ src, float* __rest
 // One wave owns one row held as fp32 in registers: chunk c of lane l covers
 // features (c * 64 + l) * 8 .. +7.  Two-pass statistics (mean, then centred
 // sum of squares) in fp32, population variance, eps inside the square root.
+template <int RC>
 struct RowRegs {
-  float v[kMaxRowChunks][8];
+  float v[RC][8];
 };
 
-__device__ __forceinline__ void row_layernorm_store(RowRegs& r, int d, int lane, const float* __restrict__ gamma,
+template <int RC>
+__device__ __forceinline__ void row_layernorm_store(RowRegs<RC>& r, int d, int lane, const float* __restrict__ gamma,
                                                     const float* __restrict__ beta, float eps,
                                                     half_t* __restrict__ out_row) {
   const int chunks = d / 8;
   float s = 0.f;
 #pragma unroll
-  for (int c = 0; c < kMaxRowChunks; ++c)
+  for (int c = 0; c < RC; ++c)
     if (c * 64 + lane < chunks)
 #pragma unroll
       for (int j = 0; j < 8; ++j) s += r.v[c][j];
   const float mean = wave_sum(s) / (float)d;
   float q = 0.f;
 #pragma unroll
-  for (int c = 0; c < kMaxRowChunks; ++c)
+  for (int c = 0; c < RC; ++c)
     if (c * 64 + lane < chunks)
 #pragma unroll
       for (int j = 0; j < 8; ++j) { float t = r.v[c][j] - mean; q += t * t; }
   const float rstd = rsqrtf(wave_sum(q) / (float)d + eps);
 #pragma unroll
-  for (int c = 0; c < kMaxRowChunks; ++c) {
+  for (int c = 0; c < RC; ++c) {
     const int ch = c * 64 + lane;
     if (ch < chunks) {
       half8 o;
@@ -93,6 +97,7 @@ __global__ void token_map_kernel(const int* __restrict__ cu, int B, int T, int* 
 }
 
 // x_t = LN_emb(E'[id_t] + Epos[pos_t]) for every packed prompt token (one wave per token).
+template <int RC>
 __global__ __launch_bounds__(256) void embed_ln_prefill_kernel(
     const int* __restrict__ ids, int Lmax, const int* __restrict__ tok_seq, const int* __restrict__ tok_pos, int T,
     const half_t* __restrict__ tok_emb, const half_t* __restrict__ pos_emb, const float* __restrict__ gamma,
@@ -104,10 +109,10 @@ __global__ __launch_bounds__(256) void embed_ln_prefill_kernel(
   const int id = ids[(size_t)b * Lmax + pos];
   const half_t* e = tok_emb + (size_t)id * d;
   const half_t* p = pos_emb + (size_t)pos * d;
-  RowRegs r;
+  RowRegs<RC> r;
   const int chunks = d / 8;
 #pragma unroll
-  for (int c = 0; c < kMaxRowChunks; ++c) {
+  for (int c = 0; c < RC; ++c) {
     const int ch = c * 64 + lane;
     if (ch < chunks) {
       const half8 a = *reinterpret_cast<const half8*>(e + ch * 8);
@@ -121,6 +126,7 @@ __global__ __launch_bounds__(256) void embed_ln_prefill_kernel(
 
 // Decode: one token per sequence at position cache_len[b].  tok_in == NULL is
 // handled by the caller passing the previous step's output buffer.
+template <int RC>
 __global__ __launch_bounds__(256) void embed_ln_decode_kernel(
     const int* __restrict__ tok, const int* __restrict__ cache_len, int B, int max_pos,
     const half_t* __restrict__ tok_emb, const half_t* __restrict__ pos_emb, const float* __restrict__ gamma,
@@ -131,10 +137,10 @@ __global__ __launch_bounds__(256) void embed_ln_decode_kernel(
   const int pos = min(cache_len[b], max_pos - 1);
   const half_t* e = tok_emb + (size_t)tok[b] * d;
   const half_t* p = pos_emb + (size_t)pos * d;
-  RowRegs r;
+  RowRegs<RC> r;
   const int chunks = d / 8;
 #pragma unroll
-  for (int c = 0; c < kMaxRowChunks; ++c) {
+  for (int c = 0; c < RC; ++c) {
     const int ch = c * 64 + lane;
     if (ch < chunks) {
       const half8 a = *reinterpret_cast<const half8*>(e + ch * 8);
@@ -147,6 +153,7 @@ __global__ __launch_bounds__(256) void embed_ln_decode_kernel(
 }
 
 // X = LN(Y) where Y already holds sublayer output + bias + residual (fp16 rows, prefill).
+template <int RC>
 __global__ __launch_bounds__(256) void ln_rows_f16_kernel(const half_t* __restrict__ Y, int rows, int d,
                                                           const float* __restrict__ gamma,
                                                           const float* __restrict__ beta, float eps,
@@ -154,10 +161,10 @@ __global__ __launch_bounds__(256) void ln_rows_f16_kernel(const half_t* __restri
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= rows) return;
-  RowRegs r;
+  RowRegs<RC> r;
   const int chunks = d / 8;
 #pragma unroll
-  for (int c = 0; c < kMaxRowChunks; ++c) {
+  for (int c = 0; c < RC; ++c) {
     const int ch = c * 64 + lane;
     if (ch < chunks) {
       const half8 a = *reinterpret_cast<const half8*>(Y + (size_t)t * d + ch * 8);
@@ -169,6 +176,7 @@ __global__ __launch_bounds__(256) void ln_rows_f16_kernel(const half_t* __restri
 }
 
 // Decode: X = LN(Y) with Y fp32 rows (sublayer output + bias + residual kept in fp32).
+template <int RC>
 __global__ __launch_bounds__(256) void ln_rows_f32_kernel(const float* __restrict__ Y, int rows, int d,
                                                           const float* __restrict__ gamma,
                                                           const float* __restrict__ beta, float eps,
@@ -176,10 +184,10 @@ __global__ __launch_bounds__(256) void ln_rows_f32_kernel(const float* __restric
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= rows) return;
-  RowRegs r;
+  RowRegs<RC> r;
   const int chunks = d / 8;
 #pragma unroll
-  for (int c = 0; c < kMaxRowChunks; ++c) {
+  for (int c = 0; c < RC; ++c) {
     const int ch = c * 64 + lane;
     if (ch < chunks) {
       const float4 a = *reinterpret_cast<const float4*>(Y + (size_t)t * d + ch * 8);

@@ -213,3 +213,47 @@ def test_base_shape_sampled_rows(E):
     _say(f"[parity] base: {st}")
     assert st["exact_required"] >= st["total"] // 4
     eng.close()
+
+
+@pytest.mark.parametrize("B", [40, 70, 130, 256])
+def test_decode_paths_by_batch_size(E, B):
+    """Batch sizes that select each decode kernel variant (1, 2, 4, 8 row tiles; fused and per-operation paths)."""
+    rng = np.random.default_rng(B)
+    lengths = [int(x) for x in rng.integers(3, 40, size=B)]
+    n_gen = 4
+    wl = _ragged_workload(lengths, max_pos=64, n_gen=n_gen)
+    eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
+    ids, lens = wl.padded(0)
+    rows = [0, B // 3, B // 2, B - 1]
+    _say(f"[parity] batch {B} rows {rows}")
+    orc = oracle_generate(wl, 0, rows, n_gen)
+    toks, hid, lg = gpu_generate(eng, ids, lens, n_gen, {r: orc[r]["tokens"] for r in orc})
+    st = check_rows(orc, toks, hid, lg, f"batch{B}")
+    _say(f"[parity] batch {B}: {st}")
+    eng.close()
+
+
+def test_decode_tuning_variants_agree(E):
+    """Every split-K setting and both decode paths meet the oracle and agree with each other closely."""
+    wl = make_workload("tiny_affine")
+    sh = wl.shape
+    ids, lens = wl.padded(0)
+    orc = oracle_generate(wl, 0, range(sh.batch), sh.n_gen)
+    forced = {r: orc[r]["tokens"] for r in orc}
+    ref = None
+    for fused, sk_out, sk_f2 in [(1, 1, 1), (0, 1, 1), (1, 2, 2), (1, 4, 8), (1, 8, 4)]:
+        eng = E.engine_from_workload(wl)
+        eng.tune("fused_decode", fused); eng.tune("sk_out", sk_out); eng.tune("sk_f2", sk_f2)
+        _say(f"[parity] variant fused={fused} sk_out={sk_out} sk_f2={sk_f2}")
+        toks, hid, lg = gpu_generate(eng, ids, lens, sh.n_gen, forced)
+        check_rows(orc, toks, hid, lg, f"variant{(fused, sk_out, sk_f2)}")
+        if ref is None:
+            ref = lg
+        assert np.max(np.abs(lg - ref)) < 2e-3
+        eng.close()
+    eng = E.engine_from_workload(wl)
+    with pytest.raises(E.ErnieError):
+        eng.tune("sk_out", 3)         # 8 k-tiles are not divisible by 3
+    with pytest.raises(E.ErnieError):
+        eng.tune("no_such_knob", 1)
+    eng.close()
