@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--workload", default="base")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=16)
+    ap.add_argument("--graph", type=int, default=1, help="replay the pass as HIP graphs (1) or launch eagerly (0)")
+    ap.add_argument("--tune", action="append", default=[], help="decode tuning knob, key=value (repeatable)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (sequences shard by batch with no collective); "
@@ -87,40 +89,64 @@ def main():
     tok = torch.empty(B, dtype=torch.int32, device="cuda:0")
     h = eng.handle
 
-    def one_pass():
+    def prefill_call():
         rc = E.ernie_prefill(h, B, ids.shape[1], ids, lens, None, None, tok)
         assert rc == 0, rc
+
+    def decode_calls():
         for _ in range(N - 1):
             rc = E.ernie_decode_step(h, None, None, None, tok)
             assert rc == 0, rc
 
-    for _ in range(args.warmup):
-        one_pass()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_pass()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    tokens_per_s = B * N / (dt / args.steps)
+    for kv in args.tune:
+        k, v = kv.split("=")
+        eng.tune(k, int(v))
 
-    # per-phase device time with events on the stream the kernels are launched on (torch's current stream)
-    reps = max(3, min(args.steps, 10))
-    pre_ms, dec_ms = [], []
-    for _ in range(reps):
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(N + 1)]
-        e[0].record()
-        E.ernie_prefill(h, B, ids.shape[1], ids, lens, None, None, tok)
-        e[1].record()
-        for t in range(1, N):
-            E.ernie_decode_step(h, None, None, None, tok)
-            e[t + 1].record()
+    # The launch sequence of one pass is recorded once into two HIP graphs (prefill; the N-1 decode steps)
+    # on a side stream and replayed: per-sequence lengths and fed-back tokens live on the device, so a
+    # replay is a complete, independent generation.
+    side = torch.cuda.Stream()
+    if args.graph:
+        with torch.cuda.stream(side):
+            prefill_call(); decode_calls()
+        side.synchronize()
+        tok_eager = tok.cpu().numpy()
+        g_pre, g_dec = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_pre, stream=side):
+            prefill_call()
+        with torch.cuda.graph(g_dec, stream=side):
+            decode_calls()
+        run_pre, run_dec = g_pre.replay, g_dec.replay
+    else:
+        run_pre, run_dec = prefill_call, decode_calls
+
+    with torch.cuda.stream(side):
+        for _ in range(args.warmup):
+            run_pre(); run_dec()
+        side.synchronize()
         torch.cuda.synchronize()
-        pre_ms.append(e[0].elapsed_time(e[1]))
-        dec_ms.append([e[t].elapsed_time(e[t + 1]) for t in range(1, N)])
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run_pre(); run_dec()
+        side.synchronize()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ms_per_step = dt / args.steps * 1e3
+        tokens_per_s = B * N / (dt / args.steps)
+
+        # device time of the two phases, events recorded on the stream the kernels run on
+        reps = max(3, min(args.steps, 10))
+        pre_ms, dec_ms = [], []
+        for _ in range(reps):
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record(side); run_pre(); e[1].record(side); run_dec(); e[2].record(side)
+            side.synchronize()
+            pre_ms.append(e[0].elapsed_time(e[1])); dec_ms.append(e[1].elapsed_time(e[2]) / (N - 1))
+        tok_host = tok.cpu().numpy()
+    if args.graph:
+        assert (tok_host == tok_eager).all(), "graph replay and eager launch disagree on the last emitted tokens"
     pre = float(np.median(pre_ms))
-    dec = np.median(np.array(dec_ms), axis=0)            # per decode step index
+    dec = np.full(N - 1, float(np.median(dec_ms)))       # mean decode-step time of a pass
     L = int(lens.max())
     step_bytes = np.array([algorithmic_decode_bytes(sh, B, int(np.mean(lens)) + t + 1) for t in range(N - 1)])
     dec_gbs = float(np.mean(step_bytes / (dec * 1e-3)) / 1e9)
@@ -133,7 +159,7 @@ def main():
         "config": {"workload": f"{sh.name}: {sh.n_layers} layers d={sh.d_model} heads={sh.n_heads} ffn={sh.d_ffn} "
                                f"V'={sh.vocab_kept}/{sh.vocab_full}, batch {B}, prompt {L}, generate {N} "
                                f"(1 prefill + {N - 1} decode steps, greedy, free-running)"},
-        "prefill_ms": pre, "prefill_tflops": pf / (pre * 1e-3) / 1e12,
+        "launch": "hip-graph replay" if args.graph else "eager", "prefill_ms": pre, "prefill_tflops": pf / (pre * 1e-3) / 1e12,
         "prefill_frac_of_mfma_peak": pf / (pre * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS,
         "decode_step_ms_mean": float(dec.mean()), "decode_step_ms_median": float(np.median(dec)),
         "decode_tokens_per_s": B / (float(dec.mean()) * 1e-3),

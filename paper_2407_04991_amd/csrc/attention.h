@@ -30,7 +30,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const half_t* __restr
                                                            half_t* __restrict__ O) {           // [T, d]
   __shared__ __align__(16) half_t sVt[64 * kAttnVtPitch];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int h = blockIdx.y, b = blockIdx.z;
   const int t0 = cu[b];
   const int L = cu[b + 1] - t0;
@@ -179,7 +180,8 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const half_t* __restri
                                                           const int* __restrict__ cache_len, int H, int S, int d,
                                                           half_t* __restrict__ O) {          // [B, d]
   __shared__ float sm[4][8][10];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int h = blockIdx.x, b = blockIdx.y;
   const int c = min(cache_len[b] + 1, S);       // keys visible: everything cached plus the token just appended
   const int ec = lane & 7, team = lane >> 3;
@@ -276,12 +278,32 @@ __global__ __launch_bounds__(256) void attn_decode_fused_kernel(const float* __r
                                                                 const int* __restrict__ cache_len, int H, int S,
                                                                 int d, half_t* __restrict__ O) {
   __shared__ float sm[4][8][10];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int h = blockIdx.x, b = blockIdx.y;
   const int len = cache_len[b];
   const bool has_new = len < S;                 // a replayed step past capacity appends nothing
   const int c = has_new ? len + 1 : S;
+  const int newest = has_new ? len : -1;        // this key comes from registers, not from the cache
   const int ec = lane & 7, team = lane >> 3;
+  half_t* Kb = Kc + ((size_t)b * H + h) * S * 64 + ec * 8;
+  half_t* Vb = Vc + ((size_t)b * H + h) * S * 64 + ec * 8;
+
+  constexpr int U = 4;                           // 8-row groups in flight per wave
+  half8 kf[U], vf[U];
+  int key[U];
+  auto load_groups = [&](int g0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      key[u] = (g0 + u) * 8 + team;
+      const bool from_cache = key[u] < c && key[u] != newest;
+      const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+      kf[u] = from_cache ? *reinterpret_cast<const half8*>(Kb + (size_t)key[u] * 64) : z;
+      vf[u] = from_cache ? *reinterpret_cast<const half8*>(Vb + (size_t)key[u] * 64) : z;
+    }
+  };
+  int g0 = wave * U;
+  load_groups(g0);                               // the cache stream starts before the prologue arithmetic
 
   float q[8];
   half8 knew, vnew;
@@ -295,36 +317,22 @@ __global__ __launch_bounds__(256) void attn_decode_fused_kernel(const float* __r
       vnew[j] = (half_t)(r[2 * d + j] + bs[2 * d + j]);
     }
   }
-  half_t* Kb = Kc + ((size_t)b * H + h) * S * 64 + ec * 8;
-  half_t* Vb = Vc + ((size_t)b * H + h) * S * 64 + ec * 8;
   if (has_new && wave == 0 && team == 0) {
     *reinterpret_cast<half8*>(Kb + (size_t)len * 64) = knew;
     *reinterpret_cast<half8*>(Vb + (size_t)len * 64) = vnew;
   }
-  const int newest = has_new ? len : -1;        // this key comes from registers
 
   SoftmaxPart st;
   st.m = -INFINITY; st.l = 0.f;
 #pragma unroll
   for (int j = 0; j < 8; ++j) st.acc[j] = 0.f;
 
-  constexpr int U = 4;
-  for (int g0 = wave * U; g0 * 8 < c; g0 += 4 * U) {
-    half8 kf[U], vf[U];
-    int key[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      key[u] = (g0 + u) * 8 + team;
-      const bool from_cache = key[u] < c && key[u] != newest;
-      const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      kf[u] = from_cache ? *reinterpret_cast<const half8*>(Kb + (size_t)key[u] * 64) : z;
-      vf[u] = from_cache ? *reinterpret_cast<const half8*>(Vb + (size_t)key[u] * 64) : z;
-      if (key[u] == newest) { kf[u] = knew; vf[u] = vnew; }
-    }
+  while (g0 * 8 < c) {
     float s[U];
     float mx = st.m;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+      if (key[u] == newest) { kf[u] = knew; vf[u] = vnew; }
       float p = 0.f;
 #pragma unroll
       for (int j = 0; j < 8; ++j) p += q[j] * (float)kf[u][j];
@@ -334,6 +342,11 @@ __global__ __launch_bounds__(256) void attn_decode_fused_kernel(const float* __r
       s[u] = (key[u] < c) ? p : -INFINITY;
       mx = fmaxf(mx, s[u]);
     }
+    half8 vcur[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) vcur[u] = vf[u];
+    g0 += 4 * U;
+    if (g0 * 8 < c) load_groups(g0);             // next batch in flight during the softmax update
     if (mx != -INFINITY) {
       const float alpha = (st.m == -INFINITY) ? 0.f : __expf(st.m - mx);
       st.l *= alpha;
@@ -344,7 +357,7 @@ __global__ __launch_bounds__(256) void attn_decode_fused_kernel(const float* __r
         const float p = __expf(s[u] - mx);
         st.l += p;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) st.acc[j] += p * (float)vf[u][j];
+        for (int j = 0; j < 8; ++j) st.acc[j] += p * (float)vcur[u][j];
       }
       st.m = mx;
     }

@@ -5,14 +5,14 @@
 // a layer to five phases by moving every row-wise operation into the PROLOGUE
 // of its consumer:
 //
-//   gemm_dec<PRO_LN>    A = LayerNorm(sum_k partial_k + bias + residual)     (QKV, FFN1)
-//   gemm_dec<PRO_GELU>  A = gelu(raw + bias)                                 (FFN2)
-//   gemm_dec<PRO_PLAIN> A = fp16 activations                                 (out-proj, logits)
+//   gemm_dec_ln   A = LayerNorm(sum_k partial_k + bias + residual)     (QKV, FFN1)
+//   gemm_dec      A = fp16 activations                                 (out-proj, FFN2, logits)
 //   attn_decode_fused   q, k, v = raw + bias; append k, v; attend            (attention)
 //
-// Every GEMM phase writes raw fp32 accumulators (optionally split over K into
+// A GEMM phase writes raw fp32 accumulators (optionally split over K into
 // `gridDim.y` partial buffers that the consumer adds in a fixed order), so the
-// result does not depend on scheduling.  Each workgroup issues its weight
+// result does not depend on scheduling; FFN1 instead applies bias + GELU in its
+// epilogue, where every element is computed exactly once.  Each workgroup issues its weight
 // fragment loads BEFORE the prologue: the HBM latency of the weight stream
 // hides under the L2-resident activation work.
 #pragma once
@@ -22,8 +22,7 @@
 
 namespace ernie {
 
-enum { PRO_PLAIN = 0, PRO_LN = 1, PRO_GELU = 2 };
-enum { EPI_RAW = 0, EPI_ARGMAX = 1 };
+enum { EPI_RAW = 0, EPI_ARGMAX = 1, EPI_GELU16 = 2 };
 
 constexpr int kDecMaxFrag = 8;   // weight fragments a wave keeps in flight
 
@@ -31,30 +30,59 @@ struct DecGemmArgs {
   const half_t* Wp;   // packed [N, K]
   int N, K, B;
   // prologue inputs
-  const half_t* a16;  // PRO_PLAIN: [B, K] fp16
-  const float* r32;   // PRO_LN / PRO_GELU: raw fp32 [sk_in][B][K]
+  const half_t* a16;  // gemm_dec: [B, K] fp16
+  const float* r32;   // gemm_dec_ln: raw fp32 [sk_in][B][K]
   int sk_in;
   const float* bias;  // [K] bias of the GEMM that produced r32
-  const half_t* res;  // PRO_LN: residual [B, K] fp16
+  const half_t* res;  // gemm_dec_ln: residual [B, K] fp16
   const float* gamma;
   const float* beta;
   float eps;
-  half_t* xout;       // PRO_LN: normalised rows [B, K] fp16, written by workgroup (0, 0); may be null
+  half_t* xout;       // gemm_dec_ln: normalised rows [B, K] fp16, written by the strip-0 workgroups; may be null
   // outputs
   float* rout;        // EPI_RAW: [gridDim.y][B][N]
+  const float* bias_out;  // EPI_GELU16: [N] bias of THIS GEMM
+  half_t* g16;        // EPI_GELU16: gelu(acc + bias_out) as fp16 [B, N]; needs gridDim.y == 1
   float* logits_out;  // EPI_ARGMAX: [B, N] or null
   float* strip_val;   // EPI_ARGMAX: [B, strips]
   int* strip_idx;
   int strips;
 };
 
-template <int MT, int NW, int PRO, int EPI, int RC>
+// Shared epilogue of the decode GEMMs: `s` is the finished accumulator of (row, col).
+template <int EPI>
+__device__ __forceinline__ void dec_epilogue(const DecGemmArgs& p, int nt, int lane, int row, int col, float s) {
+  const int B = p.B;
+  if constexpr (EPI == EPI_RAW) {
+    if (row < B && col < p.N) p.rout[((size_t)blockIdx.y * B + row) * p.N + col] = s;
+  } else if constexpr (EPI == EPI_GELU16) {
+    if (row < B && col < p.N) p.g16[(size_t)row * p.N + col] = (half_t)gelu_erf(s + p.bias_out[col]);
+  } else {
+    if (p.logits_out && row < B && col < p.N) p.logits_out[(size_t)row * p.N + col] = s;
+    float bv = (col < p.N) ? s : -INFINITY;      // best of this strip for `row`: reduce over the 32 lanes of a half-wave
+    int bi = col;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(bv, o, 64);
+      const int oi = __shfl_xor(bi, o, 64);
+      argmax_merge(bv, bi, ov, oi);
+    }
+    if ((lane & 31) == 0 && row < B) {
+      p.strip_val[(size_t)row * p.strips + nt] = bv;
+      p.strip_idx[(size_t)row * p.strips + nt] = bi;
+    }
+  }
+}
+
+// A = fp16 activations [B, K].  grid = (column strips, split-K); MT = ceil(B / 32) row tiles.
+template <int MT, int NW, int EPI>
 __global__ __launch_bounds__(NW * 64) void gemm_dec_kernel(DecGemmArgs p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   half_t* sA = reinterpret_cast<half_t*>(smem_raw);
   float* red = reinterpret_cast<float*>(smem_raw);   // reused after the MFMA loop
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int nt = blockIdx.x;
   const int K = p.K, B = p.B;
   const int k_tiles = K / 16;
@@ -73,86 +101,15 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_kernel(DecGemmArgs p) {
     wf[u] = (kb + u < ke) ? *reinterpret_cast<const half8*>(wp + (size_t)(kb + u) * 512) : z;
   }
 
-  // 2. prologue: build the fp16 A tile [MT * 32, kslice] in LDS
-  if constexpr (PRO == PRO_LN) {
-    const int chunks = K / 8;
-    for (int r = wave; r < MT * 32; r += NW) {
-      RowRegs<RC> v;
-      if (r < B) {
-#pragma unroll
-        for (int c = 0; c < RC; ++c) {
-          const int ch = c * 64 + lane;
-          if (ch < chunks) {
-            const half8 rs = *reinterpret_cast<const half8*>(p.res + (size_t)r * K + ch * 8);
-            const float4 b0 = *reinterpret_cast<const float4*>(p.bias + ch * 8);
-            const float4 b1 = *reinterpret_cast<const float4*>(p.bias + ch * 8 + 4);
-            float a[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-            for (int s = 0; s < p.sk_in; ++s) {
-              const float* src = p.r32 + ((size_t)s * B + r) * K + ch * 8;
-              const float4 x0 = *reinterpret_cast<const float4*>(src);
-              const float4 x1 = *reinterpret_cast<const float4*>(src + 4);
-              a[0] += x0.x; a[1] += x0.y; a[2] += x0.z; a[3] += x0.w;
-              a[4] += x1.x; a[5] += x1.y; a[6] += x1.z; a[7] += x1.w;
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v.v[c][j] = a[j] + (float)rs[j];
-          }
-        }
-        float s = 0.f;
-#pragma unroll
-        for (int c = 0; c < RC; ++c)
-          if (c * 64 + lane < chunks)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) s += v.v[c][j];
-        const float mean = wave_sum(s) / (float)K;
-        float q = 0.f;
-#pragma unroll
-        for (int c = 0; c < RC; ++c)
-          if (c * 64 + lane < chunks)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) { const float t = v.v[c][j] - mean; q += t * t; }
-        const float rstd = rsqrtf(wave_sum(q) / (float)K + p.eps);
-        const bool writer = p.xout && blockIdx.x == 0 && blockIdx.y == 0;
-#pragma unroll
-        for (int c = 0; c < RC; ++c) {
-          const int ch = c * 64 + lane;
-          if (ch < chunks) {
-            half8 o;
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-              o[j] = (half_t)((v.v[c][j] - mean) * rstd * p.gamma[ch * 8 + j] + p.beta[ch * 8 + j]);
-            const int kk = ch * 8 - k0;
-            if (kk >= 0 && kk < kslice) *reinterpret_cast<half8*>(sA + r * pitch + kk) = o;
-            if (writer) *reinterpret_cast<half8*>(p.xout + (size_t)r * K + ch * 8) = o;
-          }
-        }
-      } else {
-        for (int kk = lane * 8; kk < kslice; kk += 512) {
-          const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-          *reinterpret_cast<half8*>(sA + r * pitch + kk) = z;
-        }
-      }
-    }
-  } else {
+  // 2. prologue: copy the fp16 A tile [MT * 32, kslice] into LDS (rows >= B re-read row B-1; their
+  //    products land in accumulator rows that are never stored)
+  {
     const int chunks = kslice / 8;
     for (int id = tid; id < MT * 32 * chunks; id += NW * 64) {
       const int r = id / chunks, ch = id - r * chunks;
-      half8 o = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (r < B) {
-        if constexpr (PRO == PRO_PLAIN) {
-          o = *reinterpret_cast<const half8*>(p.a16 + (size_t)r * K + k0 + ch * 8);
-        } else {
-          const float* src = p.r32 + (size_t)r * K + k0 + ch * 8;
-          const float* bs = p.bias + k0 + ch * 8;
-          const float4 x0 = *reinterpret_cast<const float4*>(src), x1 = *reinterpret_cast<const float4*>(src + 4);
-          const float4 b0 = *reinterpret_cast<const float4*>(bs), b1 = *reinterpret_cast<const float4*>(bs + 4);
-          o[0] = (half_t)gelu_erf(x0.x + b0.x); o[1] = (half_t)gelu_erf(x0.y + b0.y);
-          o[2] = (half_t)gelu_erf(x0.z + b0.z); o[3] = (half_t)gelu_erf(x0.w + b0.w);
-          o[4] = (half_t)gelu_erf(x1.x + b1.x); o[5] = (half_t)gelu_erf(x1.y + b1.y);
-          o[6] = (half_t)gelu_erf(x1.z + b1.z); o[7] = (half_t)gelu_erf(x1.w + b1.w);
-        }
-      }
-      *reinterpret_cast<half8*>(sA + r * pitch + ch * 8) = o;
+      const int rr = min(r, B - 1);
+      *reinterpret_cast<half8*>(sA + r * pitch + ch * 8) =
+          *reinterpret_cast<const half8*>(p.a16 + (size_t)rr * K + k0 + ch * 8);
     }
   }
   __syncthreads();
@@ -200,24 +157,145 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_kernel(DecGemmArgs p) {
     float s = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) s += red[((w * MT + m) * 16 + v) * 64 + lane];
-    const int row = m * 32 + mfma32_row(v, lane);
-    if constexpr (EPI == EPI_RAW) {
-      if (row < B && col < p.N) p.rout[((size_t)blockIdx.y * B + row) * p.N + col] = s;
-    } else {
-      if (p.logits_out && row < B && col < p.N) p.logits_out[(size_t)row * p.N + col] = s;
-      float bv = (col < p.N) ? s : -INFINITY;
-      int bi = col;
+    dec_epilogue<EPI>(p, nt, lane, m * 32 + mfma32_row(v, lane), col, s);
+  }
+}
+
+// A = LayerNorm(sum_k partial_k + bias + residual), normalised in the prologue.
+// grid = (column strips, 1, ceil(B / NW)): a workgroup owns NW batch rows (one per
+// wave) of one 32-column strip, so the redundant normalisation work per workgroup
+// is NW rows, not the whole batch; the row groups of a strip read the same weight
+// fragments (from L2 after the first).  The MFMA tile is fed rows 0..NW-1 repeated;
+// only accumulator rows < NW are reduced and stored.
+template <int NW, int EPI, int RC>
+__global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
+  static_assert(NW == 8, "row groups are 8 rows: accumulator registers 0..3 of each half-wave");
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  half_t* sA = reinterpret_cast<half_t*>(smem_raw);            // [NW][K + 8]
+  float* red = reinterpret_cast<float*>(smem_raw);             // [NW][4][64], reused after the MFMA loop
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nt = blockIdx.x;
+  const int K = p.K, B = p.B;
+  const int k_tiles = K / 16;
+  const int pitch = K + 8;
+  const int kb = k_tiles * wave / NW, ke = k_tiles * (wave + 1) / NW;
+  const int row0 = blockIdx.z * NW;
+
+  const half_t* wp = p.Wp + packed_frag_offset(nt, 0, k_tiles) + lane * 8;
+  half8 wf[kDecMaxFrag];
 #pragma unroll
-      for (int o = 16; o > 0; o >>= 1) {
-        const float ov = __shfl_xor(bv, o, 64);
-        const int oi = __shfl_xor(bi, o, 64);
-        argmax_merge(bv, bi, ov, oi);
+  for (int u = 0; u < kDecMaxFrag; ++u) {
+    const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+    wf[u] = (kb + u < ke) ? *reinterpret_cast<const half8*>(wp + (size_t)(kb + u) * 512) : z;
+  }
+
+  // prologue: wave w normalises row row0 + w.  Loads are unconditional with clamped addresses (a row
+  // >= B or a chunk past the row end re-reads a valid location and is masked): predicated loads would
+  // be issued one at a time.
+  {
+    const int chunks = K / 8;
+    const int r = row0 + wave;
+    const int rr = min(r, B - 1);
+    float v[RC][8], g[RC][8], bt[RC][8];
+    const float* src[RC];
+#pragma unroll
+    for (int c = 0; c < RC; ++c) {
+      const int cc = min(c * 64 + lane, chunks - 1);
+      src[c] = p.r32 + (size_t)rr * K + cc * 8;
+      const half8 rs = *reinterpret_cast<const half8*>(p.res + (size_t)rr * K + cc * 8);
+      const float4 x0 = *reinterpret_cast<const float4*>(src[c]);
+      const float4 x1 = *reinterpret_cast<const float4*>(src[c] + 4);
+      const float4 b0 = *reinterpret_cast<const float4*>(p.bias + cc * 8);
+      const float4 b1 = *reinterpret_cast<const float4*>(p.bias + cc * 8 + 4);
+      const float4 g0 = *reinterpret_cast<const float4*>(p.gamma + cc * 8);
+      const float4 g1 = *reinterpret_cast<const float4*>(p.gamma + cc * 8 + 4);
+      const float4 t0 = *reinterpret_cast<const float4*>(p.beta + cc * 8);
+      const float4 t1 = *reinterpret_cast<const float4*>(p.beta + cc * 8 + 4);
+      v[c][0] = x0.x + b0.x + (float)rs[0]; v[c][1] = x0.y + b0.y + (float)rs[1];
+      v[c][2] = x0.z + b0.z + (float)rs[2]; v[c][3] = x0.w + b0.w + (float)rs[3];
+      v[c][4] = x1.x + b1.x + (float)rs[4]; v[c][5] = x1.y + b1.y + (float)rs[5];
+      v[c][6] = x1.z + b1.z + (float)rs[6]; v[c][7] = x1.w + b1.w + (float)rs[7];
+      g[c][0] = g0.x; g[c][1] = g0.y; g[c][2] = g0.z; g[c][3] = g0.w;
+      g[c][4] = g1.x; g[c][5] = g1.y; g[c][6] = g1.z; g[c][7] = g1.w;
+      bt[c][0] = t0.x; bt[c][1] = t0.y; bt[c][2] = t0.z; bt[c][3] = t0.w;
+      bt[c][4] = t1.x; bt[c][5] = t1.y; bt[c][6] = t1.z; bt[c][7] = t1.w;
+    }
+    for (int s = 1; s < p.sk_in; ++s) {          // further split-K partials, added in index order
+      const size_t off = (size_t)s * B * K;
+      float4 x0[RC], x1[RC];
+#pragma unroll
+      for (int c = 0; c < RC; ++c) {
+        x0[c] = *reinterpret_cast<const float4*>(src[c] + off);
+        x1[c] = *reinterpret_cast<const float4*>(src[c] + off + 4);
       }
-      if ((lane & 31) == 0 && row < B) {
-        p.strip_val[(size_t)row * p.strips + nt] = bv;
-        p.strip_idx[(size_t)row * p.strips + nt] = bi;
+#pragma unroll
+      for (int c = 0; c < RC; ++c) {
+        v[c][0] += x0[c].x; v[c][1] += x0[c].y; v[c][2] += x0[c].z; v[c][3] += x0[c].w;
+        v[c][4] += x1[c].x; v[c][5] += x1[c].y; v[c][6] += x1[c].z; v[c][7] += x1[c].w;
       }
     }
+    float sum = 0.f;
+#pragma unroll
+    for (int c = 0; c < RC; ++c) {
+      const float live = (c * 64 + lane < chunks) ? 1.f : 0.f;   // the duplicated tail chunk stays out of the sums
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { v[c][j] *= live; sum += v[c][j]; }
+    }
+    const float mean = wave_sum(sum) / (float)K;
+    float q = 0.f;
+#pragma unroll
+    for (int c = 0; c < RC; ++c) {
+      const float live = (c * 64 + lane < chunks) ? 1.f : 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { const float t = (v[c][j] - mean) * live; q += t * t; }
+    }
+    const float rstd = rsqrtf(wave_sum(q) / (float)K + p.eps);
+    const bool writer = p.xout && blockIdx.x == 0 && r < B;
+#pragma unroll
+    for (int c = 0; c < RC; ++c) {
+      const int ch = c * 64 + lane;
+      if (ch < chunks) {
+        half8 o;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = (half_t)((v[c][j] - mean) * rstd * g[c][j] + bt[c][j]);
+        *reinterpret_cast<half8*>(sA + wave * pitch + ch * 8) = o;
+        if (writer) *reinterpret_cast<half8*>(p.xout + (size_t)r * K + ch * 8) = o;
+      }
+    }
+  }
+  __syncthreads();
+
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  const half_t* ap = sA + (lane & 7) * pitch + 8 * (lane >> 5);    // tile rows 8..31 repeat rows 0..7
+  for (int base = kb; base < ke; base += kDecMaxFrag) {
+#pragma unroll
+    for (int u = 0; u < kDecMaxFrag; ++u)
+      if (base + u < ke) acc = mfma32(*reinterpret_cast<const half8*>(ap + (base + u) * 16), wf[u], acc);
+    if (base + kDecMaxFrag < ke) {
+#pragma unroll
+      for (int u = 0; u < kDecMaxFrag; ++u) {
+        const int kt = base + kDecMaxFrag + u;
+        const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+        wf[u] = (kt < ke) ? *reinterpret_cast<const half8*>(wp + (size_t)kt * 512) : z;
+      }
+    }
+  }
+  __syncthreads();
+
+  // accumulator registers 0..3 hold tile rows 4 * (lane / 32) + v, i.e. the NW = 8 real rows
+#pragma unroll
+  for (int v = 0; v < 4; ++v) red[(wave * 4 + v) * 64 + lane] = acc[v];
+  __syncthreads();
+  if (wave < 4) {
+    const int v = wave;
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s += red[(w * 4 + v) * 64 + lane];
+    dec_epilogue<EPI>(p, nt, lane, row0 + 4 * (lane >> 5) + v, nt * 32 + (lane & 31), s);
   }
 }
 

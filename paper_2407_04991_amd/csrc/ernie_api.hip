@@ -41,7 +41,7 @@ struct ArenaPlan {
   size_t tok_rm, tok_p, pos, emb_g, emb_b, kept;
   struct L { size_t wqkv, wo, w1, w2, bqkv, bo, b1, b2, ln1_g, ln1_b, ln2_g, ln2_b; };
   std::vector<L> layers;
-  size_t r_qkv, r_out, r_f1, r_f2;
+  size_t r_qkv, r_out, r_f2;
   size_t kv, X, X1, Y, Q, O, G, Yf, hlast, strip_val, strip_idx, cu, lens, tok_seq, tok_pos, tok_prev;
   size_t total;
   int vocab_tiles, strips;
@@ -76,7 +76,7 @@ ArenaPlan make_plan(const ErnieConfig& c) {
   p.Yf = take(Bm * d * 4);
   const size_t Bf = Bm < (size_t)kFusedMaxBatch ? Bm : (size_t)kFusedMaxBatch;
   p.r_qkv = take(Bf * 3 * d * 4); p.r_out = take(kMaxSplitK * Bf * d * 4);
-  p.r_f1 = take(Bf * f * 4); p.r_f2 = take(kMaxSplitK * Bf * d * 4);
+  p.r_f2 = take(kMaxSplitK * Bf * d * 4);
   p.hlast = take(Bm * d * 2);
   p.strip_val = take(Bm * p.strips * 4); p.strip_idx = take(Bm * p.strips * 4);
   p.cu = take((Bm + 1) * 4); p.lens = take(Bm * 4);
@@ -107,7 +107,7 @@ struct ErnieHandle {
   float *emb_g, *emb_b;
   std::vector<LayerPtrs> layers;
   half_t *kv, *X, *X1, *Y, *Q, *O, *G, *hlast;
-  float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2;
+  float *Yf, *strip_val, *r_qkv, *r_out, *r_f2;
   int sk_out, sk_f2, fused_decode;   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   int* staging;          // pinned host: kStagingSlots x (max_batch + 1) ints
@@ -190,6 +190,10 @@ int configure_kernels() {
   rc |= allow_lds(gemm_skinny_kernel<8, 4, SkinnyResidual>, big);
   rc |= allow_lds(gemm_skinny_kernel<8, 4, SkinnyGelu>, big);
   rc |= allow_lds(logits_argmax_kernel<8, 4>, big);
+  rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_RAW>, kMaxLds);
+  rc |= allow_lds(gemm_dec_kernel<2, 8, EPI_RAW>, kMaxLds);
+  rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_ARGMAX>, kMaxLds);
+  rc |= allow_lds(gemm_dec_kernel<2, 8, EPI_ARGMAX>, kMaxLds);
   return rc ? ERNIE_EHIP : ERNIE_OK;
 }
 
@@ -212,7 +216,7 @@ size_t dec_lds_bytes(int MT, int NW, int kslice) {
   return a > r ? a : r;
 }
 
-template <int PRO, int EPI>
+template <int EPI>
 int launch_gemm_dec(DecGemmArgs a, int sk, hipStream_t s) {
   constexpr int NW = 8;
   const int MT = (a.B + 31) / 32;
@@ -220,21 +224,24 @@ int launch_gemm_dec(DecGemmArgs a, int sk, hipStream_t s) {
   const size_t lds = dec_lds_bytes(MT, NW, kslice);
   if (MT > 2 || lds > kMaxLds || (a.K / 16) % sk != 0) return ERNIE_EINVAL;
   const dim3 grid((a.N + 31) / 32, sk), block(NW * 64);
-  if constexpr (PRO == PRO_LN) {
-    const int d = a.K;
-    if (MT == 1) ROW_DISPATCH(d, hipLaunchKernelGGL((gemm_dec_kernel<1, NW, PRO, EPI, RC>), grid, block, lds, s, a));
-    else ROW_DISPATCH(d, hipLaunchKernelGGL((gemm_dec_kernel<2, NW, PRO, EPI, RC>), grid, block, lds, s, a));
-  } else {
-    if (MT == 1) hipLaunchKernelGGL((gemm_dec_kernel<1, NW, PRO, EPI, 2>), grid, block, lds, s, a);
-    else hipLaunchKernelGGL((gemm_dec_kernel<2, NW, PRO, EPI, 2>), grid, block, lds, s, a);
-  }
+  if (MT == 1) hipLaunchKernelGGL((gemm_dec_kernel<1, NW, EPI>), grid, block, lds, s, a);
+  else hipLaunchKernelGGL((gemm_dec_kernel<2, NW, EPI>), grid, block, lds, s, a);
   return ERNIE_OK;
 }
 
+template <int EPI>
+int launch_gemm_dec_ln(DecGemmArgs a, hipStream_t s) {
+  constexpr int NW = 8;
+  if (a.K > 1024) return ERNIE_EINVAL;                 // the LayerNorm prologue holds rows of <= 1024 features
+  const size_t lds = (size_t)NW * (a.K + 8) * 2;      // >= the 8 KiB the reduction reuses
+  const dim3 grid((a.N + 31) / 32, 1, (a.B + NW - 1) / NW), block(NW * 64);
+  hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2>), grid, block, lds < 8192 ? 8192 : lds, s, a);
+  return ERNIE_OK;
+}
 
 // Small batches: every GEMM input fits in LDS, row-wise work lives in consumer prologues (5 launches per layer).
 bool fused_decode_fits(const ErnieHandle* h, int B) {
-  if (!h->fused_decode || B > kFusedMaxBatch) return false;
+  if (!h->fused_decode || B > kFusedMaxBatch || h->cfg.d_model > 1024) return false;
   const int MT = (B + 31) / 32, d = h->cfg.d_model, f = h->cfg.d_ffn;
   return dec_lds_bytes(MT, 8, d) <= kMaxLds && dec_lds_bytes(MT, 8, f / h->sk_f2) <= kMaxLds &&
          (d / 16) % h->sk_out == 0 && (f / 16) % h->sk_f2 == 0;
@@ -252,25 +259,26 @@ int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hi
     a.Wp = L.wqkv; a.N = 3 * d; a.K = d; a.rout = h->r_qkv;
     if (l == 0) {
       a.a16 = h->X;
-      rc |= launch_gemm_dec<PRO_PLAIN, EPI_RAW>(a, 1, s);
+      rc |= launch_gemm_dec<EPI_RAW>(a, 1, s);
     } else {
       const LayerPtrs& P = h->layers[l - 1];
       a.r32 = h->r_f2; a.sk_in = h->sk_f2; a.bias = P.b2; a.res = h->X1; a.gamma = P.ln2_g; a.beta = P.ln2_b;
       a.xout = h->X;
-      rc |= launch_gemm_dec<PRO_LN, EPI_RAW>(a, 1, s);
+      rc |= launch_gemm_dec_ln<EPI_RAW>(a, s);
     }
     hipLaunchKernelGGL(attn_decode_fused_kernel, dim3(H, B), dim3(256), 0, s, h->r_qkv, L.bqkv, kcache(h, l),
                        vcache(h, l), h->lens, H, S, d, h->O);
     DecGemmArgs o{};
     o.B = B; o.Wp = L.wo; o.N = d; o.K = d; o.a16 = h->O; o.rout = h->r_out;
-    rc |= launch_gemm_dec<PRO_PLAIN, EPI_RAW>(o, h->sk_out, s);
+    rc |= launch_gemm_dec<EPI_RAW>(o, h->sk_out, s);
     DecGemmArgs f1{};
     f1.B = B; f1.eps = c.ln_eps; f1.Wp = L.w1; f1.N = f; f1.K = d; f1.r32 = h->r_out; f1.sk_in = h->sk_out;
-    f1.bias = L.bo; f1.res = h->X; f1.gamma = L.ln1_g; f1.beta = L.ln1_b; f1.xout = h->X1; f1.rout = h->r_f1;
-    rc |= launch_gemm_dec<PRO_LN, EPI_RAW>(f1, 1, s);
+    f1.bias = L.bo; f1.res = h->X; f1.gamma = L.ln1_g; f1.beta = L.ln1_b; f1.xout = h->X1;
+    f1.bias_out = L.b1; f1.g16 = h->G;
+    rc |= launch_gemm_dec_ln<EPI_GELU16>(f1, s);
     DecGemmArgs f2{};
-    f2.B = B; f2.Wp = L.w2; f2.N = d; f2.K = f; f2.r32 = h->r_f1; f2.sk_in = 1; f2.bias = L.b1; f2.rout = h->r_f2;
-    rc |= launch_gemm_dec<PRO_GELU, EPI_RAW>(f2, h->sk_f2, s);
+    f2.B = B; f2.Wp = L.w2; f2.N = d; f2.K = f; f2.a16 = h->G; f2.rout = h->r_f2;
+    rc |= launch_gemm_dec<EPI_RAW>(f2, h->sk_f2, s);
   }
   const LayerPtrs& P = h->layers[c.n_layers - 1];
   ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_f2, h->sk_f2, P.b2, h->X1, B, d,
@@ -278,7 +286,7 @@ int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hi
   DecGemmArgs z{};
   z.B = B; z.Wp = h->tok_p; z.N = c.vocab_kept; z.K = d; z.a16 = h->X; z.logits_out = logits_out;
   z.strip_val = h->strip_val; z.strip_idx = h->strip_idx; z.strips = h->plan.strips;
-  rc |= launch_gemm_dec<PRO_PLAIN, EPI_ARGMAX>(z, 1, s);
+  rc |= launch_gemm_dec<EPI_ARGMAX>(z, 1, s);
   return rc ? ERNIE_EHIP : ERNIE_OK;
 }
 
@@ -365,7 +373,7 @@ int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* w, void* aren
   h->kv = H16(plan.kv); h->X = H16(plan.X); h->X1 = H16(plan.X1); h->Y = H16(plan.Y); h->Q = H16(plan.Q);
   h->O = H16(plan.O); h->G = H16(plan.G); h->hlast = H16(plan.hlast);
   h->Yf = F32(plan.Yf); h->strip_val = F32(plan.strip_val);
-  h->r_qkv = F32(plan.r_qkv); h->r_out = F32(plan.r_out); h->r_f1 = F32(plan.r_f1); h->r_f2 = F32(plan.r_f2);
+  h->r_qkv = F32(plan.r_qkv); h->r_out = F32(plan.r_out); h->r_f2 = F32(plan.r_f2);
   h->fused_decode = 1;
   h->sk_out = pick_split_k(cfg->d_model / 32, cfg->d_model / 16, 2);
   h->sk_f2 = pick_split_k(cfg->d_model / 32, cfg->d_ffn / 16, 4);

@@ -74,7 +74,8 @@ __global__ __launch_bounds__(256) void gemm_prefill_kernel(const half_t* __restr
   half_t* sA = reinterpret_cast<half_t*>(smem_raw);
   half_t* sB = sA + 2 * kGemmAStage;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int wm = wave >> 1, wn = wave & 1;
   const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
   const int m0 = tile_m * kGemmBM, n0 = tile_n * kGemmBN;

@@ -65,7 +65,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_skinny_kernel(const half_t* __re
   extern __shared__ __align__(16) unsigned char smem_raw[];
   float* red = reinterpret_cast<float*>(smem_raw);   // [NW][MT][16][64]
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
   const int nt = blockIdx.x;
   const int k_tiles = K / 16;
   // balanced contiguous split of the k-tiles over the waves
@@ -144,7 +145,8 @@ __global__ __launch_bounds__(NW * 64) void logits_argmax_kernel(const half_t* __
   extern __shared__ __align__(16) unsigned char smem_raw[];
   float* red = reinterpret_cast<float*>(smem_raw);
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
   const int nt = blockIdx.x;
   const int k_tiles = K / 16;
   const int kb = (int)(((long long)k_tiles * wave) / NW);
