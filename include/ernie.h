@@ -159,6 +159,32 @@ void ernie_free(ErnieHandle* h);
 int ernie_debug_buffer(ErnieHandle* h, const char* name, void** ptr_dev, size_t* bytes);
 
 /*
+ * ernie_profile / ernie_profile_read -- measurement hooks (not part of the hot path).
+ *
+ * ernie_profile(h, 1) switches per-kernel timing on and clears the counters: from then on every
+ * launch of the categories below is bracketed by HIP events recorded on the stream it is launched
+ * on (events are created on the first enable; up to 8192 launches are recorded, later ones are not
+ * timed).  Do not capture profiled calls into a graph.  ernie_profile(h, 0) switches it off.
+ * ernie_profile_read waits for the recorded events of one category and returns the summed device
+ * time between each pair, the number of launches, and the algorithmic bytes and flops of those
+ * launches: weight bytes N*K*2 for the decode GEMMs and the output projection, K and V bytes of all
+ * visible positions for decode attention, 2*M*N*K flops for GEMMs and 4*sum(L_b^2)*d for prefill
+ * attention.
+ */
+#define ERNIE_PROF_GEMM_DEC      0   /* decode GEMM on fp16 activations (attention output, FFN2, layer-0 QKV) */
+#define ERNIE_PROF_GEMM_DEC_LN   1   /* decode GEMM with the LayerNorm prologue (QKV, FFN1) */
+#define ERNIE_PROF_ATTN_DEC      2   /* decode attention over the key/value cache */
+#define ERNIE_PROF_GEMM_PREFILL  3   /* prefill MFMA GEMMs */
+#define ERNIE_PROF_ATTN_PREFILL  4   /* prefill attention */
+#define ERNIE_PROF_LOGITS        5   /* output projection + first argmax stage (decode, small-batch path) */
+#define ERNIE_PROF_ROW_DEC       6   /* decode row kernels: embedding + LayerNorm, final LayerNorm, second argmax stage */
+#define ERNIE_PROF_ROW_PREFILL   7   /* prefill row kernels: token map, embedding + LayerNorm, LayerNorm, last-row gather, argmax */
+#define ERNIE_PROF_NCAT          8
+int ernie_profile(ErnieHandle* h, int enable);
+int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* launches,
+                       double* alg_bytes, double* alg_flops);
+
+/*
  * ernie_debug_tune -- test hook: override a decode-path tuning knob of this handle.
  *   "fused_decode" 0/1  use the small-batch path (row-wise work fused into GEMM prologues) when it fits
  *   "sk_out", "sk_f2"   split of the contraction of the attention-output / second FFN GEMM over workgroups

@@ -20,7 +20,11 @@ LIB_PATH = os.path.join(_PKG, "libernie_hip.so")
 ERNIE_OK, ERNIE_EINVAL, ERNIE_ECAPACITY, ERNIE_EARENA, ERNIE_ESEQUENCE, ERNIE_EHIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("ernie_init_weights", "ernie_prefill", "ernie_decode_step", "ernie_free",
-           "ernie_debug_buffer", "ernie_debug_tune", "ernie_error_string")
+           "ernie_debug_buffer", "ernie_debug_tune", "ernie_profile", "ernie_profile_read",
+           "ernie_error_string")
+
+PROF_CATEGORIES = ("gemm_dec", "gemm_dec_ln", "attn_dec", "gemm_prefill", "attn_prefill", "logits",
+                   "row_dec", "row_prefill")
 
 
 class ErnieConfig(C.Structure):
@@ -72,6 +76,11 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ernie_debug_buffer.argtypes = [C.c_void_p, C.c_char_p, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]
     lib.ernie_debug_tune.restype = C.c_int
     lib.ernie_debug_tune.argtypes = [C.c_void_p, C.c_char_p, C.c_int]
+    lib.ernie_profile.restype = C.c_int
+    lib.ernie_profile.argtypes = [C.c_void_p, C.c_int]
+    lib.ernie_profile_read.restype = C.c_int
+    lib.ernie_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64),
+                                       C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.ernie_error_string.restype = C.c_char_p
     lib.ernie_error_string.argtypes = [C.c_int]
     if path is None:
@@ -212,6 +221,22 @@ class ErnieEngine:
         if rc != ERNIE_OK:
             raise ErnieError(rc, "ernie_debug_buffer")
         return ptr.value, n.value
+
+    def profile(self, enable: bool):
+        rc = load_library().ernie_profile(self.handle, int(bool(enable)))
+        if rc != ERNIE_OK:
+            raise ErnieError(rc, "ernie_profile")
+
+    def profile_read(self) -> dict:
+        """{category: (total_ms, launches, algorithmic bytes, algorithmic flops)} of the profiled launches."""
+        out = {}
+        for i, name in enumerate(PROF_CATEGORIES):
+            ms, n, by, fl = C.c_double(0), C.c_int64(0), C.c_double(0), C.c_double(0)
+            rc = load_library().ernie_profile_read(self.handle, i, C.byref(ms), C.byref(n), C.byref(by), C.byref(fl))
+            if rc != ERNIE_OK:
+                raise ErnieError(rc, "ernie_profile_read")
+            out[name] = (ms.value, n.value, by.value, fl.value)
+        return out
 
     def tune(self, key: str, value: int):
         rc = load_library().ernie_debug_tune(self.handle, key.encode(), int(value))

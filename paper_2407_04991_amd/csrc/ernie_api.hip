@@ -99,8 +99,21 @@ int check_config(const ErnieConfig* c) {
 
 }  // namespace
 
+
+// Optional per-kernel timing (ernie_profile): HIP events recorded on the caller's stream
+// around every launch of a category, plus the algorithmic bytes / flops of those launches.
+struct ProfSlot { hipEvent_t a, b; int cat; };
+struct Profiler {
+  bool on = false;
+  std::vector<ProfSlot> slots;
+  size_t used = 0;
+  double bytes[ERNIE_PROF_NCAT] = {0}, flops[ERNIE_PROF_NCAT] = {0};
+};
+
 struct ErnieHandle {
   ErnieConfig cfg;
+  Profiler prof;
+  double sum_len, sum_len2;   // over the batch in flight: sum of prompt lengths and of their squares
   ArenaPlan plan;
   unsigned char* arena;
   half_t *tok_rm, *tok_p, *pos;
@@ -122,6 +135,20 @@ namespace {
 // Row-kernel instantiation by model width: RC chunks of 512 features per wave.
 #define ROW_DISPATCH(d, CALL) do { if ((d) <= 1024) { constexpr int RC = 2; CALL; } else if ((d) <= 2048) { constexpr int RC = 4; CALL; } else { constexpr int RC = 8; CALL; } } while (0)
 
+// Brackets one launch with events when profiling is on (no-op otherwise).
+struct ProfScope {
+  ErnieHandle* h; hipStream_t s; long idx;
+  ProfScope(ErnieHandle* h_, int cat, hipStream_t s_, double bytes, double flops) : h(h_), s(s_), idx(-1) {
+    Profiler& p = h->prof;
+    if (!p.on || p.used >= p.slots.size()) return;
+    idx = (long)p.used++;
+    p.slots[idx].cat = cat;
+    p.bytes[cat] += bytes; p.flops[cat] += flops;
+    (void)hipEventRecord(p.slots[idx].a, s);
+  }
+  ~ProfScope() { if (idx >= 0) (void)hipEventRecord(h->prof.slots[idx].b, s); }
+};
+
 #define HIP_OK(expr) do { if ((expr) != hipSuccess) return ERNIE_EHIP; } while (0)
 
 int launch_status() { return hipGetLastError() == hipSuccess ? ERNIE_OK : ERNIE_EHIP; }
@@ -136,8 +163,9 @@ half_t* vcache(const ErnieHandle* h, int layer) {
 }
 
 template <class Epi>
-void launch_gemm_prefill(const half_t* A, const half_t* Wp, const float* bias, int M, int N, int K, Epi epi,
-                         hipStream_t s) {
+void launch_gemm_prefill(ErnieHandle* h, const half_t* A, const half_t* Wp, const float* bias, int M, int N, int K,
+                         Epi epi, hipStream_t s) {
+  ProfScope prof(h, ERNIE_PROF_GEMM_PREFILL, s, 0.0, 2.0 * M * N * K);
   const int tiles_m = (M + kGemmBM - 1) / kGemmBM, tiles_n = (N + kGemmBN - 1) / kGemmBN;
   hipLaunchKernelGGL(gemm_prefill_kernel<Epi>, dim3(tiles_m * tiles_n), dim3(256), kGemmLdsBytes, s, A, Wp, bias, M,
                      N, K, (N + 31) / 32, tiles_n, epi);
@@ -160,13 +188,13 @@ void launch_skinny(const half_t* X, const half_t* Wp, const float* bias, int B, 
 }
 
 template <int MT, int NW>
-void launch_logits_t(const ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s) {
+void launch_logits_t(ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s) {
   const size_t lds = (size_t)NW * MT * 16 * 64 * 4;
   hipLaunchKernelGGL((logits_argmax_kernel<MT, NW>), dim3(h->plan.strips), dim3(NW * 64), lds, s, X, h->tok_p, B,
                      h->cfg.vocab_kept, h->cfg.d_model, logits_out, h->strip_val, h->strip_idx, h->plan.strips);
 }
 
-void launch_logits(const ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s) {
+void launch_logits(ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s) {
   if (B <= 32) launch_logits_t<1, 4>(h, X, B, logits_out, s);
   else if (B <= 64) launch_logits_t<2, 4>(h, X, B, logits_out, s);
   else if (B <= 128) launch_logits_t<4, 4>(h, X, B, logits_out, s);
@@ -217,8 +245,9 @@ size_t dec_lds_bytes(int MT, int NW, int kslice) {
 }
 
 template <int EPI>
-int launch_gemm_dec(DecGemmArgs a, int sk, hipStream_t s) {
+int launch_gemm_dec(ErnieHandle* h, DecGemmArgs a, int sk, hipStream_t s) {
   constexpr int NW = 8;
+  ProfScope prof(h, EPI == EPI_ARGMAX ? ERNIE_PROF_LOGITS : ERNIE_PROF_GEMM_DEC, s, 2.0 * a.N * a.K, 2.0 * a.B * a.N * a.K);
   const int MT = (a.B + 31) / 32;
   const int kslice = a.K / sk;
   const size_t lds = dec_lds_bytes(MT, NW, kslice);
@@ -230,8 +259,9 @@ int launch_gemm_dec(DecGemmArgs a, int sk, hipStream_t s) {
 }
 
 template <int EPI>
-int launch_gemm_dec_ln(DecGemmArgs a, hipStream_t s) {
+int launch_gemm_dec_ln(ErnieHandle* h, DecGemmArgs a, hipStream_t s) {
   constexpr int NW = 8;
+  ProfScope prof(h, ERNIE_PROF_GEMM_DEC_LN, s, 2.0 * a.N * a.K, 2.0 * a.B * a.N * a.K);
   if (a.K > 1024) return ERNIE_EINVAL;                 // the LayerNorm prologue holds rows of <= 1024 features
   const size_t lds = (size_t)NW * (a.K + 8) * 2;      // >= the 8 KiB the reduction reuses
   const dim3 grid((a.N + 31) / 32, 1, (a.B + NW - 1) / NW), block(NW * 64);
@@ -259,34 +289,38 @@ int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hi
     a.Wp = L.wqkv; a.N = 3 * d; a.K = d; a.rout = h->r_qkv;
     if (l == 0) {
       a.a16 = h->X;
-      rc |= launch_gemm_dec<EPI_RAW>(a, 1, s);
+      rc |= launch_gemm_dec<EPI_RAW>(h, a, 1, s);
     } else {
       const LayerPtrs& P = h->layers[l - 1];
       a.r32 = h->r_f2; a.sk_in = h->sk_f2; a.bias = P.b2; a.res = h->X1; a.gamma = P.ln2_g; a.beta = P.ln2_b;
       a.xout = h->X;
-      rc |= launch_gemm_dec_ln<EPI_RAW>(a, s);
+      rc |= launch_gemm_dec_ln<EPI_RAW>(h, a, s);
     }
-    hipLaunchKernelGGL(attn_decode_fused_kernel, dim3(H, B), dim3(256), 0, s, h->r_qkv, L.bqkv, kcache(h, l),
-                       vcache(h, l), h->lens, H, S, d, h->O);
+    {
+      // K and V of every visible position (cached + the appended one), 2 bytes each
+      ProfScope prof(h, ERNIE_PROF_ATTN_DEC, s, 2.0 * (h->sum_len + (double)B * (h->steps + 1)) * d * 2.0, 0.0);
+      hipLaunchKernelGGL(attn_decode_fused_kernel, dim3(H, B), dim3(256), 0, s, h->r_qkv, L.bqkv, kcache(h, l),
+                         vcache(h, l), h->lens, H, S, d, h->O);
+    }
     DecGemmArgs o{};
     o.B = B; o.Wp = L.wo; o.N = d; o.K = d; o.a16 = h->O; o.rout = h->r_out;
-    rc |= launch_gemm_dec<EPI_RAW>(o, h->sk_out, s);
+    rc |= launch_gemm_dec<EPI_RAW>(h, o, h->sk_out, s);
     DecGemmArgs f1{};
     f1.B = B; f1.eps = c.ln_eps; f1.Wp = L.w1; f1.N = f; f1.K = d; f1.r32 = h->r_out; f1.sk_in = h->sk_out;
     f1.bias = L.bo; f1.res = h->X; f1.gamma = L.ln1_g; f1.beta = L.ln1_b; f1.xout = h->X1;
     f1.bias_out = L.b1; f1.g16 = h->G;
-    rc |= launch_gemm_dec_ln<EPI_GELU16>(f1, s);
+    rc |= launch_gemm_dec_ln<EPI_GELU16>(h, f1, s);
     DecGemmArgs f2{};
     f2.B = B; f2.Wp = L.w2; f2.N = d; f2.K = f; f2.a16 = h->G; f2.rout = h->r_f2;
-    rc |= launch_gemm_dec<EPI_RAW>(f2, h->sk_f2, s);
+    rc |= launch_gemm_dec<EPI_RAW>(h, f2, h->sk_f2, s);
   }
   const LayerPtrs& P = h->layers[c.n_layers - 1];
-  ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_f2, h->sk_f2, P.b2, h->X1, B, d,
-                     P.ln2_g, P.ln2_b, c.ln_eps, h->X, hidden_out));
+  { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_f2, h->sk_f2, P.b2, h->X1, B, d,
+                     P.ln2_g, P.ln2_b, c.ln_eps, h->X, hidden_out)); }
   DecGemmArgs z{};
   z.B = B; z.Wp = h->tok_p; z.N = c.vocab_kept; z.K = d; z.a16 = h->X; z.logits_out = logits_out;
   z.strip_val = h->strip_val; z.strip_idx = h->strip_idx; z.strips = h->plan.strips;
-  rc |= launch_gemm_dec<EPI_ARGMAX>(z, 1, s);
+  rc |= launch_gemm_dec<EPI_ARGMAX>(h, z, 1, s);
   return rc ? ERNIE_EHIP : ERNIE_OK;
 }
 
@@ -298,19 +332,24 @@ int decode_layers_multi(ErnieHandle* h, float* logits_out, float* hidden_out, hi
     const LayerPtrs& L = h->layers[l];
     launch_skinny(h->X, L.wqkv, L.bqkv, B, 3 * d, d, SkinnyQKV{h->Q, kcache(h, l), vcache(h, l), h->lens, d, H, S},
                   s);
-    hipLaunchKernelGGL(attn_decode_kernel, dim3(H, B), dim3(256), 0, s, h->Q, kcache(h, l), vcache(h, l), h->lens, H,
-                       S, d, h->O);
+    {
+      ProfScope prof(h, ERNIE_PROF_ATTN_DEC, s, 2.0 * (h->sum_len + (double)B * (h->steps + 1)) * d * 2.0, 0.0);
+      hipLaunchKernelGGL(attn_decode_kernel, dim3(H, B), dim3(256), 0, s, h->Q, kcache(h, l), vcache(h, l), h->lens, H,
+                         S, d, h->O);
+    }
     launch_skinny(h->O, L.wo, L.bo, B, d, d, SkinnyResidual{h->X, h->Yf, d}, s);
-    ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f32_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->Yf, B, d, L.ln1_g, L.ln1_b,
-                       c.ln_eps, h->X1));
+    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f32_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->Yf, B, d, L.ln1_g, L.ln1_b,
+                       c.ln_eps, h->X1)); }
     launch_skinny(h->X1, L.w1, L.b1, B, f, d, SkinnyGelu{h->G, f}, s);
     launch_skinny(h->G, L.w2, L.b2, B, d, f, SkinnyResidual{h->X1, h->Yf, d}, s);
-    ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f32_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->Yf, B, d, L.ln2_g, L.ln2_b,
-                       c.ln_eps, h->X));
+    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f32_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->Yf, B, d, L.ln2_g, L.ln2_b,
+                       c.ln_eps, h->X)); }
   }
   if (hidden_out)
-    hipLaunchKernelGGL(hidden_to_f32_kernel, dim3((B * d + 255) / 256), dim3(256), 0, s, h->X, B * d, hidden_out);
+    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); hipLaunchKernelGGL(hidden_to_f32_kernel, dim3((B * d + 255) / 256), dim3(256), 0, s, h->X, B * d, hidden_out); }
+  { ProfScope prof(h, ERNIE_PROF_LOGITS, s, 0.0, 0.0);
   launch_logits(h, h->X, B, logits_out, s);
+  }
   return ERNIE_OK;
 }
 
@@ -379,7 +418,7 @@ int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* w, void* aren
   h->sk_f2 = pick_split_k(cfg->d_model / 32, cfg->d_ffn / 16, 4);
   h->strip_idx = I32(plan.strip_idx); h->cu = I32(plan.cu); h->lens = I32(plan.lens);
   h->tok_seq = I32(plan.tok_seq); h->tok_pos = I32(plan.tok_pos); h->tok_prev = I32(plan.tok_prev);
-  h->prefilled = false; h->B = 0; h->max_len = 0; h->steps = 0;
+  h->prefilled = false; h->B = 0; h->max_len = 0; h->steps = 0; h->sum_len = h->sum_len2 = 0.0;
   h->staging = nullptr; h->staging_next = 0;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -430,10 +469,12 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
   const ErnieConfig& c = h->cfg;
   if (B > c.max_batch || Lmax > c.max_seq || Lmax > c.max_pos) return ERNIE_ECAPACITY;
   int max_len = 0;
+  double sum_len = 0.0, sum_len2 = 0.0;
   for (int b = 0; b < B; ++b) {
     const int L = prompt_lens_host[b];
     if (L < 1 || L > Lmax) return ERNIE_EINVAL;
     if (L > max_len) max_len = L;
+    sum_len += L; sum_len2 += (double)L * L;
   }
 
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -445,30 +486,38 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
   HIP_OK(hipMemcpyAsync(h->cu, stage, sizeof(int) * (B + 1), hipMemcpyHostToDevice, s));
 
   const int d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
-  hipLaunchKernelGGL(token_map_kernel, dim3((T + 255) / 256), dim3(256), 0, s, h->cu, B, T, h->tok_seq, h->tok_pos,
-                     h->lens);
-  ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_prefill_kernel<RC>, dim3((T + 3) / 4), dim3(256), 0, s, ids_dev, Lmax, h->tok_seq,
-                     h->tok_pos, T, h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X));
+  { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); hipLaunchKernelGGL(token_map_kernel, dim3((T + 255) / 256), dim3(256), 0, s, h->cu, B, T, h->tok_seq, h->tok_pos,
+                     h->lens); }
+  { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_prefill_kernel<RC>, dim3((T + 3) / 4), dim3(256), 0, s, ids_dev, Lmax, h->tok_seq,
+                     h->tok_pos, T, h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X)); }
   const int q_tiles = (max_len + kAttnQTile - 1) / kAttnQTile;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerPtrs& L = h->layers[l];
     EpiQKV eq{h->Q, kcache(h, l), vcache(h, l), h->tok_seq, h->tok_pos, d, H, S, T};
-    launch_gemm_prefill(h->X, L.wqkv, L.bqkv, T, 3 * d, d, eq, s);
-    hipLaunchKernelGGL(attn_prefill_kernel, dim3(q_tiles, H, B), dim3(256), 0, s, h->Q, kcache(h, l), vcache(h, l),
-                       h->cu, T, H, S, d, h->O);
-    launch_gemm_prefill(h->O, L.wo, L.bo, T, d, d, EpiResidual{h->X, h->Y, d}, s);
-    ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f16_kernel<RC>, dim3((T + 3) / 4), dim3(256), 0, s, h->Y, T, d, L.ln1_g, L.ln1_b, c.ln_eps,
-                       h->X1));
-    launch_gemm_prefill(h->X1, L.w1, L.b1, T, f, d, EpiGelu{h->G, f}, s);
-    launch_gemm_prefill(h->G, L.w2, L.b2, T, d, f, EpiResidual{h->X1, h->Y, d}, s);
-    ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f16_kernel<RC>, dim3((T + 3) / 4), dim3(256), 0, s, h->Y, T, d, L.ln2_g, L.ln2_b, c.ln_eps,
-                       h->X));
+    launch_gemm_prefill(h, h->X, L.wqkv, L.bqkv, T, 3 * d, d, eq, s);
+    {
+      ProfScope prof(h, ERNIE_PROF_ATTN_PREFILL, s, 0.0, 4.0 * sum_len2 * d);
+      hipLaunchKernelGGL(attn_prefill_kernel, dim3(q_tiles, H, B), dim3(256), 0, s, h->Q, kcache(h, l), vcache(h, l),
+                         h->cu, T, H, S, d, h->O);
+    }
+    launch_gemm_prefill(h, h->O, L.wo, L.bo, T, d, d, EpiResidual{h->X, h->Y, d}, s);
+    { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f16_kernel<RC>, dim3((T + 3) / 4), dim3(256), 0, s, h->Y, T, d, L.ln1_g, L.ln1_b, c.ln_eps,
+                       h->X1)); }
+    launch_gemm_prefill(h, h->X1, L.w1, L.b1, T, f, d, EpiGelu{h->G, f}, s);
+    launch_gemm_prefill(h, h->G, L.w2, L.b2, T, d, f, EpiResidual{h->X1, h->Y, d}, s);
+    { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f16_kernel<RC>, dim3((T + 3) / 4), dim3(256), 0, s, h->Y, T, d, L.ln2_g, L.ln2_b, c.ln_eps,
+                       h->X)); }
   }
-  hipLaunchKernelGGL(gather_last_rows_kernel, dim3(B), dim3(256), 0, s, h->X, h->cu, B, d, h->hlast, hidden_out_dev);
+  { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); hipLaunchKernelGGL(gather_last_rows_kernel, dim3(B), dim3(256), 0, s, h->X, h->cu, B, d, h->hlast, hidden_out_dev); }
+  { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0);
   launch_logits(h, h->hlast, B, logits_out_dev, s);
+  }
+  { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0);
   hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->plan.strips,
                      tok_out_dev, h->tok_prev, h->lens, 0, S, c.vocab_kept);
+  }
   h->prefilled = true; h->B = B; h->max_len = max_len; h->steps = 0;
+  h->sum_len = sum_len; h->sum_len2 = sum_len2;
   return launch_status();
 }
 
@@ -483,13 +532,15 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_o
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int B = h->B, d = c.d_model;
   const int* tok = tok_in_dev ? tok_in_dev : h->tok_prev;
-  ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_decode_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, tok, h->lens, B, c.max_pos,
-                     h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X));
+  { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_decode_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, tok, h->lens, B, c.max_pos,
+                     h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X)); }
   const int rc = fused_decode_fits(h, B) ? decode_layers_fused(h, logits_out_dev, hidden_out_dev, s)
                                          : decode_layers_multi(h, logits_out_dev, hidden_out_dev, s);
   if (rc != ERNIE_OK) return rc;
+  { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
   hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->plan.strips,
                      tok_out_dev, h->tok_prev, h->lens, 1, c.max_seq, c.vocab_kept);
+  }
   h->steps += 1;
   return launch_status();
 }
@@ -497,6 +548,7 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_o
 void ernie_free(ErnieHandle* h) {
   if (!h) return;
   if (h->staging) (void)hipHostFree(h->staging);
+  for (auto& sl : h->prof.slots) { (void)hipEventDestroy(sl.a); (void)hipEventDestroy(sl.b); }
   delete h;
 }
 
@@ -512,6 +564,38 @@ int ernie_debug_buffer(ErnieHandle* h, const char* name, void** ptr_dev, size_t*
   } else {
     return ERNIE_EINVAL;
   }
+  return ERNIE_OK;
+}
+
+int ernie_profile(ErnieHandle* h, int enable) {
+  if (!h) return ERNIE_EINVAL;
+  Profiler& p = h->prof;
+  if (enable && p.slots.empty()) {
+    p.slots.resize(8192);
+    for (auto& sl : p.slots)
+      if (hipEventCreate(&sl.a) != hipSuccess || hipEventCreate(&sl.b) != hipSuccess) return ERNIE_EHIP;
+  }
+  p.on = enable != 0;
+  p.used = 0;
+  for (int c = 0; c < ERNIE_PROF_NCAT; ++c) p.bytes[c] = p.flops[c] = 0.0;
+  return ERNIE_OK;
+}
+
+int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* launches, double* alg_bytes,
+                       double* alg_flops) {
+  if (!h || category < 0 || category >= ERNIE_PROF_NCAT || !total_ms || !launches) return ERNIE_EINVAL;
+  Profiler& p = h->prof;
+  double ms = 0.0; int64_t n = 0;
+  for (size_t i = 0; i < p.used; ++i) {
+    if (p.slots[i].cat != category) continue;
+    float t = 0.f;
+    if (hipEventSynchronize(p.slots[i].b) != hipSuccess ||
+        hipEventElapsedTime(&t, p.slots[i].a, p.slots[i].b) != hipSuccess) return ERNIE_EHIP;
+    ms += t; ++n;
+  }
+  *total_ms = ms; *launches = n;
+  if (alg_bytes) *alg_bytes = p.bytes[category];
+  if (alg_flops) *alg_flops = p.flops[category];
   return ERNIE_OK;
 }
 
