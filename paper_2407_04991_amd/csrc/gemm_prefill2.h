@@ -1,0 +1,181 @@
+// Prefill GEMM on FP16 MFMA, asynchronous-copy pipeline:
+//   C[M, N] = A[M, K] * W[N, K]^T  (+ fused epilogue), fp32 accumulation.
+//
+// One workgroup (4 waves, 2 x 2, each TM x TN MFMA 32x32x16 tiles) owns a
+// (64 TM) x (64 TN) output tile and walks K in steps of BK through an S-stage ring in LDS.  Operands travel global -> LDS
+// directly (global_load_lds_dwordx4: lane l's 16 bytes land at LDS base + 16 l),
+// so no registers are spent on staging and S - 1 stages stay in flight per wave.
+//
+//   A stage  64 TM rows x BK halves, row-major, 16-byte chunks XOR-swizzled
+//            (slot = chunk ^ ((row / rows_per_256B) % chunks_per_row)) so that a
+//            quarter-wave's 16-byte fragment reads fall on 64 distinct banks.  A
+//            load instruction covers 16 (BK = 32) or 8 (BK = 64) whole rows:
+//            the lanes of one row read one contiguous 64/128-byte run.
+//   W stage  the packed weight is already in fragment order: 1 KiB fragments
+//            are copied verbatim and read back lane-contiguously.
+//
+// Rows >= M and n-tiles past the end are clamped to the last valid one (their
+// products land in accumulator entries the epilogue never stores).
+#pragma once
+
+#include "common.h"
+#include "gemm_prefill.h"   // epilogue functors
+
+namespace ernie {
+
+typedef __attribute__((address_space(1))) const void global_cptr_t;
+typedef __attribute__((address_space(3))) void lds_ptr_t;
+
+__device__ __forceinline__ void async_copy16(const void* gsrc, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((global_cptr_t*)gsrc, (lds_ptr_t*)lds_wave_base, 16, 0, 0);
+}
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits [3:0] and [15:14]).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+template <int TM, int TN, int BK, int S>
+struct GemmPipe {
+  static constexpr int kBM = 64 * TM, kBN = 64 * TN;         // block tile: 2 x 2 waves of TM x TN MFMA tiles
+  static constexpr int kRowBytes = BK * 2;
+  static constexpr int kChunks = kRowBytes / 16;             // 16-byte chunks per A row (4 or 8)
+  static constexpr int kRowsPer256 = 256 / kRowBytes;        // rows sharing one 64-bank line (4 or 2)
+  static constexpr int kRowsPerInstr = 64 / kChunks;         // rows one load instruction covers (16 or 8)
+  static constexpr int kAInstr = kBM / kRowsPerInstr / 4;    // A load instructions per wave per stage
+  static constexpr int kBFrags = (kBN / 32) * (BK / 16);     // W fragments per stage
+  static constexpr int kBInstr = (kBFrags + 3) / 4;          // W load instructions per wave per stage
+  static constexpr int kLoads = kAInstr + kBInstr;           // outstanding loads per wave per stage
+  static constexpr int kAStage = kBM * kRowBytes;            // bytes
+  static constexpr int kBStage = kBInstr * 4 * 1024;         // bytes (rounded up to whole instructions)
+  static constexpr int kStage = kAStage + kBStage;
+  static constexpr int kLdsBytes = S * kStage;
+  static_assert(kAInstr >= 1 && kBM % (kRowsPerInstr * 4) == 0, "A tile must split evenly over 4 waves");
+};
+
+// Workgroup id -> logical tile id such that the workgroups of one XCD (ids congruent mod 8) cover a
+// contiguous range of tiles: they then share A rows and W columns in that XCD's L2.
+__device__ __forceinline__ int xcd_contiguous_id(int id, int total) {
+  const int x = id & 7, q = total >> 3, r = total & 7;
+  return x * q + min(x, r) + (id >> 3);
+}
+
+template <int TM, int TN, int BK, int S, class Epi>
+__global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void gemm_prefill2_kernel(const half_t* __restrict__ A,
+                                                            const half_t* __restrict__ Wp,
+                                                            const float* __restrict__ bias, int M, int N, int K,
+                                                            int n_tiles32, int tiles_n, Epi epi) {
+  using P = GemmPipe<TM, TN, BK, S>;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int tile = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int tile_m = tile / tiles_n, tile_n = tile - tile_m * tiles_n;
+  const int m0 = tile_m * P::kBM, n0 = tile_n * P::kBN;
+  const int k_tiles = K / 16;
+  const int steps = K / BK;
+
+  // ---- per-lane source addresses of this wave's load instructions (k offset added per step)
+  const half_t* a_src[P::kAInstr];
+#pragma unroll
+  for (int i = 0; i < P::kAInstr; ++i) {
+    const int r = (wave * P::kAInstr + i) * P::kRowsPerInstr + lane / P::kChunks;     // row inside the tile
+    const int c = (lane % P::kChunks) ^ ((r / P::kRowsPer256) % P::kChunks);          // global chunk that lands in slot lane % kChunks
+    a_src[i] = A + (size_t)min(m0 + r, M - 1) * K + c * 8;
+  }
+  // W fragment f of a stage = (n-tile f / (BK/16), k-tile f % (BK/16)); wave w copies fragments w*kBInstr + j
+  const half_t* b_src[P::kBInstr];
+#pragma unroll
+  for (int j = 0; j < P::kBInstr; ++j) {
+    const int f = min(wave * P::kBInstr + j, P::kBFrags - 1);
+    const int nt = min(n0 / 32 + f / (BK / 16), n_tiles32 - 1);
+    b_src[j] = Wp + packed_frag_offset(nt, f % (BK / 16), k_tiles) + lane * 8;
+  }
+
+  auto issue = [&](int stage, int kstep) {
+    unsigned char* sa = smem_raw + stage * P::kStage;
+    unsigned char* sb = sa + P::kAStage;
+    const int k0 = kstep * BK;
+#pragma unroll
+    for (int i = 0; i < P::kAInstr; ++i)
+      async_copy16(a_src[i] + k0, sa + (wave * P::kAInstr + i) * P::kRowsPerInstr * P::kRowBytes);
+#pragma unroll
+    for (int j = 0; j < P::kBInstr; ++j)
+      async_copy16(b_src[j] + (size_t)(k0 / 16) * 512, sb + (wave * P::kBInstr + j) * 1024);
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // ---- fragment read offsets (bytes) inside a stage
+  int a_off[TM], a_swz[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int r = wm * 32 * TM + i * 32 + (lane & 31);
+    a_off[i] = r * P::kRowBytes;
+    a_swz[i] = (r / P::kRowsPer256) % P::kChunks;
+  }
+  const int hh = lane >> 5;
+
+#pragma unroll
+  for (int s = 0; s < S - 1; ++s)
+    if (s < steps) issue(s, s);
+
+  for (int step = 0; step < steps; ++step) {
+    // stage `step` has landed once at most (S - 2) later stages of this wave are still in flight
+    if (step + S - 2 < steps) wait_vmcnt<(S - 2) * P::kLoads>(); else wait_vmcnt<0>();
+    // Plain s_barrier: __syncthreads() would add a fence that drains vmcnt to 0 and with it the pipeline.
+    // Each wave has waited for its own share of the stage above; LDS reads below are issued after the
+    // barrier in program order, and the compiler barriers keep them there.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();     // every wave's share of the stage is visible; the stage computed last step is free
+    asm volatile("" ::: "memory");
+    if (step + S - 1 < steps) issue((step + S - 1) % S, step + S - 1);
+
+    const unsigned char* sa = smem_raw + (step % S) * P::kStage;
+    const unsigned char* sb = sa + P::kAStage;
+    // fragments of k-substep ks + 1 are read from LDS while the MFMAs of substep ks run
+    half8 fa[2][TM], fb[2][TN];
+    auto read_frags = [&](int ks, int buf) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        fa[buf][i] = *reinterpret_cast<const half8*>(sa + a_off[i] + (((2 * ks + hh) ^ a_swz[i]) * 16));
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        fb[buf][j] = *reinterpret_cast<const half8*>(sb + ((wn * TN + j) * (BK / 16) + ks) * 1024 + lane * 16);
+    };
+    read_frags(0, 0);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      if (ks + 1 < BK / 16) read_frags(ks + 1, (ks + 1) & 1);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(fa[ks & 1][i], fb[ks & 1][j], acc[i][j]);
+    }
+  }
+
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int col = n0 + wn * 32 * TN + j * 32 + (lane & 31);
+    if (col >= N) continue;
+    const float bv = bias[col];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm * 32 * TM + i * 32 + mfma32_row(v, lane);
+        if (row < M) epi(row, col, acc[i][j][v] + bv);
+      }
+  }
+}
+
+}  // namespace ernie
