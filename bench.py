@@ -67,6 +67,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=16)
     ap.add_argument("--graph", type=int, default=1, help="replay the pass as HIP graphs (1) or launch eagerly (0)")
+    ap.add_argument("--prof-passes", type=int, default=3, help="passes of the event-bracketed per-kernel profile")
     ap.add_argument("--tune", action="append", default=[], help="decode tuning knob, key=value (repeatable)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -156,7 +157,7 @@ def main():
     # the stream it launches on (eager launches; a graph cannot carry timing events).  The family with
     # the largest total time is the "dominant kernel" of the roofline object.
     eng.profile(True)
-    prof_passes = 3
+    prof_passes = args.prof_passes
     with torch.cuda.stream(side):
         for _ in range(prof_passes):
             prefill_call(); decode_calls()

@@ -163,7 +163,7 @@ int ernie_debug_buffer(ErnieHandle* h, const char* name, void** ptr_dev, size_t*
  *
  * ernie_profile(h, 1) switches per-kernel timing on and clears the counters: from then on every
  * launch of the categories below is bracketed by HIP events recorded on the stream it is launched
- * on (events are created on the first enable; up to 8192 launches are recorded, later ones are not
+ * on (events are created on the first enable; up to 32768 launches are recorded, later ones are not
  * timed).  Do not capture profiled calls into a graph.  ernie_profile(h, 0) switches it off.
  * ernie_profile_read waits for the recorded events of one category and returns the summed device
  * time between each pair, the number of launches, and the algorithmic bytes and flops of those
@@ -186,10 +186,11 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
 
 /*
  * ernie_debug_tune -- test hook: override a decode-path tuning knob of this handle.
- *   "fused_decode" 0/1  use the small-batch path (row-wise work fused into GEMM prologues) when it fits
+ *   "fused_decode" 0/1  use the small-batch path (row-wise work fused into GEMM prologues) when it fits,
+ *                       else the large-batch path (split-K partials summed by row kernels)
  *   "sk_out", "sk_f2"   split of the contraction of the attention-output / second FFN GEMM over workgroups
- * Results are deterministic for any fixed setting.  Returns ERNIE_EINVAL for an unknown key or a split
- * that does not divide the k-tile count.
+ * Splits are 1, 2 or 4.  Results are deterministic for any fixed setting.  Returns ERNIE_EINVAL for an
+ * unknown key or a split that is not supported or does not divide the k-tile count.
  */
 int ernie_debug_tune(ErnieHandle* h, const char* key, int value);
 

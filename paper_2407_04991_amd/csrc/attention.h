@@ -4,8 +4,9 @@
 //  - attn_prefill_kernel: bidirectional attention of every prompt query over
 //    the valid prompt keys of its own sequence (padding never stored nor seen),
 //    flash-style on MFMA with fp32 online softmax.
-//  - attn_decode_kernel: one query per (sequence, head) over all cached keys,
-//    a pure streaming read of K and V with wave-shuffle softmax reductions.
+//  - attn_decode_fused_kernel: one query per (sequence, head) over all cached keys,
+//    a pure streaming read of K and V with wave-shuffle softmax reductions; the
+//    new token's q, k, v come from the raw QKV GEMM output (+ bias) in its prologue.
 #pragma once
 
 #include "common.h"
@@ -175,104 +176,13 @@ __device__ __forceinline__ void softmax_merge(SoftmaxPart& a, float om, float ol
   a.m = mn;
 }
 
-__global__ __launch_bounds__(256) void attn_decode_kernel(const half_t* __restrict__ Q,    // [B, d]
-                                                          const half_t* __restrict__ Kc, const half_t* __restrict__ Vc,
-                                                          const int* __restrict__ cache_len, int H, int S, int d,
-                                                          half_t* __restrict__ O) {          // [B, d]
-  __shared__ float sm[4][8][10];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
-  const int h = blockIdx.x, b = blockIdx.y;
-  const int c = min(cache_len[b] + 1, S);       // keys visible: everything cached plus the token just appended
-  const int ec = lane & 7, team = lane >> 3;
-
-  float q[8];
-  {
-    const half8 qv = *reinterpret_cast<const half8*>(Q + (size_t)b * d + h * 64 + ec * 8);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) q[j] = (float)qv[j] * 0.125f;
-  }
-  const half_t* Kb = Kc + ((size_t)b * H + h) * S * 64 + ec * 8;
-  const half_t* Vb = Vc + ((size_t)b * H + h) * S * 64 + ec * 8;
-
-  SoftmaxPart st;
-  st.m = -INFINITY; st.l = 0.f;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) st.acc[j] = 0.f;
-
-  constexpr int U = 4;                           // row groups in flight per wave
-  for (int g0 = wave * U; g0 * 8 < c; g0 += 4 * U) {
-    half8 kf[U], vf[U];
-    int key[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      key[u] = (g0 + u) * 8 + team;
-      const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      kf[u] = (key[u] < c) ? *reinterpret_cast<const half8*>(Kb + (size_t)key[u] * 64) : z;
-      vf[u] = (key[u] < c) ? *reinterpret_cast<const half8*>(Vb + (size_t)key[u] * 64) : z;
-    }
-    float s[U];
-    float mx = st.m;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float p = 0.f;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) p += q[j] * (float)kf[u][j];
-      p += __shfl_xor(p, 1, 64);
-      p += __shfl_xor(p, 2, 64);
-      p += __shfl_xor(p, 4, 64);
-      s[u] = (key[u] < c) ? p : -INFINITY;
-      mx = fmaxf(mx, s[u]);
-    }
-    if (mx != -INFINITY) {
-      const float alpha = (st.m == -INFINITY) ? 0.f : __expf(st.m - mx);
-      st.l *= alpha;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const float p = __expf(s[u] - mx);      // exp(-inf) = 0 for rows past the end
-        st.l += p;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) st.acc[j] += p * (float)vf[u][j];
-      }
-      st.m = mx;
-    }
-  }
-
-  // merge the 8 teams of the wave (lanes with equal lane % 8 hold the same head-dim chunk)
-#pragma unroll
-  for (int off = 8; off < 64; off <<= 1) {
-    const float om = __shfl_xor(st.m, off, 64);
-    const float ol = __shfl_xor(st.l, off, 64);
-    float oa[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) oa[j] = __shfl_xor(st.acc[j], off, 64);
-    softmax_merge(st, om, ol, oa);
-  }
-  if (team == 0) {
-    sm[wave][ec][0] = st.m; sm[wave][ec][1] = st.l;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) sm[wave][ec][2 + j] = st.acc[j];
-  }
-  __syncthreads();
-  if (wave == 0 && team == 0) {
-#pragma unroll
-    for (int w = 1; w < 4; ++w) softmax_merge(st, sm[w][ec][0], sm[w][ec][1], &sm[w][ec][2]);
-    const float inv = 1.0f / st.l;
-    half8 o;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] = (half_t)(st.acc[j] * inv);
-    *reinterpret_cast<half8*>(O + (size_t)b * d + h * 64 + ec * 8) = o;
-  }
-}
-
-// Same streaming attention, with the QKV epilogue folded into its prologue:
-// q, k, v of the new token are raw fp32 GEMM outputs [B, 3d] plus bias; the
+// The QKV epilogue is folded into the prologue:
+// q, k, v of the new token are raw fp32 GEMM outputs [B, 3d] (split-K partials) plus bias; the
 // new key and value are rounded to fp16, appended to the cache (slot
 // cache_len[b]) and used from registers, so the cache is never read back in
 // the kernel that writes it.
-__global__ __launch_bounds__(256) void attn_decode_fused_kernel(const float* __restrict__ Rqkv,   // [B, 3d] fp32
+__global__ __launch_bounds__(256) void attn_decode_fused_kernel(const float* __restrict__ Rqkv,   // [sk_in][B, 3d] fp32 split-K partials
+                                                                int sk_in, int B,
                                                                 const float* __restrict__ bqkv,   // [3d]
                                                                 half_t* __restrict__ Kc, half_t* __restrict__ Vc,
                                                                 const int* __restrict__ cache_len, int H, int S,
@@ -310,11 +220,19 @@ __global__ __launch_bounds__(256) void attn_decode_fused_kernel(const float* __r
   {
     const float* r = Rqkv + (size_t)b * 3 * d + h * 64 + ec * 8;
     const float* bs = bqkv + h * 64 + ec * 8;
+    float aq[8], ak[8], av[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { aq[j] = r[j] + bs[j]; ak[j] = r[d + j] + bs[d + j]; av[j] = r[2 * d + j] + bs[2 * d + j]; }
+    for (int s = 1; s < sk_in; ++s) {                       // further split-K partials, in index order
+      const float* rs = r + (size_t)s * B * 3 * d;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { aq[j] += rs[j]; ak[j] += rs[d + j]; av[j] += rs[2 * d + j]; }
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      q[j] = (float)(half_t)(r[j] + bs[j]) * 0.125f;      // q passes through fp16 like every stored activation
-      knew[j] = (half_t)(r[d + j] + bs[d + j]);
-      vnew[j] = (half_t)(r[2 * d + j] + bs[2 * d + j]);
+      q[j] = (float)(half_t)aq[j] * 0.125f;                 // q passes through fp16 like every stored activation
+      knew[j] = (half_t)ak[j];
+      vnew[j] = (half_t)av[j];
     }
   }
   if (has_new && wave == 0 && team == 0) {

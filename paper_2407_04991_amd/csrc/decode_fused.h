@@ -167,7 +167,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_kernel(DecGemmArgs p) {
 // is NW rows, not the whole batch; the row groups of a strip read the same weight
 // fragments (from L2 after the first).  The MFMA tile is fed rows 0..NW-1 repeated;
 // only accumulator rows < NW are reduced and stored.
-template <int NW, int EPI, int RC>
+template <int NW, int EPI, int RC, int SKIN>
 __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   static_assert(NW == 8, "row groups are 8 rows: accumulator registers 0..3 of each half-wave");
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -222,20 +222,23 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
       bt[c][0] = t0.x; bt[c][1] = t0.y; bt[c][2] = t0.z; bt[c][3] = t0.w;
       bt[c][4] = t1.x; bt[c][5] = t1.y; bt[c][6] = t1.z; bt[c][7] = t1.w;
     }
-    for (int s = 1; s < p.sk_in; ++s) {          // further split-K partials, added in index order
-      const size_t off = (size_t)s * B * K;
-      float4 x0[RC], x1[RC];
+    // further split-K partials (SKIN is a compile-time count so that all their loads are in flight together
+    // with the first partial's), added in index order
+    float4 y0[SKIN > 1 ? SKIN - 1 : 1][RC], y1[SKIN > 1 ? SKIN - 1 : 1][RC];
+#pragma unroll
+    for (int s = 1; s < SKIN; ++s)
 #pragma unroll
       for (int c = 0; c < RC; ++c) {
-        x0[c] = *reinterpret_cast<const float4*>(src[c] + off);
-        x1[c] = *reinterpret_cast<const float4*>(src[c] + off + 4);
+        y0[s - 1][c] = *reinterpret_cast<const float4*>(src[c] + (size_t)s * B * K);
+        y1[s - 1][c] = *reinterpret_cast<const float4*>(src[c] + (size_t)s * B * K + 4);
       }
 #pragma unroll
+    for (int s = 1; s < SKIN; ++s)
+#pragma unroll
       for (int c = 0; c < RC; ++c) {
-        v[c][0] += x0[c].x; v[c][1] += x0[c].y; v[c][2] += x0[c].z; v[c][3] += x0[c].w;
-        v[c][4] += x1[c].x; v[c][5] += x1[c].y; v[c][6] += x1[c].z; v[c][7] += x1[c].w;
+        v[c][0] += y0[s - 1][c].x; v[c][1] += y0[s - 1][c].y; v[c][2] += y0[s - 1][c].z; v[c][3] += y0[s - 1][c].w;
+        v[c][4] += y1[s - 1][c].x; v[c][5] += y1[s - 1][c].y; v[c][6] += y1[s - 1][c].z; v[c][7] += y1[s - 1][c].w;
       }
-    }
     float sum = 0.f;
 #pragma unroll
     for (int c = 0; c < RC; ++c) {
@@ -299,7 +302,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   }
 }
 
-// X = LayerNorm(sum_k partial_k + bias + residual), one wave per row (used once per step, before the logits).
+// X = LayerNorm(sum_k partial_k + bias + residual), one wave per row.  `advance_len` (may be null) is the
+// per-sequence cached length, not touched here; `hidden_out` optionally receives the fp32 widening of X.
 template <int RC>
 __global__ __launch_bounds__(256) void ln_partials_kernel(const float* __restrict__ r32, int sk_in,
                                                           const float* __restrict__ bias,
@@ -314,15 +318,35 @@ __global__ __launch_bounds__(256) void ln_partials_kernel(const float* __restric
   const int chunks = d / 8;
 #pragma unroll
   for (int c = 0; c < RC; ++c) {
-    const int ch = c * 64 + lane;
-    if (ch < chunks) {
-      const half8 rs = *reinterpret_cast<const half8*>(res + (size_t)r * d + ch * 8);
+    const int cc = min(c * 64 + lane, chunks - 1);      // clamped: the duplicated tail chunk is never stored
+    const half8 rs = *reinterpret_cast<const half8*>(res + (size_t)r * d + cc * 8);
+    const float4 b0 = *reinterpret_cast<const float4*>(bias + cc * 8), b1 = *reinterpret_cast<const float4*>(bias + cc * 8 + 4);
+    v.v[c][0] = b0.x + (float)rs[0]; v.v[c][1] = b0.y + (float)rs[1]; v.v[c][2] = b0.z + (float)rs[2];
+    v.v[c][3] = b0.w + (float)rs[3]; v.v[c][4] = b1.x + (float)rs[4]; v.v[c][5] = b1.y + (float)rs[5];
+    v.v[c][6] = b1.z + (float)rs[6]; v.v[c][7] = b1.w + (float)rs[7];
+  }
+  // partials are added in index order, four buffers' loads in flight at a time
+  for (int s0 = 0; s0 < sk_in; s0 += 4) {
+    float4 x0[4][RC], x1[4][RC];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) v.v[c][j] = bias[ch * 8 + j] + (float)rs[j];
-      for (int s = 0; s < sk_in; ++s) {
-        const float* src = r32 + ((size_t)s * rows + r) * d + ch * 8;
+    for (int u = 0; u < 4; ++u) {
+      const int s = min(s0 + u, sk_in - 1);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v.v[c][j] += src[j];
+      for (int c = 0; c < RC; ++c) {
+        const int cc = min(c * 64 + lane, chunks - 1);
+        const float* src = r32 + ((size_t)s * rows + r) * d + cc * 8;
+        x0[u][c] = *reinterpret_cast<const float4*>(src);
+        x1[u][c] = *reinterpret_cast<const float4*>(src + 4);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float live = (s0 + u < sk_in) ? 1.f : 0.f;
+#pragma unroll
+      for (int c = 0; c < RC; ++c) {
+        v.v[c][0] += live * x0[u][c].x; v.v[c][1] += live * x0[u][c].y; v.v[c][2] += live * x0[u][c].z;
+        v.v[c][3] += live * x0[u][c].w; v.v[c][4] += live * x1[u][c].x; v.v[c][5] += live * x1[u][c].y;
+        v.v[c][6] += live * x1[u][c].z; v.v[c][7] += live * x1[u][c].w;
       }
     }
   }
@@ -339,6 +363,40 @@ __global__ __launch_bounds__(256) void ln_partials_kernel(const float* __restric
       }
     }
   }
+}
+
+// G = gelu(sum_k partial_k + bias) as fp16 [rows, n]; one thread per 8 outputs, partial loads four at a time.
+__global__ __launch_bounds__(256) void gelu_partials_kernel(const float* __restrict__ r32, int sk_in,
+                                                            const float* __restrict__ bias, int rows, int n,
+                                                            half_t* __restrict__ G) {
+  const size_t total = (size_t)rows * n / 8;
+  const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= total) return;
+  const int col = (int)((id * 8) % n);
+  float a[8];
+  {
+    const float4 b0 = *reinterpret_cast<const float4*>(bias + col), b1 = *reinterpret_cast<const float4*>(bias + col + 4);
+    a[0] = b0.x; a[1] = b0.y; a[2] = b0.z; a[3] = b0.w; a[4] = b1.x; a[5] = b1.y; a[6] = b1.z; a[7] = b1.w;
+  }
+  for (int s0 = 0; s0 < sk_in; s0 += 4) {
+    float4 x0[4], x1[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float* src = r32 + (size_t)min(s0 + u, sk_in - 1) * rows * n + id * 8;
+      x0[u] = *reinterpret_cast<const float4*>(src);
+      x1[u] = *reinterpret_cast<const float4*>(src + 4);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float live = (s0 + u < sk_in) ? 1.f : 0.f;
+      a[0] += live * x0[u].x; a[1] += live * x0[u].y; a[2] += live * x0[u].z; a[3] += live * x0[u].w;
+      a[4] += live * x1[u].x; a[5] += live * x1[u].y; a[6] += live * x1[u].z; a[7] += live * x1[u].w;
+    }
+  }
+  half8 o;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o[j] = (half_t)gelu_erf(a[j]);
+  *reinterpret_cast<half8*>(G + id * 8) = o;
 }
 
 }  // namespace ernie

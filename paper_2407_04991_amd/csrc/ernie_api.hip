@@ -26,7 +26,7 @@ namespace {
 constexpr size_t kAlign = 256;
 constexpr int kStagingSlots = 8;
 constexpr int kFusedMaxBatch = 64;     // the fused-prologue decode path keeps the whole batch in LDS
-constexpr int kMaxSplitK = 8;
+constexpr int kBigMaxSplitK = 8;       // partial buffers of the raw fp32 GEMM outputs
 constexpr size_t kMaxLds = 160 * 1024;
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -42,7 +42,7 @@ struct ArenaPlan {
   size_t tok_rm, tok_p, pos, emb_g, emb_b, kept;
   struct L { size_t wqkv, wo, w1, w2, bqkv, bo, b1, b2, ln1_g, ln1_b, ln2_g, ln2_b; };
   std::vector<L> layers;
-  size_t r_qkv, r_out, r_f2;
+  size_t r_qkv, r_out, r_f1, r_f2, zero_bias;
   size_t kv, X, X1, Y, Q, O, G, Yf, hlast, strip_val, strip_idx, cu, lens, tok_seq, tok_pos, tok_prev;
   size_t total;
   int vocab_tiles, strips;
@@ -75,9 +75,10 @@ ArenaPlan make_plan(const ErnieConfig& c) {
   p.X = take(p.t_max * d * 2); p.X1 = take(p.t_max * d * 2); p.Y = take(p.t_max * d * 2);
   p.Q = take(p.t_max * d * 2); p.O = take(p.t_max * d * 2); p.G = take(p.t_max * f * 2);
   p.Yf = take(Bm * d * 4);
-  const size_t Bf = Bm < (size_t)kFusedMaxBatch ? Bm : (size_t)kFusedMaxBatch;
-  p.r_qkv = take(Bf * 3 * d * 4); p.r_out = take(kMaxSplitK * Bf * d * 4);
-  p.r_f2 = take(kMaxSplitK * Bf * d * 4);
+  // raw fp32 GEMM outputs of the decode step, split over K into up to kBigMaxSplitK partial buffers
+  p.r_qkv = take((size_t)kBigMaxSplitK * Bm * 3 * d * 4); p.r_out = take((size_t)kBigMaxSplitK * Bm * d * 4);
+  p.r_f1 = take((size_t)kBigMaxSplitK * Bm * f * 4); p.r_f2 = take((size_t)kBigMaxSplitK * Bm * d * 4);
+  p.zero_bias = take((3 * d > f ? 3 * d : f) * 4);
   p.hlast = take(Bm * d * 2);
   p.strip_val = take(Bm * p.strips * 4); p.strip_idx = take(Bm * p.strips * 4);
   p.cu = take((Bm + 1) * 4); p.lens = take(Bm * 4);
@@ -121,7 +122,7 @@ struct ErnieHandle {
   float *emb_g, *emb_b;
   std::vector<LayerPtrs> layers;
   half_t *kv, *X, *X1, *Y, *Q, *O, *G, *hlast;
-  float *Yf, *strip_val, *r_qkv, *r_out, *r_f2;
+  float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
   int sk_out, sk_f2, fused_decode;   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   int* staging;          // pinned host: kStagingSlots x (max_batch + 1) ints
@@ -176,30 +177,14 @@ void launch_gemm_prefill_t(const half_t* A, const half_t* Wp, const float* bias,
 
 template <class Epi>
 void launch_gemm_prefill(ErnieHandle* h, const half_t* A, const half_t* Wp, const float* bias, int M, int N, int K,
-                         Epi epi, hipStream_t s) {
-  ProfScope prof(h, ERNIE_PROF_GEMM_PREFILL, s, 0.0, 2.0 * M * N * K);
+                         Epi epi, hipStream_t s, int category = ERNIE_PROF_GEMM_PREFILL) {
+  ProfScope prof(h, category, s, 2.0 * N * K, 2.0 * M * N * K);
   const long tiles_256x128 = (long)((M + 255) / 256) * ((N + 127) / 128);
   const long tiles_128x128 = (long)((M + 127) / 128) * ((N + 127) / 128);
   if (tiles_256x128 >= 512) launch_gemm_prefill_t<4, 2, 32, 2>(A, Wp, bias, M, N, K, epi, s);
   else if (tiles_128x128 >= 384) launch_gemm_prefill_t<2, 2, 32, 3>(A, Wp, bias, M, N, K, epi, s);
   else if (K >= 2048) launch_gemm_prefill_t<2, 1, 64, 3>(A, Wp, bias, M, N, K, epi, s);
   else launch_gemm_prefill_t<2, 1, 32, 3>(A, Wp, bias, M, N, K, epi, s);
-}
-
-template <int MT, int NW, class Epi>
-void launch_skinny_t(const half_t* X, const half_t* Wp, const float* bias, int B, int N, int K, Epi epi,
-                     hipStream_t s) {
-  const size_t lds = (size_t)NW * MT * 16 * 64 * 4;
-  hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW, Epi>), dim3((N + 31) / 32), dim3(NW * 64), lds, s, X, Wp, bias, B, N,
-                     K, epi);
-}
-
-template <class Epi>
-void launch_skinny(const half_t* X, const half_t* Wp, const float* bias, int B, int N, int K, Epi epi, hipStream_t s) {
-  if (B <= 32) launch_skinny_t<1, 8>(X, Wp, bias, B, N, K, epi, s);
-  else if (B <= 64) launch_skinny_t<2, 8>(X, Wp, bias, B, N, K, epi, s);
-  else if (B <= 128) launch_skinny_t<4, 4>(X, Wp, bias, B, N, K, epi, s);
-  else launch_skinny_t<8, 4>(X, Wp, bias, B, N, K, epi, s);
 }
 
 template <int MT, int NW>
@@ -228,18 +213,17 @@ int configure_kernels() {
 #define GEMM_LDS(TM, TN, BK, S)                                                                            \
   rc |= allow_lds(gemm_prefill2_kernel<TM, TN, BK, S, EpiQKV>, GemmPipe<TM, TN, BK, S>::kLdsBytes);       \
   rc |= allow_lds(gemm_prefill2_kernel<TM, TN, BK, S, EpiResidual>, GemmPipe<TM, TN, BK, S>::kLdsBytes);  \
-  rc |= allow_lds(gemm_prefill2_kernel<TM, TN, BK, S, EpiGelu>, GemmPipe<TM, TN, BK, S>::kLdsBytes)
+  rc |= allow_lds(gemm_prefill2_kernel<TM, TN, BK, S, EpiGelu>, GemmPipe<TM, TN, BK, S>::kLdsBytes);      \
+  rc |= allow_lds(gemm_prefill2_kernel<TM, TN, BK, S, EpiRaw32>, GemmPipe<TM, TN, BK, S>::kLdsBytes)
   GEMM_LDS(4, 2, 32, 2); GEMM_LDS(2, 2, 32, 3); GEMM_LDS(2, 1, 64, 3); GEMM_LDS(2, 1, 32, 3);
 #undef GEMM_LDS
   const size_t big = (size_t)4 * 8 * 16 * 64 * 4;   // MT = 8, NW = 4
-  rc |= allow_lds(gemm_skinny_kernel<8, 4, SkinnyQKV>, big);
-  rc |= allow_lds(gemm_skinny_kernel<8, 4, SkinnyResidual>, big);
-  rc |= allow_lds(gemm_skinny_kernel<8, 4, SkinnyGelu>, big);
   rc |= allow_lds(logits_argmax_kernel<8, 4>, big);
   rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_RAW>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<2, 8, EPI_RAW>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_ARGMAX>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<2, 8, EPI_ARGMAX>, kMaxLds);
+  rc |= allow_lds(gemm_dec_kernel<4, 8, EPI_RAW>, kMaxLds);
   return rc ? ERNIE_EHIP : ERNIE_OK;
 }
 
@@ -249,7 +233,7 @@ int configure_kernels() {
 // to about 96 workgroups, capped so that the consumer does not pay for many partials.
 int pick_split_k(int strips, int k_tiles, int cap) {
   int best = 1;
-  for (int sk = 1; sk <= cap; ++sk) {
+  for (int sk = 1; sk <= cap; sk *= 2) {          // 1, 2, 4: the splits the consumers are instantiated for
     if (k_tiles % sk != 0 || k_tiles / sk < 8) continue;
     best = sk;
     if (strips * sk >= 96) break;
@@ -264,15 +248,22 @@ size_t dec_lds_bytes(int MT, int NW, int kslice) {
 
 template <int EPI>
 int launch_gemm_dec(ErnieHandle* h, DecGemmArgs a, int sk, hipStream_t s) {
-  constexpr int NW = 8;
   ProfScope prof(h, EPI == EPI_ARGMAX ? ERNIE_PROF_LOGITS : ERNIE_PROF_GEMM_DEC, s, 2.0 * a.N * a.K, 2.0 * a.B * a.N * a.K);
   const int MT = (a.B + 31) / 32;
+  if (sk < 1 || (a.K / 16) % sk != 0) return ERNIE_EINVAL;
   const int kslice = a.K / sk;
-  const size_t lds = dec_lds_bytes(MT, NW, kslice);
-  if (MT > 2 || lds > kMaxLds || (a.K / 16) % sk != 0) return ERNIE_EINVAL;
-  const dim3 grid((a.N + 31) / 32, sk), block(NW * 64);
-  if (MT == 1) hipLaunchKernelGGL((gemm_dec_kernel<1, NW, EPI>), grid, block, lds, s, a);
-  else hipLaunchKernelGGL((gemm_dec_kernel<2, NW, EPI>), grid, block, lds, s, a);
+  const dim3 grid((a.N + 31) / 32, sk);
+#define DEC_LAUNCH(MTV, NWV)                                                                    \
+  do {                                                                                          \
+    const size_t lds = dec_lds_bytes(MTV, NWV, kslice);                                         \
+    if (lds > kMaxLds) return ERNIE_EINVAL;                                                     \
+    hipLaunchKernelGGL((gemm_dec_kernel<MTV, NWV, EPI>), grid, dim3(NWV * 64), lds, s, a);      \
+  } while (0)
+  if (MT == 1) DEC_LAUNCH(1, 8);
+  else if (MT == 2) DEC_LAUNCH(2, 8);
+  else if (MT <= 4) DEC_LAUNCH(4, 8);
+  else return ERNIE_EINVAL;
+#undef DEC_LAUNCH
   return ERNIE_OK;
 }
 
@@ -283,7 +274,13 @@ int launch_gemm_dec_ln(ErnieHandle* h, DecGemmArgs a, hipStream_t s) {
   if (a.K > 1024) return ERNIE_EINVAL;                 // the LayerNorm prologue holds rows of <= 1024 features
   const size_t lds = (size_t)NW * (a.K + 8) * 2;      // >= the 8 KiB the reduction reuses
   const dim3 grid((a.N + 31) / 32, 1, (a.B + NW - 1) / NW), block(NW * 64);
-  hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2>), grid, block, lds < 8192 ? 8192 : lds, s, a);
+  const size_t ldsz = lds < 8192 ? 8192 : lds;
+  switch (a.sk_in) {      // the count of split-K partials to add is a template parameter of the prologue
+    case 1: hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2, 1>), grid, block, ldsz, s, a); break;
+    case 2: hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2, 2>), grid, block, ldsz, s, a); break;
+    case 4: hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2, 4>), grid, block, ldsz, s, a); break;
+    default: return ERNIE_EINVAL;
+  }
   return ERNIE_OK;
 }
 
@@ -317,7 +314,7 @@ int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hi
     {
       // K and V of every visible position (cached + the appended one), 2 bytes each
       ProfScope prof(h, ERNIE_PROF_ATTN_DEC, s, 2.0 * (h->sum_len + (double)B * (h->steps + 1)) * d * 2.0, 0.0);
-      hipLaunchKernelGGL(attn_decode_fused_kernel, dim3(H, B), dim3(256), 0, s, h->r_qkv, L.bqkv, kcache(h, l),
+      hipLaunchKernelGGL(attn_decode_fused_kernel, dim3(H, B), dim3(256), 0, s, h->r_qkv, 1, B, L.bqkv, kcache(h, l),
                          vcache(h, l), h->lens, H, S, d, h->O);
     }
     DecGemmArgs o{};
@@ -342,33 +339,70 @@ int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hi
   return rc ? ERNIE_EHIP : ERNIE_OK;
 }
 
-// Larger batches: one kernel per operation (weights are a small share of the step's bytes there).
-int decode_layers_multi(ErnieHandle* h, float* logits_out, float* hidden_out, hipStream_t s) {
+// Split of the contraction for the medium-batch path: the smallest split whose A tile (128 rows) fits
+// in LDS and that yields at least ~160 workgroups (or the largest that fits).
+int pick_mid_split(int N, int K) {
+  const int strips = (N + 31) / 32;
+  int best = 0;
+  for (int sk : {1, 2, 3, 4, 6, 8}) {
+    if ((K / 16) % sk != 0 || dec_lds_bytes(4, 8, K / sk) > kMaxLds) continue;
+    best = sk;
+    if (strips * sk >= 160) break;
+  }
+  return best;
+}
+
+// Larger batches.  64 < B <= 128: the weight-streaming GEMM split over K writes fp32 partials.  B > 128:
+// the batch is a real M dimension and the projections run on the prefill MFMA GEMM (asynchronous-copy
+// pipeline) with raw fp32 or bias + GELU epilogues.  In both, row kernels add partials + bias + residual
+// and normalise (7-8 launches per layer); the step is bound by the cache stream of the attention.
+int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipStream_t s) {
   const ErnieConfig& c = h->cfg;
   const int B = h->B, d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
+  const bool mid = B <= 128;
+  const int sk_q = mid ? pick_mid_split(3 * d, d) : 1, sk_o = mid ? pick_mid_split(d, d) : 1,
+            sk_1 = mid ? pick_mid_split(f, d) : 1, sk_2 = mid ? pick_mid_split(d, f) : 1;
+  if (!sk_q || !sk_o || !sk_1 || !sk_2) return ERNIE_EINVAL;
+  int rc = ERNIE_OK;
+  auto raw_gemm = [&](const half_t* A, const half_t* Wp, int N, int K, float* out, int sk) {
+    if (mid) {
+      DecGemmArgs a{};
+      a.B = B; a.Wp = Wp; a.N = N; a.K = K; a.a16 = A; a.rout = out;
+      rc |= launch_gemm_dec<EPI_RAW>(h, a, sk, s);
+    } else {
+      launch_gemm_prefill(h, A, Wp, h->zero_bias, B, N, K, EpiRaw32{out, N}, s, ERNIE_PROF_GEMM_DEC);
+    }
+  };
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerPtrs& L = h->layers[l];
-    launch_skinny(h->X, L.wqkv, L.bqkv, B, 3 * d, d, SkinnyQKV{h->Q, kcache(h, l), vcache(h, l), h->lens, d, H, S},
-                  s);
+    raw_gemm(h->X, L.wqkv, 3 * d, d, h->r_qkv, sk_q);
     {
       ProfScope prof(h, ERNIE_PROF_ATTN_DEC, s, 2.0 * (h->sum_len + (double)B * (h->steps + 1)) * d * 2.0, 0.0);
-      hipLaunchKernelGGL(attn_decode_kernel, dim3(H, B), dim3(256), 0, s, h->Q, kcache(h, l), vcache(h, l), h->lens, H,
-                         S, d, h->O);
+      hipLaunchKernelGGL(attn_decode_fused_kernel, dim3(H, B), dim3(256), 0, s, h->r_qkv, sk_q, B, L.bqkv,
+                         kcache(h, l), vcache(h, l), h->lens, H, S, d, h->O);
     }
-    launch_skinny(h->O, L.wo, L.bo, B, d, d, SkinnyResidual{h->X, h->Yf, d}, s);
-    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f32_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->Yf, B, d, L.ln1_g, L.ln1_b,
-                       c.ln_eps, h->X1)); }
-    launch_skinny(h->X1, L.w1, L.b1, B, f, d, SkinnyGelu{h->G, f}, s);
-    launch_skinny(h->G, L.w2, L.b2, B, d, f, SkinnyResidual{h->X1, h->Yf, d}, s);
-    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(ln_rows_f32_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->Yf, B, d, L.ln2_g, L.ln2_b,
-                       c.ln_eps, h->X)); }
+    raw_gemm(h->O, L.wo, d, d, h->r_out, sk_o);
+    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
+      ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_out, sk_o,
+                                         L.bo, h->X, B, d, L.ln1_g, L.ln1_b, c.ln_eps, h->X1, (float*)nullptr)); }
+    if (mid) {
+      raw_gemm(h->X1, L.w1, f, d, h->r_f1, sk_1);
+      ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
+      const size_t n8 = (size_t)B * f / 8;
+      hipLaunchKernelGGL(gelu_partials_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, h->r_f1, sk_1, L.b1,
+                         B, f, h->G);
+    } else {
+      launch_gemm_prefill(h, h->X1, L.w1, L.b1, B, f, d, EpiGelu{h->G, f}, s, ERNIE_PROF_GEMM_DEC);
+    }
+    raw_gemm(h->G, L.w2, d, f, h->r_f2, sk_2);
+    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
+      float* hid = (l == c.n_layers - 1) ? hidden_out : nullptr;
+      ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_f2, sk_2,
+                                         L.b2, h->X1, B, d, L.ln2_g, L.ln2_b, c.ln_eps, h->X, hid)); }
   }
-  if (hidden_out)
-    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); hipLaunchKernelGGL(hidden_to_f32_kernel, dim3((B * d + 255) / 256), dim3(256), 0, s, h->X, B * d, hidden_out); }
-  { ProfScope prof(h, ERNIE_PROF_LOGITS, s, 0.0, 0.0);
-  launch_logits(h, h->X, B, logits_out, s);
-  }
-  return ERNIE_OK;
+  { ProfScope prof(h, ERNIE_PROF_LOGITS, s, 2.0 * c.vocab_kept * d, 2.0 * B * c.vocab_kept * d);
+    launch_logits(h, h->X, B, logits_out, s); }
+  return rc ? ERNIE_EHIP : ERNIE_OK;
 }
 
 void pack_into(const void* src, half_t* dst, int N, int K, hipStream_t s) {
@@ -430,7 +464,7 @@ int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* w, void* aren
   h->kv = H16(plan.kv); h->X = H16(plan.X); h->X1 = H16(plan.X1); h->Y = H16(plan.Y); h->Q = H16(plan.Q);
   h->O = H16(plan.O); h->G = H16(plan.G); h->hlast = H16(plan.hlast);
   h->Yf = F32(plan.Yf); h->strip_val = F32(plan.strip_val);
-  h->r_qkv = F32(plan.r_qkv); h->r_out = F32(plan.r_out); h->r_f2 = F32(plan.r_f2);
+  h->r_qkv = F32(plan.r_qkv); h->r_out = F32(plan.r_out); h->r_f1 = F32(plan.r_f1); h->r_f2 = F32(plan.r_f2); h->zero_bias = F32(plan.zero_bias);
   h->fused_decode = 1;
   h->sk_out = pick_split_k(cfg->d_model / 32, cfg->d_model / 16, 2);
   h->sk_f2 = pick_split_k(cfg->d_model / 32, cfg->d_ffn / 16, 4);
@@ -449,6 +483,7 @@ int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* w, void* aren
 
   const int d = cfg->d_model, f = cfg->d_ffn, V = cfg->vocab_kept;
   bool copies_ok = true;
+  copies_ok &= hipMemsetAsync(h->zero_bias, 0, (size_t)(3 * cfg->d_model > cfg->d_ffn ? 3 * cfg->d_model : cfg->d_ffn) * 4, s) == hipSuccess;
   copies_ok &= hipMemcpyAsync(h->tok_rm, w->tok_emb_kept, (size_t)V * d * 2, hipMemcpyDeviceToDevice, s) == hipSuccess;
   copies_ok &= hipMemcpyAsync(h->pos, w->pos_emb, (size_t)cfg->max_pos * d * 2, hipMemcpyDeviceToDevice, s) == hipSuccess;
   copies_ok &= hipMemcpyAsync(a + plan.kept, w->kept_ids, (size_t)V * 4, hipMemcpyDeviceToDevice, s) == hipSuccess;
@@ -553,7 +588,7 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_o
   { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_decode_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, tok, h->lens, B, c.max_pos,
                      h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X)); }
   const int rc = fused_decode_fits(h, B) ? decode_layers_fused(h, logits_out_dev, hidden_out_dev, s)
-                                         : decode_layers_multi(h, logits_out_dev, hidden_out_dev, s);
+                                         : decode_layers_big(h, logits_out_dev, hidden_out_dev, s);
   if (rc != ERNIE_OK) return rc;
   { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
   hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->plan.strips,
@@ -589,7 +624,7 @@ int ernie_profile(ErnieHandle* h, int enable) {
   if (!h) return ERNIE_EINVAL;
   Profiler& p = h->prof;
   if (enable && p.slots.empty()) {
-    p.slots.resize(8192);
+    p.slots.resize(32768);
     for (auto& sl : p.slots)
       if (hipEventCreate(&sl.a) != hipSuccess || hipEventCreate(&sl.b) != hipSuccess) return ERNIE_EHIP;
   }
@@ -622,7 +657,7 @@ int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "sk_out") || !strcmp(key, "sk_f2")) {
     const int k_tiles = (!strcmp(key, "sk_out") ? h->cfg.d_model : h->cfg.d_ffn) / 16;
-    if (value < 1 || value > kMaxSplitK || k_tiles % value != 0) return ERNIE_EINVAL;
+    if ((value != 1 && value != 2 && value != 4) || k_tiles % value != 0) return ERNIE_EINVAL;
     (!strcmp(key, "sk_out") ? h->sk_out : h->sk_f2) = value;
     return ERNIE_OK;
   }

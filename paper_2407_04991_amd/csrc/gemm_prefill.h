@@ -49,4 +49,11 @@ struct EpiGelu {
   }
 };
 
+// Raw fp32 output [M, N] (decode step at large batch: the consumer kernels add bias and residual).
+struct EpiRaw32 {
+  float* r;
+  int N;
+  __device__ __forceinline__ void operator()(int row, int col, float v) const { r[(size_t)row * N + col] = v; }
+};
+
 }  // namespace ernie

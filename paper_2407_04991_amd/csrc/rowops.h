@@ -175,30 +175,6 @@ __global__ __launch_bounds__(256) void ln_rows_f16_kernel(const half_t* __restri
   row_layernorm_store(r, d, lane, gamma, beta, eps, X + (size_t)t * d);
 }
 
-// Decode: X = LN(Y) with Y fp32 rows (sublayer output + bias + residual kept in fp32).
-template <int RC>
-__global__ __launch_bounds__(256) void ln_rows_f32_kernel(const float* __restrict__ Y, int rows, int d,
-                                                          const float* __restrict__ gamma,
-                                                          const float* __restrict__ beta, float eps,
-                                                          half_t* __restrict__ X) {
-  const int lane = threadIdx.x & 63;
-  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (t >= rows) return;
-  RowRegs<RC> r;
-  const int chunks = d / 8;
-#pragma unroll
-  for (int c = 0; c < RC; ++c) {
-    const int ch = c * 64 + lane;
-    if (ch < chunks) {
-      const float4 a = *reinterpret_cast<const float4*>(Y + (size_t)t * d + ch * 8);
-      const float4 b = *reinterpret_cast<const float4*>(Y + (size_t)t * d + ch * 8 + 4);
-      r.v[c][0] = a.x; r.v[c][1] = a.y; r.v[c][2] = a.z; r.v[c][3] = a.w;
-      r.v[c][4] = b.x; r.v[c][5] = b.y; r.v[c][6] = b.z; r.v[c][7] = b.w;
-    }
-  }
-  row_layernorm_store(r, d, lane, gamma, beta, eps, X + (size_t)t * d);
-}
-
 // Last valid prompt row of every sequence -> dense [B, d] (fp16 for the logits
 // GEMM, optional fp32 copy for the caller).
 __global__ void gather_last_rows_kernel(const half_t* __restrict__ X, const int* __restrict__ cu, int B, int d,
@@ -210,11 +186,6 @@ __global__ void gather_last_rows_kernel(const half_t* __restrict__ X, const int*
     Hlast[(size_t)b * d + i] = v;
     if (hidden_out) hidden_out[(size_t)b * d + i] = (float)v;
   }
-}
-
-__global__ void hidden_to_f32_kernel(const half_t* __restrict__ X, int n, float* __restrict__ out) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) out[i] = (float)X[i];
 }
 
 // Second argmax stage: one block per sequence reduces the per-strip candidates
