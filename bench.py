@@ -21,6 +21,15 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 MFMA_F16_PEAK_TFLOPS = 2500.0
 
+# HBM bytes per launch (reads + writes) of each kernel family, from two rocprofv3 --pmc runs (FETCH_SIZE,
+# WRITE_SIZE) of this script, scaled by what the same counters read for a 256 MiB device copy (FETCH_SIZE
+# 2.0, WRITE_SIZE 1.0); summary and commands in profiles/base_b32_hbm_traffic_pmc.txt.  Counters cannot be
+# read from inside the process, so the figures are carried here for the workload they were measured on.
+MEASURED_HBM_BYTES_PER_LAUNCH = {
+    "base": {"gemm_dec": 4.283e6, "gemm_dec_ln": 7.325e6, "attn_dec": 14.612e6, "logits": 29.289e6,
+             "gemm_prefill": 62.286e6, "attn_prefill": 25.281e6},
+}
+
 
 def algorithmic_decode_bytes(sh, B, c_keys):
     """Bytes one decode step must move: every layer weight once, the trimmed table once,
@@ -68,6 +77,8 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=16)
     ap.add_argument("--graph", type=int, default=1, help="replay the pass as HIP graphs (1) or launch eagerly (0)")
     ap.add_argument("--prof-passes", type=int, default=3, help="passes of the event-bracketed per-kernel profile")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (reference for scaling HBM counters)")
     ap.add_argument("--tune", action="append", default=[], help="decode tuning knob, key=value (repeatable)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -191,7 +202,9 @@ def main():
     dom = max(cand, key=lambda k: kernels[k]["ms_per_pass"])
     roof = {"kernel": dom, "bound": kernels[dom]["bound"], "achieved": kernels[dom]["achieved"],
             "peak": kernels[dom]["peak"], "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"],
-            "avg_launch_us": kernels[dom]["avg_us"], "traffic": None}
+            "avg_launch_us": kernels[dom]["avg_us"],
+            "algorithmic_per_launch": (prof[dom][2] if kernels[dom]["bound"] == "hbm" else prof[dom][3]) / prof[dom][1],
+            "traffic": MEASURED_HBM_BYTES_PER_LAUNCH.get(args.workload, {}).get(dom)}
 
     out = {
         "metric": "generated tokens/sec (ERNIE-base FP16, 1 GPU)", "value": tokens_per_s, "unit": "tokens/s",
@@ -208,6 +221,14 @@ def main():
         "decode_step_algorithmic_gbs": dec_gbs, "decode_step_frac_of_hbm_peak": dec_gbs / HBM_PEAK_GBS,
         "kernels": kernels,
     }
+    if args.calib_copy_mb > 0:
+        n = args.calib_copy_mb * (1 << 20)
+        src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                      # one elementwise copy kernel: reads n bytes, writes n bytes
+        torch.cuda.synchronize()
+        out["calib_copy_bytes"] = n
     if not args.no_cpu_baseline:
         rows = list(range(min(args.cpu_rows, B)))
         out["cpu_baseline"] = cpu_baseline(wl, rows, N)

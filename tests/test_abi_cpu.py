@@ -63,6 +63,10 @@ def test_null_arguments_are_rejected_on_the_host():
     assert lib.ernie_prefill(None, 1, 1, None, None, None, None, None, None) == E.ERNIE_EINVAL
     assert lib.ernie_decode_step(None, None, None, None, None, None) == E.ERNIE_EINVAL
     lib.ernie_free(None)     # no-op
+    assert lib.ernie_profile(None, 1) == E.ERNIE_EINVAL
+    assert lib.ernie_debug_tune(None, b"sk_out", 1) == E.ERNIE_EINVAL
+    ms = C.c_double(); cnt = C.c_int64()
+    assert lib.ernie_profile_read(None, 0, C.byref(ms), C.byref(cnt), None, None) == E.ERNIE_EINVAL
     out = C.c_void_p(); n = C.c_size_t()
     assert lib.ernie_debug_buffer(None, b"x", C.byref(out), C.byref(n)) == E.ERNIE_EINVAL
 

@@ -257,3 +257,56 @@ def test_decode_tuning_variants_agree(E):
     with pytest.raises(E.ErnieError):
         eng.tune("no_such_knob", 1)
     eng.close()
+
+
+def test_profile_hooks_count_launches(E):
+    """ernie_profile brackets every launch of a kernel family; counts and algorithmic bytes match the step structure."""
+    import torch
+    wl = make_workload("tiny_affine")
+    sh = wl.shape
+    eng = E.engine_from_workload(wl)
+    ids, lens = wl.padded(0)
+    eng.profile(True)
+    tok, _, _ = eng.prefill(torch.as_tensor(ids), lens)
+    for _ in range(3):
+        eng.decode_step(None)
+    torch.cuda.synchronize()
+    p = eng.profile_read()
+    Nl, d, f = sh.n_layers, sh.d_model, sh.d_ffn
+    assert p["gemm_prefill"][1] == 4 * Nl and p["attn_prefill"][1] == Nl
+    assert p["attn_dec"][1] == 3 * Nl and p["logits"][1] == 3
+    assert p["gemm_dec"][1] + p["gemm_dec_ln"][1] == 3 * 4 * Nl          # four projections per layer per step
+    assert p["gemm_dec_ln"][1] == 3 * (2 * Nl - 1)                       # QKV of layers >= 1 and every FFN1
+    w_layer = (4 * d * d + 2 * d * f) * 2
+    assert abs(p["gemm_dec"][2] + p["gemm_dec_ln"][2] - 3 * Nl * w_layer) < 1
+    kv = sum(2 * (int(lens.sum()) + sh.batch * (t + 1)) * d * 2 for t in range(3)) * Nl
+    assert abs(p["attn_dec"][2] - kv) < 1
+    assert abs(p["gemm_prefill"][3] - 2 * int(lens.sum()) * Nl * (4 * d * d + 2 * d * f)) < 1
+    for name in ("gemm_prefill", "attn_prefill", "attn_dec", "gemm_dec", "gemm_dec_ln", "logits"):
+        assert p[name][0] > 0.0
+    eng.profile(False)
+    eng.decode_step(None)
+    torch.cuda.synchronize()
+    assert eng.profile_read()["attn_dec"][1] == 0        # switched off: nothing recorded after the reset
+    eng.close()
+
+
+@pytest.mark.parametrize("name,rows,batch", [
+    ("base_pruned_varlen", [0, 31, 63], 0),      # cfg 2, shortest batch (lengths 16..)
+    ("base_pruned_varlen", [0, 40, 63], 7),      # cfg 2, longest batch (lengths ..256)
+    ("large", [5, 127], 0),                      # cfg 3: 24 layers x 1024, batch 128, prompt 256, 64 tokens
+    ("decode_bound", [17, 255], 0),              # cfg 4: batch 256, prompt 512, 128 tokens
+])
+def test_full_size_configs_sampled_rows(E, name, rows, batch):
+    """The remaining benchmark configurations at full size; the oracle computes a sample of rows one by one."""
+    wl = make_workload(name)
+    sh = wl.shape
+    eng = E.engine_from_workload(wl)
+    ids, lens = wl.padded(batch)
+    _say(f"[parity] {name} batch {batch} rows {rows} lens {[int(lens[r]) for r in rows]}")
+    orc = oracle_generate(wl, batch, rows, sh.n_gen)
+    forced = {r: orc[r]["tokens"] for r in orc}
+    toks, hid, lg = gpu_generate(eng, ids, lens, sh.n_gen, forced)
+    st = check_rows(orc, toks, hid, lg, name)
+    _say(f"[parity] {name}: {st}")
+    eng.close()
