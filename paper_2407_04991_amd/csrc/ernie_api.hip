@@ -166,12 +166,13 @@ half_t* vcache(const ErnieHandle* h, int layer) {
 
 // Tile shape by problem size: large tiles halve the L2 -> LDS bytes per flop but need enough of them
 // to fill 256 CUs twice over; small problems take smaller tiles so that every CU holds several workgroups.
-template <int TM, int TN, int BK, int S, class Epi>
+template <int WGM, int WGN, int TM, int TN, int BK, int S, class Epi>
 void launch_gemm_prefill_t(const half_t* A, const half_t* Wp, const float* bias, int M, int N, int K, Epi epi,
                            hipStream_t s) {
-  using P = GemmPipe<TM, TN, BK, S>;
+  using P = GemmPipe<WGM, WGN, TM, TN, BK, S>;
   const int tiles_m = (M + P::kBM - 1) / P::kBM, tiles_n = (N + P::kBN - 1) / P::kBN;
-  hipLaunchKernelGGL((gemm_prefill2_kernel<TM, TN, BK, S, Epi>), dim3(tiles_m * tiles_n), dim3(256), P::kLdsBytes, s,
+  hipLaunchKernelGGL((gemm_prefill2_kernel<WGM, WGN, TM, TN, BK, S, Epi>), dim3(tiles_m * tiles_n), dim3(64 * WGM * WGN),
+                     P::kLdsBytes, s,
                      A, Wp, bias, M, N, K, (N + 31) / 32, tiles_n, epi);
 }
 
@@ -179,12 +180,12 @@ template <class Epi>
 void launch_gemm_prefill(ErnieHandle* h, const half_t* A, const half_t* Wp, const float* bias, int M, int N, int K,
                          Epi epi, hipStream_t s, int category = ERNIE_PROF_GEMM_PREFILL) {
   ProfScope prof(h, category, s, 2.0 * N * K, 2.0 * M * N * K);
-  const long tiles_256x128 = (long)((M + 255) / 256) * ((N + 127) / 128);
+  const long tiles_256x256 = (long)((M + 255) / 256) * ((N + 255) / 256);
   const long tiles_128x128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-  if (tiles_256x128 >= 512) launch_gemm_prefill_t<4, 2, 32, 2>(A, Wp, bias, M, N, K, epi, s);
-  else if (tiles_128x128 >= 384) launch_gemm_prefill_t<2, 2, 32, 3>(A, Wp, bias, M, N, K, epi, s);
-  else if (K >= 2048) launch_gemm_prefill_t<2, 1, 64, 3>(A, Wp, bias, M, N, K, epi, s);
-  else launch_gemm_prefill_t<2, 1, 32, 3>(A, Wp, bias, M, N, K, epi, s);
+  if (tiles_256x256 >= 512) launch_gemm_prefill_t<4, 4, 2, 2, 32, 3>(A, Wp, bias, M, N, K, epi, s);
+  else if (tiles_128x128 >= 384) launch_gemm_prefill_t<2, 2, 2, 2, 32, 3>(A, Wp, bias, M, N, K, epi, s);
+  else if (K >= 2048) launch_gemm_prefill_t<2, 2, 2, 1, 64, 3>(A, Wp, bias, M, N, K, epi, s);
+  else launch_gemm_prefill_t<2, 2, 2, 1, 32, 3>(A, Wp, bias, M, N, K, epi, s);
 }
 
 template <int MT, int NW>
@@ -210,12 +211,12 @@ int allow_lds(F* fn, size_t bytes) {
 
 int configure_kernels() {
   int rc = ERNIE_OK;
-#define GEMM_LDS(TM, TN, BK, S)                                                                            \
-  rc |= allow_lds(gemm_prefill2_kernel<TM, TN, BK, S, EpiQKV>, GemmPipe<TM, TN, BK, S>::kLdsBytes);       \
-  rc |= allow_lds(gemm_prefill2_kernel<TM, TN, BK, S, EpiResidual>, GemmPipe<TM, TN, BK, S>::kLdsBytes);  \
-  rc |= allow_lds(gemm_prefill2_kernel<TM, TN, BK, S, EpiGelu>, GemmPipe<TM, TN, BK, S>::kLdsBytes);      \
-  rc |= allow_lds(gemm_prefill2_kernel<TM, TN, BK, S, EpiRaw32>, GemmPipe<TM, TN, BK, S>::kLdsBytes)
-  GEMM_LDS(4, 2, 32, 2); GEMM_LDS(2, 2, 32, 3); GEMM_LDS(2, 1, 64, 3); GEMM_LDS(2, 1, 32, 3);
+#define GEMM_LDS(...)                                                                              \
+  rc |= allow_lds(gemm_prefill2_kernel<__VA_ARGS__, EpiQKV>, GemmPipe<__VA_ARGS__>::kLdsBytes);       \
+  rc |= allow_lds(gemm_prefill2_kernel<__VA_ARGS__, EpiResidual>, GemmPipe<__VA_ARGS__>::kLdsBytes);  \
+  rc |= allow_lds(gemm_prefill2_kernel<__VA_ARGS__, EpiGelu>, GemmPipe<__VA_ARGS__>::kLdsBytes);      \
+  rc |= allow_lds(gemm_prefill2_kernel<__VA_ARGS__, EpiRaw32>, GemmPipe<__VA_ARGS__>::kLdsBytes)
+  GEMM_LDS(4, 4, 2, 2, 32, 3); GEMM_LDS(2, 2, 2, 2, 32, 3); GEMM_LDS(2, 2, 2, 1, 64, 3); GEMM_LDS(2, 2, 2, 1, 32, 3);
 #undef GEMM_LDS
   const size_t big = (size_t)4 * 8 * 16 * 64 * 4;   // MT = 8, NW = 4
   rc |= allow_lds(logits_argmax_kernel<8, 4>, big);

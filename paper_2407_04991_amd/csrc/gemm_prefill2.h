@@ -1,12 +1,13 @@
 // Prefill GEMM on FP16 MFMA, asynchronous-copy pipeline:
 //   C[M, N] = A[M, K] * W[N, K]^T  (+ fused epilogue), fp32 accumulation.
 //
-// One workgroup (4 waves, 2 x 2, each TM x TN MFMA 32x32x16 tiles) owns a
-// (64 TM) x (64 TN) output tile and walks K in steps of BK through an S-stage ring in LDS.  Operands travel global -> LDS
+// One workgroup (WGM x WGN waves, each TM x TN MFMA 32x32x16 tiles) owns a
+// (32 WGM TM) x (32 WGN TN) output tile and walks K in steps of BK through an
+// S-stage ring in LDS.  Operands travel global -> LDS
 // directly (global_load_lds_dwordx4: lane l's 16 bytes land at LDS base + 16 l),
 // so no registers are spent on staging and S - 1 stages stay in flight per wave.
 //
-//   A stage  64 TM rows x BK halves, row-major, 16-byte chunks XOR-swizzled
+//   A stage  32 WGM TM rows x BK halves, row-major, 16-byte chunks XOR-swizzled
 //            (slot = chunk ^ ((row / rows_per_256B) % chunks_per_row)) so that a
 //            quarter-wave's 16-byte fragment reads fall on 64 distinct banks.  A
 //            load instruction covers 16 (BK = 32) or 8 (BK = 64) whole rows:
@@ -36,22 +37,23 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
-template <int TM, int TN, int BK, int S>
+template <int WGM, int WGN, int TM, int TN, int BK, int S>
 struct GemmPipe {
-  static constexpr int kBM = 64 * TM, kBN = 64 * TN;         // block tile: 2 x 2 waves of TM x TN MFMA tiles
+  static constexpr int kWaves = WGM * WGN;                   // WGM x WGN waves, each TM x TN MFMA tiles
+  static constexpr int kBM = 32 * WGM * TM, kBN = 32 * WGN * TN;
   static constexpr int kRowBytes = BK * 2;
   static constexpr int kChunks = kRowBytes / 16;             // 16-byte chunks per A row (4 or 8)
   static constexpr int kRowsPer256 = 256 / kRowBytes;        // rows sharing one 64-bank line (4 or 2)
   static constexpr int kRowsPerInstr = 64 / kChunks;         // rows one load instruction covers (16 or 8)
-  static constexpr int kAInstr = kBM / kRowsPerInstr / 4;    // A load instructions per wave per stage
+  static constexpr int kAInstr = kBM / kRowsPerInstr / kWaves;   // A load instructions per wave per stage
   static constexpr int kBFrags = (kBN / 32) * (BK / 16);     // W fragments per stage
-  static constexpr int kBInstr = (kBFrags + 3) / 4;          // W load instructions per wave per stage
+  static constexpr int kBInstr = (kBFrags + kWaves - 1) / kWaves;   // W load instructions per wave per stage
   static constexpr int kLoads = kAInstr + kBInstr;           // outstanding loads per wave per stage
   static constexpr int kAStage = kBM * kRowBytes;            // bytes
-  static constexpr int kBStage = kBInstr * 4 * 1024;         // bytes (rounded up to whole instructions)
+  static constexpr int kBStage = kBInstr * kWaves * 1024;    // bytes (rounded up to whole instructions)
   static constexpr int kStage = kAStage + kBStage;
   static constexpr int kLdsBytes = S * kStage;
-  static_assert(kAInstr >= 1 && kBM % (kRowsPerInstr * 4) == 0, "A tile must split evenly over 4 waves");
+  static_assert(kAInstr >= 1 && kBM % (kRowsPerInstr * kWaves) == 0, "A tile must split evenly over the waves");
 };
 
 // Workgroup id -> logical tile id such that the workgroups of one XCD (ids congruent mod 8) cover a
@@ -61,17 +63,19 @@ __device__ __forceinline__ int xcd_contiguous_id(int id, int total) {
   return x * q + min(x, r) + (id >> 3);
 }
 
-template <int TM, int TN, int BK, int S, class Epi>
-__global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void gemm_prefill2_kernel(const half_t* __restrict__ A,
+// DBG (measurement builds only, 0 in the library): 1 = no operand copies after the first stages,
+// 2 = fragments read from LDS once, 4 = no barrier / waits.
+template <int WGM, int WGN, int TM, int TN, int BK, int S, class Epi, int DBG = 0>
+__global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_prefill2_kernel(const half_t* __restrict__ A,
                                                             const half_t* __restrict__ Wp,
                                                             const float* __restrict__ bias, int M, int N, int K,
                                                             int n_tiles32, int tiles_n, Epi epi) {
-  using P = GemmPipe<TM, TN, BK, S>;
+  using P = GemmPipe<WGM, WGN, TM, TN, BK, S>;
   extern __shared__ __align__(16) unsigned char smem_raw[];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
   const int tile = xcd_contiguous_id(blockIdx.x, gridDim.x);
   const int tile_m = tile / tiles_n, tile_n = tile - tile_m * tiles_n;
   const int m0 = tile_m * P::kBM, n0 = tile_n * P::kBN;
@@ -129,21 +133,21 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void gemm_prefill2_ker
   for (int s = 0; s < S - 1; ++s)
     if (s < steps) issue(s, s);
 
+  half8 fa[2][TM], fb[2][TN];
   for (int step = 0; step < steps; ++step) {
     // stage `step` has landed once at most (S - 2) later stages of this wave are still in flight
-    if (step + S - 2 < steps) wait_vmcnt<(S - 2) * P::kLoads>(); else wait_vmcnt<0>();
+    if constexpr (!(DBG & 4)) { if (step + S - 2 < steps) wait_vmcnt<(S - 2) * P::kLoads>(); else wait_vmcnt<0>(); }
     // Plain s_barrier: __syncthreads() would add a fence that drains vmcnt to 0 and with it the pipeline.
     // Each wave has waited for its own share of the stage above; LDS reads below are issued after the
     // barrier in program order, and the compiler barriers keep them there.
     asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();     // every wave's share of the stage is visible; the stage computed last step is free
+    if constexpr (!(DBG & 4)) __builtin_amdgcn_s_barrier();     // every wave's share of the stage is visible; the stage computed last step is free
     asm volatile("" ::: "memory");
-    if (step + S - 1 < steps) issue((step + S - 1) % S, step + S - 1);
+    if constexpr (!(DBG & 1)) if (step + S - 1 < steps) issue((step + S - 1) % S, step + S - 1);
 
     const unsigned char* sa = smem_raw + (step % S) * P::kStage;
     const unsigned char* sb = sa + P::kAStage;
     // fragments of k-substep ks + 1 are read from LDS while the MFMAs of substep ks run
-    half8 fa[2][TM], fb[2][TN];
     auto read_frags = [&](int ks, int buf) {
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -152,10 +156,10 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void gemm_prefill2_ker
       for (int j = 0; j < TN; ++j)
         fb[buf][j] = *reinterpret_cast<const half8*>(sb + ((wn * TN + j) * (BK / 16) + ks) * 1024 + lane * 16);
     };
-    read_frags(0, 0);
+    if (!(DBG & 2) || step == 0) read_frags(0, 0);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      if (ks + 1 < BK / 16) read_frags(ks + 1, (ks + 1) & 1);
+      if constexpr (!(DBG & 2)) if (ks + 1 < BK / 16) read_frags(ks + 1, (ks + 1) & 1);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -163,18 +167,32 @@ __global__ __launch_bounds__(256, (TM * TN <= 8 ? 2 : 1)) void gemm_prefill2_ker
     }
   }
 
+  // ---- epilogue: every 32 x 32 accumulator tile goes through a private 32 x 33 fp32 patch of LDS
+  // (lane = column on the way in, 8 consecutive columns of one row on the way out), so that the
+  // epilogue functor stores runs of 8 columns instead of single elements.
+  __syncthreads();                       // all waves have finished reading the last stage
+  float* patch = reinterpret_cast<float*>(smem_raw) + wave * (32 * 33);
+  static_assert(P::kLdsBytes >= P::kWaves * 32 * 33 * 4, "the stage ring must hold one patch per wave");
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
-    const int col = n0 + wn * 32 * TN + j * 32 + (lane & 31);
-    if (col >= N) continue;
-    const float bv = bias[col];
+    const int colbase = n0 + wn * 32 * TN + j * 32;
+    const int mycol = colbase + (lane & 31);
+    const float bv = (mycol < N) ? bias[mycol] : 0.f;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm * 32 * TM + i * 32 + mfma32_row(v, lane);
-        if (row < M) epi(row, col, acc[i][j][v] + bv);
+      for (int v = 0; v < 16; ++v) patch[mfma32_row(v, lane) * 33 + (lane & 31)] = acc[i][j][v] + bv;
+      // same-wave LDS traffic: the compiler's lgkmcnt waits order the reads after the writes
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int r = t * 16 + (lane >> 2), c8 = (lane & 3) * 8;
+        float o[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) o[q] = patch[r * 33 + c8 + q];
+        const int row = m0 + wm * 32 * TM + i * 32 + r, col = colbase + c8;
+        if (row < M && col < N) epi.store8(row, col, o);
       }
+    }
   }
 }
 
