@@ -224,7 +224,6 @@ int configure_kernels() {
   rc |= allow_lds(gemm_dec_kernel<2, 8, EPI_RAW>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_ARGMAX>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<2, 8, EPI_ARGMAX>, kMaxLds);
-  rc |= allow_lds(gemm_dec_kernel<4, 8, EPI_RAW>, kMaxLds);
   return rc ? ERNIE_EHIP : ERNIE_OK;
 }
 
@@ -262,7 +261,6 @@ int launch_gemm_dec(ErnieHandle* h, DecGemmArgs a, int sk, hipStream_t s) {
   } while (0)
   if (MT == 1) DEC_LAUNCH(1, 8);
   else if (MT == 2) DEC_LAUNCH(2, 8);
-  else if (MT <= 4) DEC_LAUNCH(4, 8);
   else return ERNIE_EINVAL;
 #undef DEC_LAUNCH
   return ERNIE_OK;
@@ -340,62 +338,56 @@ int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hi
   return rc ? ERNIE_EHIP : ERNIE_OK;
 }
 
-// Split of the contraction for the medium-batch path: the smallest split whose A tile (128 rows) fits
-// in LDS and that yields at least ~160 workgroups (or the largest that fits).
-int pick_mid_split(int N, int K) {
-  const int strips = (N + 31) / 32;
-  int best = 0;
-  for (int sk : {1, 2, 3, 4, 6, 8}) {
-    if ((K / 16) % sk != 0 || dec_lds_bytes(4, 8, K / sk) > kMaxLds) continue;
+// Decode projections at B > 64: the batch is a real M dimension, so they run on the MFMA GEMM pipeline
+// (128 x 64 tiles) with the contraction split over gridDim.y until about 192 workgroups stream the
+// weights; partial results are fp32 [split][B][N].
+int pick_gemm_split(int B, int N, int K) {
+  const long tiles = (long)((B + 127) / 128) * ((N + 63) / 64);
+  int best = 1;
+  for (int sk = 1; sk <= kBigMaxSplitK; sk *= 2) {
+    if ((K / 32) % sk != 0 || K / sk < 128) break;
     best = sk;
-    if (strips * sk >= 160) break;
+    if (tiles * sk >= 192) break;
   }
   return best;
 }
 
-// Larger batches.  64 < B <= 128: the weight-streaming GEMM split over K writes fp32 partials.  B > 128:
-// the batch is a real M dimension and the projections run on the prefill MFMA GEMM (asynchronous-copy
-// pipeline) with raw fp32 or bias + GELU epilogues.  In both, row kernels add partials + bias + residual
-// and normalise (7-8 launches per layer); the step is bound by the cache stream of the attention.
+void launch_gemm_splitk(ErnieHandle* h, const half_t* A, const half_t* Wp, int M, int N, int K, float* out, int sk,
+                        hipStream_t s) {
+  ProfScope prof(h, ERNIE_PROF_GEMM_DEC, s, 2.0 * N * K, 2.0 * M * N * K);
+  using P = GemmPipe<2, 2, 2, 1, 32, 3>;
+  const int tiles_m = (M + P::kBM - 1) / P::kBM, tiles_n = (N + P::kBN - 1) / P::kBN;
+  hipLaunchKernelGGL((gemm_prefill2_kernel<2, 2, 2, 1, 32, 3, EpiRaw32>), dim3(tiles_m * tiles_n, sk), dim3(256),
+                     P::kLdsBytes, s, A, Wp, h->zero_bias, M, N, K, (N + 31) / 32, tiles_n,
+                     EpiRaw32{out, N, (size_t)M * N});
+}
+
+// Larger batches (B > 64): split-K MFMA GEMMs write fp32 partials; the attention prologue and two row
+// kernels add partials + bias (+ residual) and apply LayerNorm / GELU.  8 launches per layer; the step is
+// bound by the cache stream of the attention.
 int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipStream_t s) {
   const ErnieConfig& c = h->cfg;
   const int B = h->B, d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
-  const bool mid = B <= 128;
-  const int sk_q = mid ? pick_mid_split(3 * d, d) : 1, sk_o = mid ? pick_mid_split(d, d) : 1,
-            sk_1 = mid ? pick_mid_split(f, d) : 1, sk_2 = mid ? pick_mid_split(d, f) : 1;
-  if (!sk_q || !sk_o || !sk_1 || !sk_2) return ERNIE_EINVAL;
-  int rc = ERNIE_OK;
-  auto raw_gemm = [&](const half_t* A, const half_t* Wp, int N, int K, float* out, int sk) {
-    if (mid) {
-      DecGemmArgs a{};
-      a.B = B; a.Wp = Wp; a.N = N; a.K = K; a.a16 = A; a.rout = out;
-      rc |= launch_gemm_dec<EPI_RAW>(h, a, sk, s);
-    } else {
-      launch_gemm_prefill(h, A, Wp, h->zero_bias, B, N, K, EpiRaw32{out, N}, s, ERNIE_PROF_GEMM_DEC);
-    }
-  };
+  const int sk_q = pick_gemm_split(B, 3 * d, d), sk_o = pick_gemm_split(B, d, d), sk_1 = pick_gemm_split(B, f, d),
+            sk_2 = pick_gemm_split(B, d, f);
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerPtrs& L = h->layers[l];
-    raw_gemm(h->X, L.wqkv, 3 * d, d, h->r_qkv, sk_q);
+    launch_gemm_splitk(h, h->X, L.wqkv, B, 3 * d, d, h->r_qkv, sk_q, s);
     {
       ProfScope prof(h, ERNIE_PROF_ATTN_DEC, s, 2.0 * (h->sum_len + (double)B * (h->steps + 1)) * d * 2.0, 0.0);
       hipLaunchKernelGGL(attn_decode_fused_kernel, dim3(H, B), dim3(256), 0, s, h->r_qkv, sk_q, B, L.bqkv,
                          kcache(h, l), vcache(h, l), h->lens, H, S, d, h->O);
     }
-    raw_gemm(h->O, L.wo, d, d, h->r_out, sk_o);
+    launch_gemm_splitk(h, h->O, L.wo, B, d, d, h->r_out, sk_o, s);
     { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
       ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_out, sk_o,
                                          L.bo, h->X, B, d, L.ln1_g, L.ln1_b, c.ln_eps, h->X1, (float*)nullptr)); }
-    if (mid) {
-      raw_gemm(h->X1, L.w1, f, d, h->r_f1, sk_1);
-      ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
+    launch_gemm_splitk(h, h->X1, L.w1, B, f, d, h->r_f1, sk_1, s);
+    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
       const size_t n8 = (size_t)B * f / 8;
       hipLaunchKernelGGL(gelu_partials_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, h->r_f1, sk_1, L.b1,
-                         B, f, h->G);
-    } else {
-      launch_gemm_prefill(h, h->X1, L.w1, L.b1, B, f, d, EpiGelu{h->G, f}, s, ERNIE_PROF_GEMM_DEC);
-    }
-    raw_gemm(h->G, L.w2, d, f, h->r_f2, sk_2);
+                         B, f, h->G); }
+    launch_gemm_splitk(h, h->G, L.w2, B, d, f, h->r_f2, sk_2, s);
     { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
       float* hid = (l == c.n_layers - 1) ? hidden_out : nullptr;
       ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_f2, sk_2,
@@ -403,7 +395,7 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
   }
   { ProfScope prof(h, ERNIE_PROF_LOGITS, s, 2.0 * c.vocab_kept * d, 2.0 * B * c.vocab_kept * d);
     launch_logits(h, h->X, B, logits_out, s); }
-  return rc ? ERNIE_EHIP : ERNIE_OK;
+  return ERNIE_OK;
 }
 
 void pack_into(const void* src, half_t* dst, int N, int K, hipStream_t s) {

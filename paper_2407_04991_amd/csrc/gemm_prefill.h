@@ -66,12 +66,14 @@ struct EpiGelu {
   }
 };
 
-// Raw fp32 output [M, N] (decode step at large batch: the consumer kernels add bias and residual).
+// Raw fp32 output [gridDim.y][M, N]: one partial buffer per split of the contraction (decode step at
+// large batch: the consumer kernels add the partials, bias and residual).
 struct EpiRaw32 {
   float* r;
   int N;
+  size_t slab;   // M * N
   __device__ __forceinline__ void store8(int row, int col, const float (&v)[8]) const {
-    float* dst = r + (size_t)row * N + col;
+    float* dst = r + blockIdx.y * slab + (size_t)row * N + col;
     *reinterpret_cast<float4*>(dst) = float4{v[0], v[1], v[2], v[3]};
     *reinterpret_cast<float4*>(dst + 4) = float4{v[4], v[5], v[6], v[7]};
   }

@@ -80,7 +80,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
   const int tile_m = tile / tiles_n, tile_n = tile - tile_m * tiles_n;
   const int m0 = tile_m * P::kBM, n0 = tile_n * P::kBN;
   const int k_tiles = K / 16;
-  const int steps = K / BK;
+  // gridDim.y > 1 splits the contraction: workgroup y accumulates k in [y, y + 1) * K / gridDim.y and the
+  // epilogue functor routes the partial result by blockIdx.y (host guarantees divisibility by BK)
+  const int steps = K / BK / gridDim.y;
+  const int kbeg = blockIdx.y * steps * BK;
 
   // ---- per-lane source addresses of this wave's load instructions (k offset added per step)
   const half_t* a_src[P::kAInstr];
@@ -88,7 +91,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
   for (int i = 0; i < P::kAInstr; ++i) {
     const int r = (wave * P::kAInstr + i) * P::kRowsPerInstr + lane / P::kChunks;     // row inside the tile
     const int c = (lane % P::kChunks) ^ ((r / P::kRowsPer256) % P::kChunks);          // global chunk that lands in slot lane % kChunks
-    a_src[i] = A + (size_t)min(m0 + r, M - 1) * K + c * 8;
+    a_src[i] = A + (size_t)min(m0 + r, M - 1) * K + kbeg + c * 8;
   }
   // W fragment f of a stage = (n-tile f / (BK/16), k-tile f % (BK/16)); wave w copies fragments w*kBInstr + j
   const half_t* b_src[P::kBInstr];
@@ -96,7 +99,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
   for (int j = 0; j < P::kBInstr; ++j) {
     const int f = min(wave * P::kBInstr + j, P::kBFrags - 1);
     const int nt = min(n0 / 32 + f / (BK / 16), n_tiles32 - 1);
-    b_src[j] = Wp + packed_frag_offset(nt, f % (BK / 16), k_tiles) + lane * 8;
+    b_src[j] = Wp + packed_frag_offset(nt, kbeg / 16 + f % (BK / 16), k_tiles) + lane * 8;
   }
 
   auto issue = [&](int stage, int kstep) {
