@@ -162,17 +162,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_kernel(DecGemmArgs p) {
 }
 
 // A = LayerNorm(sum_k partial_k + bias + residual), normalised in the prologue.
-// grid = (column strips, 1, ceil(B / NW)): a workgroup owns NW batch rows (one per
+// grid = (column strips, 1, ceil(B / R)), R = NW * RPW: a workgroup owns R batch rows (RPW per
 // wave) of one 32-column strip, so the redundant normalisation work per workgroup
-// is NW rows, not the whole batch; the row groups of a strip read the same weight
-// fragments (from L2 after the first).  The MFMA tile is fed rows 0..NW-1 repeated;
-// only accumulator rows < NW are reduced and stored.
-template <int NW, int EPI, int RC, int SKIN>
+// is R rows, not the whole batch; the row groups of a strip read the same weight
+// fragments (from L2 after the first).  The MFMA tile is fed rows 0..R-1 repeated;
+// only the accumulator registers that hold rows < R are reduced and stored.
+template <int NW, int EPI, int RC, int SKIN, int RPW>
 __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
-  static_assert(NW == 8, "row groups are 8 rows: accumulator registers 0..3 of each half-wave");
+  constexpr int R = NW * RPW;                 // rows per workgroup: 8, 16 or 32
+  constexpr int NV = R / 2;                   // accumulator registers holding rows < R (row = 8(v/4) + 4(lane/32) + v%4)
+  static_assert(NW == 8 && (RPW == 1 || RPW == 2 || RPW == 4), "row groups of 8, 16 or 32 rows");
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  half_t* sA = reinterpret_cast<half_t*>(smem_raw);            // [NW][K + 8]
-  float* red = reinterpret_cast<float*>(smem_raw);             // [NW][4][64], reused after the MFMA loop
+  half_t* sA = reinterpret_cast<half_t*>(smem_raw);            // [R][K + 8]
+  float* red = reinterpret_cast<float*>(smem_raw);             // [NW][NV][64], reused after the MFMA loop
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   const int k_tiles = K / 16;
   const int pitch = K + 8;
   const int kb = k_tiles * wave / NW, ke = k_tiles * (wave + 1) / NW;
-  const int row0 = blockIdx.z * NW;
+  const int row0 = blockIdx.z * R;
 
   const half_t* wp = p.Wp + packed_frag_offset(nt, 0, k_tiles) + lane * 8;
   half8 wf[kDecMaxFrag];
@@ -191,80 +193,103 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
     wf[u] = (kb + u < ke) ? *reinterpret_cast<const half8*>(wp + (size_t)(kb + u) * 512) : z;
   }
 
-  // prologue: wave w normalises row row0 + w.  Loads are unconditional with clamped addresses (a row
-  // >= B or a chunk past the row end re-reads a valid location and is masked): predicated loads would
-  // be issued one at a time.
+  // prologue: wave w normalises rows row0 + w * RPW + i.  Loads are unconditional with clamped addresses
+  // (a row >= B or a chunk past the row end re-reads a valid location and is masked): predicated loads
+  // would be issued one at a time.  SKIN is a compile-time count so that the loads of every split-K
+  // partial are in flight together; partials are added in index order.
   {
     const int chunks = K / 8;
-    const int r = row0 + wave;
-    const int rr = min(r, B - 1);
-    float v[RC][8], g[RC][8], bt[RC][8];
-    const float* src[RC];
+    float v[RPW][RC][8], g[RC][8], bt[RC][8], bs[RC][8];
 #pragma unroll
     for (int c = 0; c < RC; ++c) {
       const int cc = min(c * 64 + lane, chunks - 1);
-      src[c] = p.r32 + (size_t)rr * K + cc * 8;
-      const half8 rs = *reinterpret_cast<const half8*>(p.res + (size_t)rr * K + cc * 8);
-      const float4 x0 = *reinterpret_cast<const float4*>(src[c]);
-      const float4 x1 = *reinterpret_cast<const float4*>(src[c] + 4);
       const float4 b0 = *reinterpret_cast<const float4*>(p.bias + cc * 8);
       const float4 b1 = *reinterpret_cast<const float4*>(p.bias + cc * 8 + 4);
       const float4 g0 = *reinterpret_cast<const float4*>(p.gamma + cc * 8);
       const float4 g1 = *reinterpret_cast<const float4*>(p.gamma + cc * 8 + 4);
       const float4 t0 = *reinterpret_cast<const float4*>(p.beta + cc * 8);
       const float4 t1 = *reinterpret_cast<const float4*>(p.beta + cc * 8 + 4);
-      v[c][0] = x0.x + b0.x + (float)rs[0]; v[c][1] = x0.y + b0.y + (float)rs[1];
-      v[c][2] = x0.z + b0.z + (float)rs[2]; v[c][3] = x0.w + b0.w + (float)rs[3];
-      v[c][4] = x1.x + b1.x + (float)rs[4]; v[c][5] = x1.y + b1.y + (float)rs[5];
-      v[c][6] = x1.z + b1.z + (float)rs[6]; v[c][7] = x1.w + b1.w + (float)rs[7];
+      bs[c][0] = b0.x; bs[c][1] = b0.y; bs[c][2] = b0.z; bs[c][3] = b0.w;
+      bs[c][4] = b1.x; bs[c][5] = b1.y; bs[c][6] = b1.z; bs[c][7] = b1.w;
       g[c][0] = g0.x; g[c][1] = g0.y; g[c][2] = g0.z; g[c][3] = g0.w;
       g[c][4] = g1.x; g[c][5] = g1.y; g[c][6] = g1.z; g[c][7] = g1.w;
       bt[c][0] = t0.x; bt[c][1] = t0.y; bt[c][2] = t0.z; bt[c][3] = t0.w;
       bt[c][4] = t1.x; bt[c][5] = t1.y; bt[c][6] = t1.z; bt[c][7] = t1.w;
     }
-    // further split-K partials (SKIN is a compile-time count so that all their loads are in flight together
-    // with the first partial's), added in index order
-    float4 y0[SKIN > 1 ? SKIN - 1 : 1][RC], y1[SKIN > 1 ? SKIN - 1 : 1][RC];
 #pragma unroll
-    for (int s = 1; s < SKIN; ++s)
-#pragma unroll
-      for (int c = 0; c < RC; ++c) {
-        y0[s - 1][c] = *reinterpret_cast<const float4*>(src[c] + (size_t)s * B * K);
-        y1[s - 1][c] = *reinterpret_cast<const float4*>(src[c] + (size_t)s * B * K + 4);
-      }
-#pragma unroll
-    for (int s = 1; s < SKIN; ++s)
+    for (int i = 0; i < RPW; ++i) {
+      const int rr = min(row0 + wave * RPW + i, B - 1);
+      half8 rs[RC];
+      float4 y0[SKIN][RC], y1[SKIN][RC];
 #pragma unroll
       for (int c = 0; c < RC; ++c) {
-        v[c][0] += y0[s - 1][c].x; v[c][1] += y0[s - 1][c].y; v[c][2] += y0[s - 1][c].z; v[c][3] += y0[s - 1][c].w;
-        v[c][4] += y1[s - 1][c].x; v[c][5] += y1[s - 1][c].y; v[c][6] += y1[s - 1][c].z; v[c][7] += y1[s - 1][c].w;
+        const int cc = min(c * 64 + lane, chunks - 1);
+        rs[c] = *reinterpret_cast<const half8*>(p.res + (size_t)rr * K + cc * 8);
+#pragma unroll
+        for (int s = 0; s < SKIN; ++s) {
+          const float* src = p.r32 + ((size_t)s * B + rr) * K + cc * 8;
+          y0[s][c] = *reinterpret_cast<const float4*>(src);
+          y1[s][c] = *reinterpret_cast<const float4*>(src + 4);
+        }
       }
-    float sum = 0.f;
 #pragma unroll
-    for (int c = 0; c < RC; ++c) {
-      const float live = (c * 64 + lane < chunks) ? 1.f : 0.f;   // the duplicated tail chunk stays out of the sums
+      for (int c = 0; c < RC; ++c) {
+        float a[8] = {y0[0][c].x, y0[0][c].y, y0[0][c].z, y0[0][c].w, y1[0][c].x, y1[0][c].y, y1[0][c].z, y1[0][c].w};
 #pragma unroll
-      for (int j = 0; j < 8; ++j) { v[c][j] *= live; sum += v[c][j]; }
+        for (int s = 1; s < SKIN; ++s) {
+          a[0] += y0[s][c].x; a[1] += y0[s][c].y; a[2] += y0[s][c].z; a[3] += y0[s][c].w;
+          a[4] += y1[s][c].x; a[5] += y1[s][c].y; a[6] += y1[s][c].z; a[7] += y1[s][c].w;
+        }
+        const float live = (c * 64 + lane < chunks) ? 1.f : 0.f;   // the duplicated tail chunk stays out of the sums
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[i][c][j] = (a[j] + bs[c][j] + (float)rs[c][j]) * live;
+      }
     }
-    const float mean = wave_sum(sum) / (float)K;
-    float q = 0.f;
+    float mean[RPW], rstd[RPW];
 #pragma unroll
-    for (int c = 0; c < RC; ++c) {
-      const float live = (c * 64 + lane < chunks) ? 1.f : 0.f;
+    for (int i = 0; i < RPW; ++i) {
+      float sum = 0.f;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) { const float t = (v[c][j] - mean) * live; q += t * t; }
+      for (int c = 0; c < RC; ++c)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sum += v[i][c][j];
+      mean[i] = sum;
     }
-    const float rstd = rsqrtf(wave_sum(q) / (float)K + p.eps);
-    const bool writer = p.xout && blockIdx.x == 0 && r < B;
 #pragma unroll
-    for (int c = 0; c < RC; ++c) {
-      const int ch = c * 64 + lane;
-      if (ch < chunks) {
-        half8 o;
+    for (int o = 32; o > 0; o >>= 1)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] = (half_t)((v[c][j] - mean) * rstd * g[c][j] + bt[c][j]);
-        *reinterpret_cast<half8*>(sA + wave * pitch + ch * 8) = o;
-        if (writer) *reinterpret_cast<half8*>(p.xout + (size_t)r * K + ch * 8) = o;
+      for (int i = 0; i < RPW; ++i) mean[i] += __shfl_xor(mean[i], o, 64);
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+      mean[i] /= (float)K;
+      float q = 0.f;
+#pragma unroll
+      for (int c = 0; c < RC; ++c) {
+        const float live = (c * 64 + lane < chunks) ? 1.f : 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { const float t = (v[i][c][j] - mean[i]) * live; q += t * t; }
+      }
+      rstd[i] = q;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+#pragma unroll
+      for (int i = 0; i < RPW; ++i) rstd[i] += __shfl_xor(rstd[i], o, 64);
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+      const int r = row0 + wave * RPW + i;
+      const float rs = rsqrtf(rstd[i] / (float)K + p.eps);
+      const bool writer = p.xout && blockIdx.x == 0 && r < B;
+#pragma unroll
+      for (int c = 0; c < RC; ++c) {
+        const int ch = c * 64 + lane;
+        if (ch < chunks) {
+          half8 o;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) o[j] = (half_t)((v[i][c][j] - mean[i]) * rs * g[c][j] + bt[c][j]);
+          *reinterpret_cast<half8*>(sA + (wave * RPW + i) * pitch + ch * 8) = o;
+          if (writer) *reinterpret_cast<half8*>(p.xout + (size_t)r * K + ch * 8) = o;
+        }
       }
     }
   }
@@ -273,7 +298,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   floatx16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-  const half_t* ap = sA + (lane & 7) * pitch + 8 * (lane >> 5);    // tile rows 8..31 repeat rows 0..7
+  const half_t* ap = sA + (lane & (R - 1)) * pitch + 8 * (lane >> 5);    // tile rows R..31 repeat rows 0..R-1
   for (int base = kb; base < ke; base += kDecMaxFrag) {
 #pragma unroll
     for (int u = 0; u < kDecMaxFrag; ++u)
@@ -289,16 +314,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   }
   __syncthreads();
 
-  // accumulator registers 0..3 hold tile rows 4 * (lane / 32) + v, i.e. the NW = 8 real rows
 #pragma unroll
-  for (int v = 0; v < 4; ++v) red[(wave * 4 + v) * 64 + lane] = acc[v];
+  for (int v = 0; v < NV; ++v) red[(wave * NV + v) * 64 + lane] = acc[v];
   __syncthreads();
-  if (wave < 4) {
-    const int v = wave;
+  for (int v = wave; v < NV; v += NW) {
     float s = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) s += red[(w * 4 + v) * 64 + lane];
-    dec_epilogue<EPI>(p, nt, lane, row0 + 4 * (lane >> 5) + v, nt * 32 + (lane & 31), s);
+    for (int w = 0; w < NW; ++w) s += red[(w * NV + v) * 64 + lane];
+    dec_epilogue<EPI>(p, nt, lane, row0 + mfma32_row(v, lane), nt * 32 + (lane & 31), s);
   }
 }
 

@@ -220,6 +220,9 @@ int configure_kernels() {
 #undef GEMM_LDS
   const size_t big = (size_t)4 * 8 * 16 * 64 * 4;   // MT = 8, NW = 4
   rc |= allow_lds(logits_argmax_kernel<8, 4>, big);
+#define LN_LDS(EPI, SK) rc |= allow_lds(gemm_dec_ln_kernel<8, EPI, 2, SK, 1>, kMaxLds)
+  LN_LDS(EPI_RAW, 1); LN_LDS(EPI_RAW, 2); LN_LDS(EPI_RAW, 4); LN_LDS(EPI_GELU16, 1); LN_LDS(EPI_GELU16, 2); LN_LDS(EPI_GELU16, 4);
+#undef LN_LDS
   rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_RAW>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<2, 8, EPI_RAW>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_ARGMAX>, kMaxLds);
@@ -271,15 +274,20 @@ int launch_gemm_dec_ln(ErnieHandle* h, DecGemmArgs a, hipStream_t s) {
   constexpr int NW = 8;
   ProfScope prof(h, ERNIE_PROF_GEMM_DEC_LN, s, 2.0 * a.N * a.K, 2.0 * a.B * a.N * a.K);
   if (a.K > 1024) return ERNIE_EINVAL;                 // the LayerNorm prologue holds rows of <= 1024 features
-  const size_t lds = (size_t)NW * (a.K + 8) * 2;      // >= the 8 KiB the reduction reuses
-  const dim3 grid((a.N + 31) / 32, 1, (a.B + NW - 1) / NW), block(NW * 64);
-  const size_t ldsz = lds < 8192 ? 8192 : lds;
+  constexpr int rpw = 1, R = NW * rpw;   // 8-row groups measured fastest (16 equal, 32 slower)
+  const size_t a_bytes = (size_t)R * (a.K + 8) * 2, r_bytes = (size_t)NW * (R / 2) * 64 * 4;
+  const size_t lds = a_bytes > r_bytes ? a_bytes : r_bytes;
+  const dim3 grid((a.N + 31) / 32, 1, (a.B + R - 1) / R), block(NW * 64);
+#define LN_LAUNCH(SK, RPW) hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2, SK, RPW>), grid, block, lds, s, a)
+#define LN_BY_RPW(SK) LN_LAUNCH(SK, 1)
   switch (a.sk_in) {      // the count of split-K partials to add is a template parameter of the prologue
-    case 1: hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2, 1>), grid, block, ldsz, s, a); break;
-    case 2: hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2, 2>), grid, block, ldsz, s, a); break;
-    case 4: hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2, 4>), grid, block, ldsz, s, a); break;
+    case 1: LN_BY_RPW(1); break;
+    case 2: LN_BY_RPW(2); break;
+    case 4: LN_BY_RPW(4); break;
     default: return ERNIE_EINVAL;
   }
+#undef LN_BY_RPW
+#undef LN_LAUNCH
   return ERNIE_OK;
 }
 
