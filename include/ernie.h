@@ -189,6 +189,8 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
  *   "fused_decode" 0/1  use the small-batch path (row-wise work fused into GEMM prologues) when it fits,
  *                       else the large-batch path (split-K partials summed by row kernels)
  *   "sk_out", "sk_f2"   split of the contraction of the attention-output / second FFN GEMM over workgroups
+ *   "attn_dec" 0..3     decode attention shape: 0 = chosen from max_seq, 1 = 4 waves x 4 key groups in flight,
+ *                       2 = 8 waves x 3, 3 = 8 waves x 4 (a batch of waves x groups x 8 keys per memory round trip)
  * Splits are 1, 2 or 4.  Results are deterministic for any fixed setting.  Returns ERNIE_EINVAL for an
  * unknown key or a split that is not supported or does not divide the k-tile count.
  */

@@ -156,10 +156,10 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const half_t* __restr
 
 // ---------------------------------------------------------------- decode
 
-// One workgroup (4 waves) per (head, sequence).  Lane l of a wave reads 16
+// One workgroup (NW waves) per (head, sequence).  Lane l of a wave reads 16
 // bytes (8 head-dim values, chunk l % 8) of key row (l / 8) of an 8-row group,
 // so one wave load instruction covers 1 KiB of contiguous cache.  Wave w takes
-// the 8-row groups g with g % 4 == w.  Every 8-lane team keeps an online
+// U consecutive 8-row groups out of every NW * U.  Every 8-lane team keeps an online
 // softmax (max, sum, 8 output values) over its own rows; teams are merged by
 // shuffles, waves through LDS.
 struct SoftmaxPart {
@@ -181,39 +181,39 @@ __device__ __forceinline__ void softmax_merge(SoftmaxPart& a, float om, float ol
 // new key and value are rounded to fp16, appended to the cache (slot
 // cache_len[b]) and used from registers, so the cache is never read back in
 // the kernel that writes it.
-__global__ __launch_bounds__(256) void attn_decode_fused_kernel(const float* __restrict__ Rqkv,   // [sk_in][B, 3d] fp32 split-K partials
-                                                                int sk_in, int B,
-                                                                const float* __restrict__ bqkv,   // [3d]
-                                                                half_t* __restrict__ Kc, half_t* __restrict__ Vc,
-                                                                const int* __restrict__ cache_len, int H, int S,
-                                                                int d, half_t* __restrict__ O) {
-  __shared__ float sm[4][8][10];
+//
+// NW waves, U groups in flight per wave: one batch covers NW * U * 8 keys, and the host picks
+// (NW, U) so that a short cache is covered by a single batch.  The first batch is requested before
+// the cached length is known (bounded by the capacity S only: the cache is allocated up to S, and
+// whatever lies past the valid length is masked out after the fact), so the length, the cache
+// stream and the raw q, k, v are all fetched in one memory round trip instead of three.
+template <int NW, int U>
+__global__ __launch_bounds__(NW * 64) void attn_decode_fused_kernel(const float* __restrict__ Rqkv,   // [sk_in][B, 3d] fp32 split-K partials
+                                                                    int sk_in, int B,
+                                                                    const float* __restrict__ bqkv,   // [3d]
+                                                                    half_t* __restrict__ Kc, half_t* __restrict__ Vc,
+                                                                    const int* __restrict__ cache_len, int H, int S,
+                                                                    int d, half_t* __restrict__ O) {
+  __shared__ float sm[NW][8][10];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int h = blockIdx.x, b = blockIdx.y;
-  const int len = cache_len[b];
-  const bool has_new = len < S;                 // a replayed step past capacity appends nothing
-  const int c = has_new ? len + 1 : S;
-  const int newest = has_new ? len : -1;        // this key comes from registers, not from the cache
   const int ec = lane & 7, team = lane >> 3;
   half_t* Kb = Kc + ((size_t)b * H + h) * S * 64 + ec * 8;
   half_t* Vb = Vc + ((size_t)b * H + h) * S * 64 + ec * 8;
 
-  constexpr int U = 4;                           // 8-row groups in flight per wave
   half8 kf[U], vf[U];
   int key[U];
-  auto load_groups = [&](int g0) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      key[u] = (g0 + u) * 8 + team;
-      const bool from_cache = key[u] < c && key[u] != newest;
-      const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      kf[u] = from_cache ? *reinterpret_cast<const half8*>(Kb + (size_t)key[u] * 64) : z;
-      vf[u] = from_cache ? *reinterpret_cast<const half8*>(Vb + (size_t)key[u] * 64) : z;
-    }
-  };
   int g0 = wave * U;
-  load_groups(g0);                               // the cache stream starts before the prologue arithmetic
+  // first batch: addresses clamped to the capacity, validity decided later
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    key[u] = (g0 + u) * 8 + team;
+    const size_t row = (size_t)min(key[u], S - 1) * 64;
+    kf[u] = *reinterpret_cast<const half8*>(Kb + row);
+    vf[u] = *reinterpret_cast<const half8*>(Vb + row);
+  }
+  const int len = cache_len[b];
 
   float q[8];
   half8 knew, vnew;
@@ -235,6 +235,9 @@ __global__ __launch_bounds__(256) void attn_decode_fused_kernel(const float* __r
       vnew[j] = (half_t)av[j];
     }
   }
+  const bool has_new = len < S;                 // a replayed step past capacity appends nothing
+  const int c = has_new ? len + 1 : S;
+  const int newest = has_new ? len : -1;        // this key comes from registers, not from the cache
   if (has_new && wave == 0 && team == 0) {
     *reinterpret_cast<half8*>(Kb + (size_t)len * 64) = knew;
     *reinterpret_cast<half8*>(Vb + (size_t)len * 64) = vnew;
@@ -248,8 +251,11 @@ __global__ __launch_bounds__(256) void attn_decode_fused_kernel(const float* __r
   while (g0 * 8 < c) {
     float s[U];
     float mx = st.m;
+    half8 vcur[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+      const bool valid = key[u] < c;
+      const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
       if (key[u] == newest) { kf[u] = knew; vf[u] = vnew; }
       float p = 0.f;
 #pragma unroll
@@ -257,14 +263,20 @@ __global__ __launch_bounds__(256) void attn_decode_fused_kernel(const float* __r
       p += __shfl_xor(p, 1, 64);
       p += __shfl_xor(p, 2, 64);
       p += __shfl_xor(p, 4, 64);
-      s[u] = (key[u] < c) ? p : -INFINITY;
+      s[u] = valid ? p : -INFINITY;
+      vcur[u] = valid ? vf[u] : z;               // rows past the valid length hold arbitrary bits: weight 0 must meet value 0
       mx = fmaxf(mx, s[u]);
     }
-    half8 vcur[U];
+    g0 += NW * U;
+    if (g0 * 8 < c) {                            // next batch in flight during the softmax update
 #pragma unroll
-    for (int u = 0; u < U; ++u) vcur[u] = vf[u];
-    g0 += 4 * U;
-    if (g0 * 8 < c) load_groups(g0);             // next batch in flight during the softmax update
+      for (int u = 0; u < U; ++u) {
+        key[u] = (g0 + u) * 8 + team;
+        const size_t row = (size_t)min(key[u], S - 1) * 64;
+        kf[u] = *reinterpret_cast<const half8*>(Kb + row);
+        vf[u] = *reinterpret_cast<const half8*>(Vb + row);
+      }
+    }
     if (mx != -INFINITY) {
       const float alpha = (st.m == -INFINITY) ? 0.f : __expf(st.m - mx);
       st.l *= alpha;
@@ -297,7 +309,7 @@ __global__ __launch_bounds__(256) void attn_decode_fused_kernel(const float* __r
   __syncthreads();
   if (wave == 0 && team == 0) {
 #pragma unroll
-    for (int w = 1; w < 4; ++w) softmax_merge(st, sm[w][ec][0], sm[w][ec][1], &sm[w][ec][2]);
+    for (int w = 1; w < NW; ++w) softmax_merge(st, sm[w][ec][0], sm[w][ec][1], &sm[w][ec][2]);
     const float inv = 1.0f / st.l;
     half8 o;
 #pragma unroll

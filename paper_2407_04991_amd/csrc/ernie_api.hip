@@ -123,7 +123,7 @@ struct ErnieHandle {
   std::vector<LayerPtrs> layers;
   half_t *kv, *X, *X1, *Y, *Q, *O, *G, *hlast;
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
-  int sk_out, sk_f2, fused_decode;   // decode tuning (see ernie_debug_tune)
+  int sk_out, sk_f2, fused_decode, attn_dec;   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   int* staging;          // pinned host: kStagingSlots x (max_batch + 1) ints
   int staging_next;
@@ -162,6 +162,22 @@ half_t* kcache(const ErnieHandle* h, int layer) {
 half_t* vcache(const ErnieHandle* h, int layer) {
   const size_t per = (size_t)h->cfg.max_batch * h->cfg.max_seq * h->cfg.d_model;
   return h->kv + ((size_t)layer * 2 + 1) * per;
+}
+
+// Decode attention: (waves, groups in flight per wave) chosen so that one batch of NW * U * 8 keys covers
+// the whole cache when the capacity allows it (a single memory round trip); long caches stream with 4 waves.
+void launch_attn_decode(const ErnieHandle* h, const float* rqkv, int sk_in, int B, const float* bqkv, half_t* kc,
+                        half_t* vc, hipStream_t s) {
+  const int H = h->cfg.n_heads, S = h->cfg.max_seq, d = h->cfg.d_model;
+  int v = h->attn_dec;
+  if (v == 0) v = 1;   // measured: the three shapes are within 5 % of each other at every cache length tried
+#define ATTN_DEC_LAUNCH(NW, U)                                                                                  \
+  hipLaunchKernelGGL((attn_decode_fused_kernel<NW, U>), dim3(H, B), dim3(NW * 64), 0, s, rqkv, sk_in, B, bqkv, \
+                     kc, vc, h->lens, H, S, d, h->O)
+  if (v == 2) ATTN_DEC_LAUNCH(8, 3);
+  else if (v == 3) ATTN_DEC_LAUNCH(8, 4);
+  else ATTN_DEC_LAUNCH(4, 4);
+#undef ATTN_DEC_LAUNCH
 }
 
 // Tile shape by problem size: large tiles halve the L2 -> LDS bytes per flop but need enough of them
@@ -301,7 +317,7 @@ bool fused_decode_fits(const ErnieHandle* h, int B) {
 
 int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hipStream_t s) {
   const ErnieConfig& c = h->cfg;
-  const int B = h->B, d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
+  const int B = h->B, d = c.d_model, f = c.d_ffn;
   int rc = ERNIE_OK;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerPtrs& L = h->layers[l];
@@ -321,8 +337,7 @@ int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hi
     {
       // K and V of every visible position (cached + the appended one), 2 bytes each
       ProfScope prof(h, ERNIE_PROF_ATTN_DEC, s, 2.0 * (h->sum_len + (double)B * (h->steps + 1)) * d * 2.0, 0.0);
-      hipLaunchKernelGGL(attn_decode_fused_kernel, dim3(H, B), dim3(256), 0, s, h->r_qkv, 1, B, L.bqkv, kcache(h, l),
-                         vcache(h, l), h->lens, H, S, d, h->O);
+      launch_attn_decode(h, h->r_qkv, 1, B, L.bqkv, kcache(h, l), vcache(h, l), s);
     }
     DecGemmArgs o{};
     o.B = B; o.Wp = L.wo; o.N = d; o.K = d; o.a16 = h->O; o.rout = h->r_out;
@@ -375,7 +390,7 @@ void launch_gemm_splitk(ErnieHandle* h, const half_t* A, const half_t* Wp, int M
 // bound by the cache stream of the attention.
 int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipStream_t s) {
   const ErnieConfig& c = h->cfg;
-  const int B = h->B, d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
+  const int B = h->B, d = c.d_model, f = c.d_ffn;
   const int sk_q = pick_gemm_split(B, 3 * d, d), sk_o = pick_gemm_split(B, d, d), sk_1 = pick_gemm_split(B, f, d),
             sk_2 = pick_gemm_split(B, d, f);
   for (int l = 0; l < c.n_layers; ++l) {
@@ -383,8 +398,7 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
     launch_gemm_splitk(h, h->X, L.wqkv, B, 3 * d, d, h->r_qkv, sk_q, s);
     {
       ProfScope prof(h, ERNIE_PROF_ATTN_DEC, s, 2.0 * (h->sum_len + (double)B * (h->steps + 1)) * d * 2.0, 0.0);
-      hipLaunchKernelGGL(attn_decode_fused_kernel, dim3(H, B), dim3(256), 0, s, h->r_qkv, sk_q, B, L.bqkv,
-                         kcache(h, l), vcache(h, l), h->lens, H, S, d, h->O);
+      launch_attn_decode(h, h->r_qkv, sk_q, B, L.bqkv, kcache(h, l), vcache(h, l), s);
     }
     launch_gemm_splitk(h, h->O, L.wo, B, d, d, h->r_out, sk_o, s);
     { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
@@ -467,6 +481,7 @@ int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* w, void* aren
   h->Yf = F32(plan.Yf); h->strip_val = F32(plan.strip_val);
   h->r_qkv = F32(plan.r_qkv); h->r_out = F32(plan.r_out); h->r_f1 = F32(plan.r_f1); h->r_f2 = F32(plan.r_f2); h->zero_bias = F32(plan.zero_bias);
   h->fused_decode = 1;
+  h->attn_dec = 0;
   h->sk_out = pick_split_k(cfg->d_model / 32, cfg->d_model / 16, 2);
   h->sk_f2 = pick_split_k(cfg->d_model / 32, cfg->d_ffn / 16, 4);
   h->strip_idx = I32(plan.strip_idx); h->cu = I32(plan.cu); h->lens = I32(plan.lens);
@@ -656,6 +671,11 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
 int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!h || !key) return ERNIE_EINVAL;
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
+  if (!strcmp(key, "attn_dec")) {
+    if (value < 0 || value > 3) return ERNIE_EINVAL;
+    h->attn_dec = value;
+    return ERNIE_OK;
+  }
   if (!strcmp(key, "sk_out") || !strcmp(key, "sk_f2")) {
     const int k_tiles = (!strcmp(key, "sk_out") ? h->cfg.d_model : h->cfg.d_ffn) / 16;
     if ((value != 1 && value != 2 && value != 4) || k_tiles % value != 0) return ERNIE_EINVAL;

@@ -259,6 +259,36 @@ def test_decode_tuning_variants_agree(E):
     eng.close()
 
 
+def test_decode_attention_shapes_and_poisoned_cache_tail(E):
+    """Every decode-attention shape meets the oracle on caches that straddle its batch sizes (128, 192, 256 keys),
+    with every cache slot past the valid lengths holding NaN bit patterns."""
+    import ctypes as C
+    import torch
+    lengths = [1, 7, 63, 125, 127, 128, 190, 193, 250]
+    n_gen = 6
+    wl = _ragged_workload(lengths, max_pos=256, n_gen=n_gen)
+    ids, lens = wl.padded(0)
+    orc = oracle_generate(wl, 0, range(len(lengths)), n_gen)
+    forced = {r: orc[r]["tokens"] for r in orc}
+    hip = C.CDLL("libamdhip64.so.7")
+    for variant in (0, 1, 2, 3):
+        eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
+        eng.tune("attn_dec", variant)
+        ptr, nbytes = eng.debug_buffer("kv")
+        torch.cuda.synchronize()
+        assert hip.hipMemset(C.c_void_p(ptr), 0xFF, C.c_size_t(nbytes)) == 0     # fp16 0xFFFF is a NaN
+        torch.cuda.synchronize()
+        _say(f"[parity] decode attention shape {variant}, poisoned cache")
+        toks, hid, lg = gpu_generate(eng, ids, lens, n_gen, forced)
+        assert np.isfinite(lg).all() and np.isfinite(hid).all()
+        check_rows(orc, toks, hid, lg, f"attn_dec{variant}")
+        eng.close()
+    eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
+    with pytest.raises(E.ErnieError):
+        eng.tune("attn_dec", 4)
+    eng.close()
+
+
 def test_profile_hooks_count_launches(E):
     """ernie_profile brackets every launch of a kernel family; counts and algorithmic bytes match the step structure."""
     import torch
