@@ -6,8 +6,8 @@ tests/bench draw their inputs from here so that they see bit-identical data.
 """
 from .ernie_inputs import (CONFIGS, ErnieShape, make_weights, make_kept_ids,
                            make_prompts, full_to_trimmed, trim_table, Workload,
-                           make_workload)
+                           make_workload, make_corpus)
 
 __all__ = ["CONFIGS", "ErnieShape", "make_weights", "make_kept_ids",
            "make_prompts", "full_to_trimmed", "trim_table", "Workload",
-           "make_workload"]
+           "make_workload", "make_corpus"]

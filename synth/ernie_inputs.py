@@ -158,6 +158,27 @@ def make_prompts(shape: ErnieShape, kept_ids: np.ndarray, seed: Optional[int] = 
     return [seqs[i:i + shape.batch] for i in range(0, len(seqs), shape.batch)]
 
 
+def make_corpus(vocab: int, n_tokens: int, seed: int = 5000, s: float = 1.1, shuffle_ranks: bool = True,
+                noise_ids: int = 0) -> np.ndarray:
+    """A synthetic token stream for frequency counting: bounded Zipf over ranks 1..vocab.
+
+    Rank r is carried by id `perm[r - 1]`, a seeded permutation of the
+    vocabulary (identity if `shuffle_ranks` is False), so the frequent rows are
+    scattered over the id range.  `noise_ids` values outside [0, vocab) are
+    mixed in at seeded positions (malformed input that a counter must ignore).
+    """
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    cdf = np.cumsum(_zipf_p(vocab, s))
+    ranks = np.minimum(np.searchsorted(cdf, rng.random(n_tokens), side="right"), vocab - 1)
+    perm = rng.permutation(vocab) if shuffle_ranks else np.arange(vocab)
+    ids = perm[ranks].astype(np.int32)
+    if noise_ids:
+        where = rng.choice(n_tokens, size=noise_ids, replace=False)
+        ids[where] = np.where(rng.random(noise_ids) < 0.5, -1 - rng.integers(0, 1000, size=noise_ids),
+                              vocab + rng.integers(0, 1000, size=noise_ids)).astype(np.int32)
+    return ids
+
+
 def full_to_trimmed(ids_full: np.ndarray, kept_ids: np.ndarray) -> np.ndarray:
     """Re-index full-vocabulary ids into the trimmed table.
 
