@@ -21,7 +21,8 @@ ERNIE_OK, ERNIE_EINVAL, ERNIE_ECAPACITY, ERNIE_EARENA, ERNIE_ESEQUENCE, ERNIE_EH
 
 EXPORTS = ("ernie_init_weights", "ernie_prefill", "ernie_decode_step", "ernie_free",
            "ernie_debug_buffer", "ernie_debug_tune", "ernie_profile", "ernie_profile_read",
-           "ernie_error_string")
+           "ernie_error_string",
+           "ernie_vocab_count", "ernie_vocab_select", "ernie_vocab_gather_rows", "ernie_remap_ids")
 
 PROF_CATEGORIES = ("gemm_dec", "gemm_dec_ln", "attn_dec", "gemm_prefill", "attn_prefill", "logits",
                    "row_dec", "row_prefill")
@@ -83,6 +84,16 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
                                        C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.ernie_error_string.restype = C.c_char_p
     lib.ernie_error_string.argtypes = [C.c_int]
+    lib.ernie_vocab_count.restype = C.c_int
+    lib.ernie_vocab_count.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.ernie_vocab_select.restype = C.c_int
+    lib.ernie_vocab_select.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.c_int32,
+                                       C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.ernie_vocab_gather_rows.restype = C.c_int
+    lib.ernie_vocab_gather_rows.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
+                                            C.c_void_p]
+    lib.ernie_remap_ids.restype = C.c_int
+    lib.ernie_remap_ids.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     if path is None:
         _lib = lib
     return lib
@@ -131,6 +142,89 @@ def ernie_decode_step(handle, tok_in: Optional[torch.Tensor], logits_out: Option
 
 def ernie_free(handle) -> None:
     load_library().ernie_free(handle)
+
+
+# ---- vocabulary trimming (include/ernie_prune.h) ------------------------------
+
+def ernie_vocab_count(ids_dev: Optional[torch.Tensor], n: int, vocab_full: int, counts_dev: Optional[torch.Tensor],
+                      stream=None) -> int:
+    """counts_dev: int64 tensor viewed as uint64 bins (torch has no unsigned 64-bit arithmetic; the bits are the same)."""
+    return load_library().ernie_vocab_count(_ptr(ids_dev), n, vocab_full, _ptr(counts_dev), _stream_ptr(stream))
+
+
+def ernie_vocab_select(counts_dev, vocab_full: int, k: int, reserved_host, unk_full_id: int, kept_ids_dev,
+                       full_to_trimmed_dev, stream=None) -> int:
+    res = None if reserved_host is None else np.ascontiguousarray(reserved_host, dtype=np.int32)
+    return load_library().ernie_vocab_select(_ptr(counts_dev), vocab_full, k,
+                                             None if res is None else res.ctypes.data_as(C.POINTER(C.c_int32)),
+                                             0 if res is None else res.size, unk_full_id, _ptr(kept_ids_dev),
+                                             _ptr(full_to_trimmed_dev), _stream_ptr(stream))
+
+
+def ernie_vocab_gather_rows(table_full_dev, vocab_full: int, d: int, kept_ids_dev, k: int, table_kept_dev,
+                            stream=None) -> int:
+    return load_library().ernie_vocab_gather_rows(_ptr(table_full_dev), vocab_full, d, _ptr(kept_ids_dev), k,
+                                                  _ptr(table_kept_dev), _stream_ptr(stream))
+
+
+def ernie_remap_ids(in_dev, n: int, map_dev, map_len: int, fallback: int, out_dev, stream=None) -> int:
+    return load_library().ernie_remap_ids(_ptr(in_dev), n, _ptr(map_dev), map_len, fallback, _ptr(out_dev),
+                                          _stream_ptr(stream))
+
+
+def _check(rc: int, what: str):
+    if rc != ERNIE_OK:
+        raise ErnieError(rc, what)
+
+
+class VocabTrimmer:
+    """Buffers + call sequence of the trimming step; every result is computed by the library's kernels.
+
+    count(ids) may be called any number of times (a corpus streamed in pieces);
+    select(k, reserved, unk) then fixes kept_ids [k] and full_to_trimmed [V] on the device.
+    """
+
+    def __init__(self, vocab_full: int, device="cuda:0"):
+        load_library()
+        self.V = int(vocab_full)
+        self.device = torch.device(device)
+        self.counts = torch.zeros(self.V, dtype=torch.int64, device=self.device)
+        self.kept_ids = None
+        self.full_to_trimmed = torch.empty(self.V, dtype=torch.int32, device=self.device)
+        self.unk_trimmed = None
+
+    def count(self, ids: torch.Tensor, stream=None):
+        assert ids.dtype == torch.int32 and ids.is_contiguous() and ids.device == self.device
+        _check(ernie_vocab_count(ids, ids.numel(), self.V, self.counts, stream), "ernie_vocab_count")
+
+    def select(self, k: int, reserved, unk_full_id: int, stream=None):
+        self.kept_ids = torch.empty(int(k), dtype=torch.int32, device=self.device)
+        _check(ernie_vocab_select(self.counts, self.V, int(k), reserved, int(unk_full_id), self.kept_ids,
+                                  self.full_to_trimmed, stream), "ernie_vocab_select")
+        self.unk_full, self.unk_trimmed = int(unk_full_id), None
+        return self.kept_ids
+
+    def trim_table(self, table_full: torch.Tensor, stream=None) -> torch.Tensor:
+        assert table_full.dtype == torch.float16 and table_full.is_contiguous() and table_full.shape[0] == self.V
+        k, d = self.kept_ids.numel(), table_full.shape[1]
+        out = torch.empty((k, d), dtype=torch.float16, device=self.device)
+        _check(ernie_vocab_gather_rows(table_full, self.V, d, self.kept_ids, k, out, stream), "ernie_vocab_gather_rows")
+        return out
+
+    def to_trimmed(self, ids_full: torch.Tensor, stream=None) -> torch.Tensor:
+        """Full -> trimmed ids; dropped and out-of-range ids become the unknown-word row."""
+        if self.unk_trimmed is None:
+            self.unk_trimmed = int(self.full_to_trimmed[self.unk_full].item())
+        out = torch.empty_like(ids_full)
+        _check(ernie_remap_ids(ids_full, ids_full.numel(), self.full_to_trimmed, self.V, self.unk_trimmed, out, stream),
+               "ernie_remap_ids")
+        return out
+
+    def to_full(self, ids_trimmed: torch.Tensor, stream=None) -> torch.Tensor:
+        out = torch.empty_like(ids_trimmed)
+        _check(ernie_remap_ids(ids_trimmed, ids_trimmed.numel(), self.kept_ids, self.kept_ids.numel(), -1, out, stream),
+               "ernie_remap_ids")
+        return out
 
 
 # ---- convenience object ------------------------------------------------------

@@ -12,7 +12,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "ernie.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", f)).read()
+                   for f in sorted(os.listdir(os.path.join(ROOT, "include"))) if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ernie_[a-z_]+)\s*\(", text)))
 
@@ -76,3 +77,36 @@ def test_error_strings():
     for code in (-1, -2, -3, -4, -5):
         assert E.error_string(code) not in ("ok", "unknown error")
     assert E.error_string(-99) == "unknown error"
+
+
+def test_trimming_entry_points_reject_bad_arguments_before_any_device_call():
+    """ernie_prune.h: every ERNIE_EINVAL is decided on the host, so these calls are safe without a GPU
+    (the fake addresses are never dereferenced)."""
+    lib = E.load_library()
+    fake, odd = 0x10000, 0x10002
+    res = (C.c_int32 * 2)(3, 4)
+    assert lib.ernie_vocab_count(None, 5, 100, fake, None) == E.ERNIE_EINVAL          # NULL stream of ids
+    assert lib.ernie_vocab_count(fake, 5, 100, None, None) == E.ERNIE_EINVAL          # NULL bins
+    assert lib.ernie_vocab_count(odd, 5, 100, fake, None) == E.ERNIE_EINVAL           # misaligned ids
+    assert lib.ernie_vocab_count(fake, 5, 100, fake + 4, None) == E.ERNIE_EINVAL      # misaligned bins
+    assert lib.ernie_vocab_count(fake, 5, 0, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_vocab_count(fake, 5, 262145, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_vocab_count(fake, -1, 100, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_vocab_count(fake, (1 << 40) + 1, 100, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_vocab_select(None, 100, 10, res, 2, 3, fake, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_vocab_select(fake, 100, 10, None, 2, 3, fake, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_vocab_select(fake, 100, 0, res, 2, 3, fake, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_vocab_select(fake, 100, 101, res, 2, 3, fake, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_vocab_select(fake, 100, 1, res, 2, 3, fake, fake, None) == E.ERNIE_EINVAL    # more reserved than k
+    assert lib.ernie_vocab_select(fake, 100, 10, res, 2, 5, fake, fake, None) == E.ERNIE_EINVAL   # unk not reserved
+    assert lib.ernie_vocab_select(fake, 4, 3, res, 2, 3, fake, fake, None) == E.ERNIE_EINVAL      # reserved id 4 >= V
+    assert lib.ernie_vocab_gather_rows(None, 100, 64, fake, 10, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_vocab_gather_rows(fake, 100, 60, fake, 10, fake, None) == E.ERNIE_EINVAL     # d % 8 != 0
+    assert lib.ernie_vocab_gather_rows(fake, 100, 64, fake, 10, fake + 8, None) == E.ERNIE_EINVAL  # misaligned table
+    assert lib.ernie_vocab_gather_rows(fake, 100, 64, fake, 0, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_remap_ids(fake, 5, None, 10, 0, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_remap_ids(fake, 5, fake, 0, 0, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_remap_ids(None, 5, fake, 10, 0, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_remap_ids(fake, -1, fake, 10, 0, fake, None) == E.ERNIE_EINVAL
+    assert lib.ernie_remap_ids(None, 0, fake, 10, 0, None, None) == E.ERNIE_OK                    # empty stream: no-op
+    assert lib.ernie_vocab_count(None, 0, 100, fake, None) == E.ERNIE_OK
