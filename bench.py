@@ -67,36 +67,12 @@ def cpu_baseline(wl, rows, n_gen):
                       f"{n_gen} tokens each, fp64 cached path, {dt:.1f} s"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="base")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=16)
-    ap.add_argument("--graph", type=int, default=1, help="replay the pass as HIP graphs (1) or launch eagerly (0)")
-    ap.add_argument("--prof-passes", type=int, default=3, help="passes of the event-bracketed per-kernel profile")
-    ap.add_argument("--calib-copy-mb", type=int, default=0,
-                    help="also run one plain device copy of this many MiB (reference for scaling HBM counters)")
-    ap.add_argument("--tune", action="append", default=[], help="decode tuning knob, key=value (repeatable)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (sequences shard by batch with no collective); "
-              "--gpus must be 1", file=sys.stderr)
-        sys.exit(2)
-
+def measure_pass(E, eng, ids_np, lens, N, steps, warmup, graph=1, prof_passes=3):
+    """Times `steps` passes (one prefill + N-1 free-running decode steps each) after `warmup` untimed ones, then the
+    two phases with events, then one event-bracketed eager profile.  Returns a dict of the measurements."""
     import numpy as np
     import torch
-    import paper_2407_04991_amd as E
-    from synth import make_workload
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
-    wl = make_workload(args.workload)
-    sh = wl.shape
-    eng = E.engine_from_workload(wl)
-    ids_np, lens = wl.padded(0)
-    B, N = sh.batch, sh.n_gen
+    B = len(lens)
     ids = torch.as_tensor(ids_np).to("cuda:0")
     tok = torch.empty(B, dtype=torch.int32, device="cuda:0")
     h = eng.handle
@@ -110,15 +86,11 @@ def main():
             rc = E.ernie_decode_step(h, None, None, None, tok)
             assert rc == 0, rc
 
-    for kv in args.tune:
-        k, v = kv.split("=")
-        eng.tune(k, int(v))
-
     # The launch sequence of one pass is recorded once into two HIP graphs (prefill; the N-1 decode steps)
     # on a side stream and replayed: per-sequence lengths and fed-back tokens live on the device, so a
     # replay is a complete, independent generation.
     side = torch.cuda.Stream()
-    if args.graph:
+    if graph:
         with torch.cuda.stream(side):
             prefill_call(); decode_calls()
         side.synchronize()
@@ -133,21 +105,19 @@ def main():
         run_pre, run_dec = prefill_call, decode_calls
 
     with torch.cuda.stream(side):
-        for _ in range(args.warmup):
+        for _ in range(warmup):
             run_pre(); run_dec()
         side.synchronize()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             run_pre(); run_dec()
         side.synchronize()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        ms_per_step = dt / args.steps * 1e3
-        tokens_per_s = B * N / (dt / args.steps)
 
         # device time of the two phases, events recorded on the stream the kernels run on
-        reps = max(3, min(args.steps, 10))
+        reps = max(3, min(steps, 10))
         pre_ms, dec_ms = [], []
         for _ in range(reps):
             e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
@@ -155,26 +125,150 @@ def main():
             side.synchronize()
             pre_ms.append(e[0].elapsed_time(e[1])); dec_ms.append(e[1].elapsed_time(e[2]) / (N - 1))
         tok_host = tok.cpu().numpy()
-    if args.graph:
+    if graph:
         assert (tok_host == tok_eager).all(), "graph replay and eager launch disagree on the last emitted tokens"
-    pre = float(np.median(pre_ms))
-    dec_ms_mean = float(np.median(dec_ms))               # mean decode-step time of a pass
+
+    # Per-kernel device time: the library brackets every launch of a kernel family with HIP events on
+    # the stream it launches on (eager launches; a graph cannot carry timing events).
+    prof = {}
+    if prof_passes > 0:
+        eng.profile(True)
+        with torch.cuda.stream(side):
+            for _ in range(prof_passes):
+                prefill_call(); decode_calls()
+            side.synchronize()
+        prof = eng.profile_read()
+        eng.profile(False)
+    return {"ms_per_step": dt / steps * 1e3, "tokens_per_s": B * N / (dt / steps),
+            "prefill_ms": float(np.median(pre_ms)), "decode_step_ms": float(np.median(dec_ms)),   # mean step of a pass
+            "prof": prof, "last_tokens": tok_host}
+
+
+def trim_sweep(args):
+    """Vocabulary trimming measured end to end at the ERNIE-base shape: the trimming kernels on a synthetic Zipf
+    corpus, then the generation pass for several kept-row counts V' (kept rows chosen, table trimmed and prompts
+    re-indexed by the library's kernels).  Prints ONE JSON line."""
+    from dataclasses import replace
+    import numpy as np
+    import torch
+    import paper_2407_04991_amd as E
+    from synth import CONFIGS, make_weights, make_corpus
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
+    base = CONFIGS["base"]
+    V, d = base.vocab_full, base.d_model
+    w = make_weights(base)
+    n_tok = args.corpus_mtok << 20
+    corpus = torch.as_tensor(make_corpus(V, n_tok, seed=5000)).to("cuda:0")
+    table_full = torch.as_tensor(w["tok_emb"]).to("cuda:0")
+    # prompts are windows of the corpus itself, so their id statistics are the counted ones
+    rng = np.random.default_rng(7)
+    starts = rng.integers(0, n_tok - base.prompt_len, size=base.batch)
+    prompts_full = np.stack([corpus[s:s + base.prompt_len].cpu().numpy() for s in starts])
+    prompts_dev = torch.as_tensor(prompts_full).to("cuda:0")
+    lens = np.full(base.batch, base.prompt_len, dtype=np.int32)
+    unk = int(prompts_full[0, 0])
+
+    def timed(fn, reps=10):
+        fn(); torch.cuda.synchronize()
+        ms = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); fn(); e1.record(); torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        return float(np.median(ms))
+
+    tr = E.VocabTrimmer(V)
+    count_ms = timed(lambda: tr.count(corpus))
+    tr.counts.zero_()
+    tr.count(corpus)
+    kernels = {"vocab_count": {"ms": count_ms, "bound": "hbm", "algorithmic_bytes": n_tok * 4,
+                               "achieved": n_tok * 4 / (count_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                               "frac": n_tok * 4 / (count_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "tokens": n_tok}}
+    rows = []
+    for k in [int(x) for x in args.trim_sweep.split(",")]:
+        sel_ms = timed(lambda: tr.select(k, [unk], unk))
+        kept = tr.select(k, [unk], unk)
+        gat_ms = timed(lambda: tr.trim_table(table_full))
+        table = tr.trim_table(table_full)
+        map_ms = timed(lambda: tr.to_trimmed(corpus), reps=5)
+        ids_t = tr.to_trimmed(prompts_dev)
+        cover = float(tr.counts[kept.long()].sum().item() / tr.counts.sum().item())
+        weights = dict(w)
+        weights["tok_emb_kept"] = table.cpu().numpy()
+        eng = E.ErnieEngine(n_layers=base.n_layers, d_model=d, n_heads=base.n_heads, d_ffn=base.d_ffn, vocab_full=V,
+                            vocab_kept=k, max_pos=base.max_pos, max_batch=base.batch,
+                            max_seq=base.prompt_len + base.n_gen, ln_eps=base.ln_eps, weights=weights,
+                            kept_ids=kept.cpu().numpy())
+        m = measure_pass(E, eng, ids_t.cpu().numpy(), lens, base.n_gen, args.steps, args.warmup, 1, 1)
+        prof = m["prof"]
+        dec_total = sum(ms for name, (ms, n, by, fl) in prof.items()
+                        if name in ("gemm_dec", "gemm_dec_ln", "attn_dec", "logits", "row_dec"))
+        rows.append({"vocab_kept": k, "corpus_coverage": cover, "tokens_per_s": m["tokens_per_s"],
+                     "prefill_ms": m["prefill_ms"], "decode_step_ms": m["decode_step_ms"],
+                     "logits_share_of_decode_step": prof["logits"][0] / dec_total,
+                     "logits_us_per_launch": prof["logits"][0] / prof["logits"][1] * 1e3 * m["decode_step_ms"]
+                     * (base.n_gen - 1) / dec_total,
+                     "select_ms": sel_ms, "gather_rows_ms": gat_ms,
+                     "gather_rows_gbs": 2 * k * d * 2 / (gat_ms * 1e-3) / 1e9,
+                     "remap_corpus_ms": map_ms, "remap_gbs": 2 * n_tok * 4 / (map_ms * 1e-3) / 1e9})
+        eng.close()
+    full = rows[0]["tokens_per_s"]
+    for r in rows:
+        r["speedup_vs_first"] = r["tokens_per_s"] / full
+    print(json.dumps({"metric": "vocabulary trimming sweep (ERNIE-base FP16, 1 GPU)", "unit": "tokens/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "dtype": "f16 / int32 / uint64", "data": "synthetic",
+                      "config": {"workload": f"base shape, batch {base.batch}, prompt {base.prompt_len}, generate "
+                                             f"{base.n_gen}; corpus {n_tok} Zipf(1.1) tokens over {V} ids"},
+                      "kernels": kernels, "sweep": rows}), flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="base")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=16)
+    ap.add_argument("--graph", type=int, default=1, help="replay the pass as HIP graphs (1) or launch eagerly (0)")
+    ap.add_argument("--prof-passes", type=int, default=3, help="passes of the event-bracketed per-kernel profile")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (reference for scaling HBM counters)")
+    ap.add_argument("--trim-sweep", default="", help="comma-separated kept-row counts: run the vocabulary-trimming "
+                    "sweep instead of the headline benchmark, e.g. 18000,12000,8000,6000,4000,2000")
+    ap.add_argument("--corpus-mtok", type=int, default=64, help="trim sweep: corpus size in Mi tokens")
+    ap.add_argument("--tune", action="append", default=[], help="decode tuning knob, key=value (repeatable)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (sequences shard by batch with no collective); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    if args.trim_sweep:
+        return trim_sweep(args)
+
+    import numpy as np
+    import torch
+    import paper_2407_04991_amd as E
+    from synth import make_workload
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
+    wl = make_workload(args.workload)
+    sh = wl.shape
+    eng = E.engine_from_workload(wl)
+    ids_np, lens = wl.padded(0)
+    B, N = sh.batch, sh.n_gen
+    for kv in args.tune:
+        k, v = kv.split("=")
+        eng.tune(k, int(v))
+    m = measure_pass(E, eng, ids_np, lens, N, args.steps, args.warmup, args.graph, args.prof_passes)
+    ms_per_step, tokens_per_s, pre, dec_ms_mean, prof = m["ms_per_step"], m["tokens_per_s"], m["prefill_ms"], \
+        m["decode_step_ms"], m["prof"]
+    prof_passes = args.prof_passes
     L = int(lens.max())
     step_bytes = np.array([algorithmic_decode_bytes(sh, B, int(np.mean(lens)) + t + 1) for t in range(N - 1)])
     dec_gbs = float(np.mean(step_bytes) / (dec_ms_mean * 1e-3) / 1e9)
     pf = prefill_flops(sh, lens)
-
-    # Per-kernel device time: the library brackets every launch of a kernel family with HIP events on
-    # the stream it launches on (eager launches; a graph cannot carry timing events).  The family with
-    # the largest total time is the "dominant kernel" of the roofline object.
-    eng.profile(True)
-    prof_passes = args.prof_passes
-    with torch.cuda.stream(side):
-        for _ in range(prof_passes):
-            prefill_call(); decode_calls()
-        side.synchronize()
-    prof = eng.profile_read()
-    eng.profile(False)
     bound = {"gemm_dec": "hbm", "gemm_dec_ln": "hbm", "attn_dec": "hbm", "logits": "hbm", "row_dec": "hbm",
              "gemm_prefill": "mfma", "attn_prefill": "mfma", "row_prefill": "hbm"}
     phase = {"gemm_dec": "decode", "gemm_dec_ln": "decode", "attn_dec": "decode", "logits": "decode",
