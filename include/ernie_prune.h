@@ -36,7 +36,7 @@ extern "C" {
  *   counts_dev  [vocab_full] uint64, 8-byte aligned; ACCUMULATED into, so the caller
  *               zeroes it before the first call and may stream a corpus in pieces
  * n == 0 is a no-op.  Errors: ERNIE_EINVAL (NULL pointer with n > 0, misalignment,
- * vocab_full outside [1, ERNIE_VOCAB_MAX], n < 0 or n > 2^40).
+ * vocab_full outside [1, ERNIE_VOCAB_MAX], n < 0 or n > 2^39).
  */
 int ernie_vocab_count(const int32_t* ids_dev, int64_t n, int32_t vocab_full,
                       uint64_t* counts_dev, void* stream);

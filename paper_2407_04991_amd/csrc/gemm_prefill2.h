@@ -64,7 +64,7 @@ __device__ __forceinline__ int xcd_contiguous_id(int id, int total) {
 }
 
 // DBG (measurement builds only, 0 in the library): 1 = no operand copies after the first stages,
-// 2 = fragments read from LDS once, 4 = no barrier / waits.
+// 2 = fragments read from LDS once, 4 = no barrier / waits, 8 = no A copies, 16 = no W copies.
 template <int WGM, int WGN, int TM, int TN, int BK, int S, class Epi, int DBG = 0>
 __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_prefill2_kernel(const half_t* __restrict__ A,
                                                             const half_t* __restrict__ Wp,
@@ -106,12 +106,16 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
     unsigned char* sa = smem_raw + stage * P::kStage;
     unsigned char* sb = sa + P::kAStage;
     const int k0 = kstep * BK;
+    if constexpr (!(DBG & 8)) {
 #pragma unroll
-    for (int i = 0; i < P::kAInstr; ++i)
-      async_copy16(a_src[i] + k0, sa + (wave * P::kAInstr + i) * P::kRowsPerInstr * P::kRowBytes);
+      for (int i = 0; i < P::kAInstr; ++i)
+        async_copy16(a_src[i] + k0, sa + (wave * P::kAInstr + i) * P::kRowsPerInstr * P::kRowBytes);
+    }
+    if constexpr (!(DBG & 16)) {
 #pragma unroll
-    for (int j = 0; j < P::kBInstr; ++j)
-      async_copy16(b_src[j] + (size_t)(k0 / 16) * 512, sb + (wave * P::kBInstr + j) * 1024);
+      for (int j = 0; j < P::kBInstr; ++j)
+        async_copy16(b_src[j] + (size_t)(k0 / 16) * 512, sb + (wave * P::kBInstr + j) * 1024);
+    }
   };
 
   floatx16 acc[TM][TN];
@@ -139,7 +143,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
   half8 fa[2][TM], fb[2][TN];
   for (int step = 0; step < steps; ++step) {
     // stage `step` has landed once at most (S - 2) later stages of this wave are still in flight
-    if constexpr (!(DBG & 4)) { if (step + S - 2 < steps) wait_vmcnt<(S - 2) * P::kLoads>(); else wait_vmcnt<0>(); }
+    constexpr int kInFlight = ((DBG & 8) ? 0 : P::kAInstr) + ((DBG & 16) ? 0 : P::kBInstr);   // = P::kLoads in the library
+    if constexpr (!(DBG & 4)) { if (step + S - 2 < steps) wait_vmcnt<(S - 2) * kInFlight>(); else wait_vmcnt<0>(); }
     // Plain s_barrier: __syncthreads() would add a fence that drains vmcnt to 0 and with it the pipeline.
     // Each wave has waited for its own share of the stage above; LDS reads below are issued after the
     // barrier in program order, and the compiler barriers keep them there.

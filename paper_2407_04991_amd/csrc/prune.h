@@ -10,11 +10,11 @@ namespace ernie {
 
 typedef unsigned long long u64_t;
 
-constexpr int kCountThreads = 512;
+constexpr int kCountThreads = 1024;
 constexpr int kCountMaxLdsVocab = 36864;   // 144 KiB of 32-bit bins
 
 // Occurrence count.  Each workgroup owns a private 32-bit histogram in LDS (a
-// workgroup sees fewer than 2^32 tokens: the host bounds n / gridDim.x) and
+// workgroup sees fewer than 2^32 tokens: the host bounds n and gridDim.x) and
 // adds its non-zero bins to the 64-bit totals at the end, so global atomics are
 // V per workgroup instead of one per token.  LDS = false counts straight into
 // the totals (vocabularies too large for LDS).
@@ -83,14 +83,24 @@ __device__ __forceinline__ u64_t select_key(const u64_t* __restrict__ counts, in
   return (counts[j] & 0x7FFFFFFFFFFFFFFFull) | ((u64_t)f << 63);
 }
 
-__global__ __launch_bounds__(kRankThreads) void vocab_rank_kernel(const u64_t* __restrict__ counts, int V, int k,
-                                                                  ReservedIds res, int* __restrict__ flag) {
+__global__ __launch_bounds__(256) void fill_int_kernel(int* __restrict__ p, int n, int v) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// gridDim.y slices of the id range are compared by different workgroups; the partial counts are added
+// into rank[i] (zeroed beforehand), integers, so the sum does not depend on the order.
+__global__ __launch_bounds__(kRankThreads) void vocab_rank_kernel(const u64_t* __restrict__ counts, int V,
+                                                                  ReservedIds res, int* __restrict__ rank_out) {
   __shared__ u64_t tile[kRankTile];
   const int tid = threadIdx.x;
   const int i = blockIdx.x * kRankThreads + tid;
   const u64_t ki = (i < V) ? select_key(counts, i, res) : 0;
+  const int tiles = (V + kRankTile - 1) / kRankTile;
+  const int t_beg = (int)((long long)tiles * blockIdx.y / gridDim.y), t_end = (int)((long long)tiles * (blockIdx.y + 1) / gridDim.y);
   int rank = 0;
-  for (int j0 = 0; j0 < V; j0 += kRankTile) {
+  for (int tt = t_beg; tt < t_end; ++tt) {
+    const int j0 = tt * kRankTile;
     __syncthreads();
     for (int t = tid; t < kRankTile; t += kRankThreads) tile[t] = (j0 + t < V) ? select_key(counts, j0 + t, res) : 0;
     __syncthreads();
@@ -100,15 +110,15 @@ __global__ __launch_bounds__(kRankThreads) void vocab_rank_kernel(const u64_t* _
       rank += (kj > ki) || (kj == ki && (j0 + t) < i);
     }
   }
-  if (i < V) flag[i] = (rank < k) ? 1 : 0;
+  if (i < V && rank) atomicAdd(&rank_out[i], rank);
 }
 
-// Compaction by one workgroup: `map` holds the keep flags on entry; on exit
+// Compaction by one workgroup: `map` holds the ranks on entry (id i is kept iff rank < k); on exit
 // map[i] = trimmed index of full id i (dropped ids: the trimmed index of `unk`)
 // and kept_ids[t] = full id of trimmed index t, ascending.
 constexpr int kCompactThreads = 1024;
 
-__global__ __launch_bounds__(kCompactThreads) void vocab_compact_kernel(int* __restrict__ map, int V, int unk,
+__global__ __launch_bounds__(kCompactThreads) void vocab_compact_kernel(int* __restrict__ map, int V, int k, int unk,
                                                                         int* __restrict__ kept_ids) {
   __shared__ int wsum[kCompactThreads / 64];
   __shared__ int s_base, s_unk;
@@ -117,7 +127,7 @@ __global__ __launch_bounds__(kCompactThreads) void vocab_compact_kernel(int* __r
   __syncthreads();
   for (int c0 = 0; c0 < V; c0 += kCompactThreads) {
     const int i = c0 + tid;
-    const int f = (i < V) ? map[i] : 0;
+    const int f = (i < V && map[i] < k) ? 1 : 0;
     int x = f;                                              // inclusive scan inside the wave
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -170,7 +180,16 @@ __global__ __launch_bounds__(256) void remap_ids_kernel(const int* in, long long
     const long long nvec = n / 4;
     const int4* vi = reinterpret_cast<const int4*>(in);
     int4* vo = reinterpret_cast<int4*>(out);
-    for (long long i = g; i < nvec; i += stride) {
+    long long i = g;
+    for (; i + 3 * stride < nvec; i += 4 * stride) {       // four vectors (16 table lookups) in flight per lane
+      const int4 a = vi[i], b = vi[i + stride], c = vi[i + 2 * stride], e = vi[i + 3 * stride];
+      const int4 ra = int4{look(a.x), look(a.y), look(a.z), look(a.w)};
+      const int4 rb = int4{look(b.x), look(b.y), look(b.z), look(b.w)};
+      const int4 rc = int4{look(c.x), look(c.y), look(c.z), look(c.w)};
+      const int4 re = int4{look(e.x), look(e.y), look(e.z), look(e.w)};
+      vo[i] = ra; vo[i + stride] = rb; vo[i + 2 * stride] = rc; vo[i + 3 * stride] = re;
+    }
+    for (; i < nvec; i += stride) {
       const int4 a = vi[i];
       vo[i] = int4{look(a.x), look(a.y), look(a.z), look(a.w)};
     }

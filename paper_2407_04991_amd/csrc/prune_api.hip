@@ -23,14 +23,15 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 extern "C" {
 
 int ernie_vocab_count(const int32_t* ids_dev, int64_t n, int32_t vocab_full, uint64_t* counts_dev, void* stream) {
-  if (vocab_full < 1 || vocab_full > ERNIE_VOCAB_MAX || n < 0 || n > ((int64_t)1 << 40)) return ERNIE_EINVAL;
+  if (vocab_full < 1 || vocab_full > ERNIE_VOCAB_MAX || n < 0 || n > ((int64_t)1 << 39)) return ERNIE_EINVAL;
   if (!counts_dev || !aligned(counts_dev, 8)) return ERNIE_EINVAL;
   if (n == 0) return ERNIE_OK;
   if (!ids_dev || !aligned(ids_dev, 4)) return ERNIE_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  // up to 1024 workgroups, each with at least 16 KiB of stream (n <= 2^40 keeps a workgroup below 2^30 tokens)
+  // one workgroup per CU at most (each flushes its whole histogram at the end), each with at least 32 KiB of
+  // stream; n <= 2^39 keeps a workgroup below 2^32 tokens
   const int64_t per_wg = (int64_t)kCountThreads * 4 * 2;
-  const int grid = (int)std::min<int64_t>(1024, std::max<int64_t>(1, (n + per_wg - 1) / per_wg));
+  const int grid = (int)std::min<int64_t>(256, std::max<int64_t>(1, (n + per_wg - 1) / per_wg));
   if (vocab_full <= kCountMaxLdsVocab) {
     const size_t lds = (size_t)vocab_full * sizeof(unsigned int);
     static bool configured = false;     // raises the dynamic LDS limit once per process (same value for every device)
@@ -69,9 +70,14 @@ int ernie_vocab_select(const uint64_t* counts_dev, int32_t vocab_full, int32_t k
   }
   if (!has_unk) return ERNIE_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipLaunchKernelGGL(vocab_rank_kernel, dim3((vocab_full + kRankThreads - 1) / kRankThreads), dim3(kRankThreads), 0, s,
-                     reinterpret_cast<const u64_t*>(counts_dev), vocab_full, k, res, full_to_trimmed_dev);
-  hipLaunchKernelGGL(vocab_compact_kernel, dim3(1), dim3(kCompactThreads), 0, s, full_to_trimmed_dev, vocab_full,
+  // ranks accumulate in the map buffer: zero it, add the partial ranks of every id slice, then compact
+  const int blocks = (vocab_full + kRankThreads - 1) / kRankThreads;
+  const int tiles = (vocab_full + kRankTile - 1) / kRankTile;
+  const int slices = std::max(1, std::min(tiles, 2048 / blocks));
+  hipLaunchKernelGGL(fill_int_kernel, dim3((vocab_full + 255) / 256), dim3(256), 0, s, full_to_trimmed_dev, vocab_full, 0);
+  hipLaunchKernelGGL(vocab_rank_kernel, dim3(blocks, slices), dim3(kRankThreads), 0, s,
+                     reinterpret_cast<const u64_t*>(counts_dev), vocab_full, res, full_to_trimmed_dev);
+  hipLaunchKernelGGL(vocab_compact_kernel, dim3(1), dim3(kCompactThreads), 0, s, full_to_trimmed_dev, vocab_full, k,
                      unk_full_id, kept_ids_dev);
   return launch_rc();
 }
