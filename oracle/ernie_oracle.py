@@ -31,7 +31,10 @@ sublayers; erf GELU; LayerNorm with population variance and eps inside the
 square root; score scale 1/sqrt(head_dim); masked keys excluded from the
 softmax; output projection tied to the token table, no bias; greedy argmax
 with the lowest index winning exact ties; the first generated token is
-emitted from the last prompt position.
+emitted from the last prompt position.  Optional variants, off unless the
+weight dictionary carries them: a two-row segment embedding (prompt /
+generated), an output-head transform LN(gelu(W h + b)) before the tied
+projection, and a per-row output bias.
 
 Pins: every function here is pinned by tests/test_oracle_*.py (brute force
 written independently with scalar loops, closed forms, invariants, torch CPU
@@ -103,6 +106,14 @@ class Params:
         self.emb_ln_g = c(weights["emb_ln_g"])
         self.emb_ln_b = c(weights["emb_ln_b"])
         self.layers = [{k: c(v) for k, v in lw.items()} for lw in weights["layers"]]
+        # optional variants (absent in the paper's description; present in public ERNIE / UNIMO checkpoints):
+        # a segment embedding with one row for prompt positions and one for generated positions, a
+        # dense + GELU + LayerNorm transform in front of the tied projection, and an output bias per vocabulary row
+        opt = lambda k: c(weights[k]) if weights.get(k) is not None else None
+        self.type_emb = opt("type_emb")           # [2, d]: row 0 = prompt positions, row 1 = generated positions
+        self.head_w, self.head_b = opt("head_w"), opt("head_b")             # [d, d], [d]
+        self.head_ln_g, self.head_ln_b = opt("head_ln_g"), opt("head_ln_b")
+        self.out_bias = opt("out_bias")           # [V] over the FULL vocabulary
         self.d = self.tok_emb.shape[1]
         assert self.d % self.n_heads == 0
         self.dh = self.d // self.n_heads
@@ -112,11 +123,18 @@ class Params:
 # the definition: full recompute
 # --------------------------------------------------------------------------
 
-def embed(p: Params, ids_full: np.ndarray, first_pos: int = 0) -> np.ndarray:
-    """x_i = LN_emb(E[u_i] + Epos[first_pos + i])."""
+def embed(p: Params, ids_full: np.ndarray, first_pos: int = 0, L: int | None = None) -> np.ndarray:
+    """x_i = LN_emb(E[u_i] + Epos[first_pos + i] (+ Etype[0 if position < L else 1])).
+
+    L is the prompt length; it only matters when the model has a segment embedding.
+    """
     n = len(ids_full)
     pos = np.arange(first_pos, first_pos + n)
-    return layer_norm(p.tok_emb[ids_full] + p.pos_emb[pos], p.emb_ln_g, p.emb_ln_b, p.eps)
+    y = p.tok_emb[ids_full] + p.pos_emb[pos]
+    if p.type_emb is not None:
+        assert L is not None
+        y = y + p.type_emb[(pos >= L).astype(np.int64)]
+    return layer_norm(y, p.emb_ln_g, p.emb_ln_b, p.eps)
 
 
 def attention_full(p: Params, lw: dict, X: np.ndarray, L: int, probs_out: list | None = None) -> np.ndarray:
@@ -150,15 +168,23 @@ def forward_full(p: Params, ids_full: np.ndarray, L: int, probs_out: list | None
     """Final-layer hidden states [n, d] of a sequence whose first L tokens are the prompt."""
     ids_full = np.asarray(ids_full)
     assert 1 <= L <= len(ids_full)
-    X = embed(p, ids_full)
+    X = embed(p, ids_full, 0, L)
     for lw in p.layers:
         X = layer_full(p, lw, X, L, probs_out)
     return X
 
 
+def head_transform(p: Params, h: np.ndarray) -> np.ndarray:
+    """t = LN_head(gelu(W_head h + b_head)) if the model has an output-head transform, else h."""
+    if p.head_w is None:
+        return h
+    return layer_norm(gelu(p.head_w @ h + p.head_b), p.head_ln_g, p.head_ln_b, p.eps)
+
+
 def logits_full_vocab(p: Params, h: np.ndarray) -> np.ndarray:
-    """z_v = h . E[v] over the full, untrimmed table."""
-    return p.tok_emb @ h
+    """z_v = t . E[v] (+ bias_v) over the full, untrimmed table, t = head_transform(h)."""
+    z = p.tok_emb @ head_transform(p, h)
+    return z if p.out_bias is None else z + p.out_bias
 
 
 def logits_kept(p: Params, h: np.ndarray, kept_ids: np.ndarray) -> np.ndarray:
@@ -251,14 +277,14 @@ class CachedSequence:
     def prefill(self, prompt_full: np.ndarray) -> np.ndarray:
         """Process the whole prompt; returns the final hidden state of its last position."""
         assert self.n == 0
-        X = embed(self.p, np.asarray(prompt_full))
+        X = embed(self.p, np.asarray(prompt_full), 0, len(prompt_full))
         H = self._layers(X)
-        self.n = len(prompt_full)
+        self.n = self.L = len(prompt_full)
         return H[-1]
 
     def step(self, token_full: int) -> np.ndarray:
         """Process one generated token at position n; returns its final hidden state."""
-        X = embed(self.p, np.array([token_full]), first_pos=self.n)
+        X = embed(self.p, np.array([token_full]), first_pos=self.n, L=self.L)
         H = self._layers(X)
         self.n += 1
         return H[0]

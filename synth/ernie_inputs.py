@@ -38,6 +38,7 @@ class ErnieShape:
     varlen_lo: int = 0       # >0: lengths uniform in [varlen_lo, prompt_len]
     varlen_pool: int = 0     # number of sequences drawn before batching
     trivial_affine: bool = True   # LN gamma=1 beta=0, biases 0
+    extras: bool = False     # also draw a segment embedding, an output-head transform and an output bias
     ln_eps: float = 1e-5
 
     @property
@@ -53,6 +54,9 @@ CONFIGS: Dict[str, ErnieShape] = {
     # or swapped gamma/beta cannot pass unnoticed
     "tiny_affine": ErnieShape("tiny_affine", 5, 2, 128, 2, 512, 1024, 512, 64, 2, 32, 16,
                               kept="uniform", ids="uniform_kept", trivial_affine=False),
+    # cfg 0c: cfg 0b plus the optional variants (segment embedding, output-head transform, output bias)
+    "tiny_head": ErnieShape("tiny_head", 6, 2, 128, 2, 512, 1024, 512, 64, 2, 32, 16,
+                            kept="uniform", ids="uniform_kept", trivial_affine=False, extras=True),
     # cfg 1: ERNIE-base, no pruning
     "base": ErnieShape("base", 1, 12, 768, 12, 3072, 18000, 18000, 512, 32, 128, 32),
     # cfg 2: ERNIE-base, pruned to the 6000 most frequent rows, variable lengths
@@ -106,6 +110,14 @@ def make_weights(shape: ErnieShape, seed: Optional[int] = None) -> dict:
             "w2": _normal_f16(rng, (d, f)), "b2": bias(d),
             "ln2_g": gamma(d), "ln2_b": beta(d),
         })
+    if shape.extras:
+        # drawn after everything else, so the parameters above are the same with and without the variants
+        w["type_emb"] = _normal_f16(rng, (2, d))
+        w["head_w"] = _normal_f16(rng, (d, d), 0.05)
+        w["head_b"] = _normal_f16(rng, d, 0.1)
+        w["head_ln_g"] = _normal_f16(rng, d, 0.1, 1.0)
+        w["head_ln_b"] = _normal_f16(rng, d, 0.1)
+        w["out_bias"] = _normal_f16(rng, shape.vocab_full, 0.1)
     return w
 
 

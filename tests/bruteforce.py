@@ -33,8 +33,12 @@ def forward(weights, n_heads, eps, ids, L):
     d = len(E[0])
     dh = d // n_heads
     X = []
+    Et = weights.get("type_emb")        # optional: row 0 for prompt positions, row 1 for generated ones
     for i in range(n):
         row = [E[ids[i]][c] + Ep[i][c] for c in range(d)]
+        if Et is not None:
+            seg = Et[0] if i < L else Et[1]
+            row = [row[c] + seg[c] for c in range(d)]
         X.append(_ln(row, weights["emb_ln_g"], weights["emb_ln_b"], eps))
     for lw in weights["layers"]:
         q, k, v = [], [], []
@@ -77,7 +81,12 @@ def generate(weights, n_heads, eps, prompt, n_gen, kept_ids):
     for _ in range(n_gen):
         H = forward(weights, n_heads, eps, seq, L)
         h = H[-1]
+        if weights.get("head_w") is not None:       # optional output head: LN(gelu(W h + b))
+            u = [_gelu(t) for t in _linear(h, weights["head_w"], weights["head_b"])]
+            h = _ln(u, weights["head_ln_g"], weights["head_ln_b"], eps)
         z = [sum(E[v][c] * h[c] for c in range(len(h))) for v in kept_ids]
+        if weights.get("out_bias") is not None:     # optional bias, indexed by FULL vocabulary id
+            z = [z[t] + weights["out_bias"][kept_ids[t]] for t in range(len(kept_ids))]
         best = 0
         for kk in range(1, len(z)):
             if z[kk] > z[best]:
