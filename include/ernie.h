@@ -100,6 +100,35 @@ int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* weights,
                        void* stream, ErnieHandle** out);
 
 /*
+ * Optional model variants, absent from the paper's description (Method: stacked transformer
+ * layers, trimmed word-embedding matrix) but present in public ERNIE / UNIMO checkpoints.
+ * Every field may be NULL (variant off); all are caller-owned DEVICE tensors, fp16.
+ *   type_emb   [2, d]  segment embedding added to token + position before the embedding
+ *                      LayerNorm: row 0 at prompt positions, row 1 at generated positions
+ *   head_w     [d, d]  output-head transform t = LayerNorm(gelu(head_w h + head_b)) applied to
+ *   head_b, head_ln_g, head_ln_b [d]   the final hidden state before the tied projection;
+ *                      all four are required together
+ *   out_bias   [V']    added to the logits, already gathered to the KEPT rows (bias_full[kept_ids])
+ * hidden_out of prefill / decode stays the final hidden state BEFORE the head transform.
+ */
+typedef struct {
+  const void* type_emb;
+  const void* head_w; const void* head_b; const void* head_ln_g; const void* head_ln_b;
+  const void* out_bias;
+} ErnieVariants;
+
+/*
+ * ernie_init_weights_ex -- ernie_init_weights for a model with optional variants.
+ * `variants` may be NULL (then identical to ernie_init_weights).  For the size query
+ * (arena_dev == NULL) only the NULL-ness of the fields is inspected; the arena grows by
+ * the repacked variant parameters.  Additional error: ERNIE_EINVAL if only some of the
+ * four head parameters are given.
+ */
+int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* weights, const ErnieVariants* variants,
+                          void* arena_dev, size_t arena_bytes, size_t* arena_needed,
+                          void* stream, ErnieHandle** out);
+
+/*
  * ernie_prefill -- one pass over a batch of prompts (FP16 forward, Method
  * item 1; fills the key/value cache of Method item 3) and emission of the
  * first generated token of every sequence from its last prompt position.

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_PKG, "libernie_hip.so")
 
 ERNIE_OK, ERNIE_EINVAL, ERNIE_ECAPACITY, ERNIE_EARENA, ERNIE_ESEQUENCE, ERNIE_EHIP = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ("ernie_init_weights", "ernie_prefill", "ernie_decode_step", "ernie_free",
+EXPORTS = ("ernie_init_weights", "ernie_init_weights_ex", "ernie_prefill", "ernie_decode_step", "ernie_free",
            "ernie_debug_buffer", "ernie_debug_tune", "ernie_profile", "ernie_profile_read",
            "ernie_error_string",
            "ernie_vocab_count", "ernie_vocab_select", "ernie_vocab_gather_rows", "ernie_remap_ids")
@@ -44,6 +44,13 @@ class ErnieWeights(C.Structure):
                 ("w1", _PP), ("b1", _PP), ("w2", _PP), ("b2", _PP), ("ln2_g", _PP), ("ln2_b", _PP)]
 
 
+class ErnieVariants(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("type_emb", "head_w", "head_b", "head_ln_g", "head_ln_b", "out_bias")]
+
+
+VARIANT_KEYS = ("type_emb", "head_w", "head_b", "head_ln_g", "head_ln_b", "out_bias_kept")
+
+
 class ErnieError(RuntimeError):
     def __init__(self, code: int, what: str):
         self.code = code
@@ -66,6 +73,10 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ernie_init_weights.restype = C.c_int
     lib.ernie_init_weights.argtypes = [C.POINTER(ErnieConfig), C.POINTER(ErnieWeights), C.c_void_p, C.c_size_t,
                                        C.POINTER(C.c_size_t), C.c_void_p, C.POINTER(C.c_void_p)]
+    lib.ernie_init_weights_ex.restype = C.c_int
+    lib.ernie_init_weights_ex.argtypes = [C.POINTER(ErnieConfig), C.POINTER(ErnieWeights), C.POINTER(ErnieVariants),
+                                          C.c_void_p, C.c_size_t, C.POINTER(C.c_size_t), C.c_void_p,
+                                          C.POINTER(C.c_void_p)]
     lib.ernie_prefill.restype = C.c_int
     lib.ernie_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_int32),
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -123,6 +134,19 @@ def ernie_init_weights(cfg: ErnieConfig, weights: Optional[ErnieWeights], arena:
     rc = lib.ernie_init_weights(C.byref(cfg), C.byref(weights) if weights is not None else None,
                                 _ptr(arena), arena.numel() if arena is not None else 0, C.byref(need),
                                 _stream_ptr(stream) if arena is not None else None, C.byref(out))
+    return rc, need.value, out.value
+
+
+def ernie_init_weights_ex(cfg: ErnieConfig, weights: Optional[ErnieWeights], variants: Optional[ErnieVariants],
+                          arena: Optional[torch.Tensor], stream=None):
+    """Returns (rc, arena_needed, handle)."""
+    lib = load_library()
+    need = C.c_size_t(0)
+    out = C.c_void_p(None)
+    rc = lib.ernie_init_weights_ex(C.byref(cfg), C.byref(weights) if weights is not None else None,
+                                   C.byref(variants) if variants is not None else None,
+                                   _ptr(arena), arena.numel() if arena is not None else 0, C.byref(need),
+                                   _stream_ptr(stream) if arena is not None else None, C.byref(out))
     return rc, need.value, out.value
 
 
@@ -237,7 +261,9 @@ class ErnieEngine:
 
     `weights` is a dict of numpy/torch fp16 arrays laid out as the synthetic
     generator produces them, with the token table ALREADY trimmed to the kept
-    rows under key "tok_emb_kept".
+    rows under key "tok_emb_kept".  Optional variants are switched on by the
+    keys "type_emb", "head_w" + "head_b" + "head_ln_g" + "head_ln_b", and
+    "out_bias_kept" (the output bias already gathered to the kept rows).
     """
 
     def __init__(self, *, n_layers, d_model, n_heads, d_ffn, vocab_full, vocab_kept, max_pos, max_batch, max_seq,
@@ -248,9 +274,14 @@ class ErnieEngine:
         self.cfg = ErnieConfig(n_layers, d_model, n_heads, d_ffn, vocab_full, vocab_kept, max_pos, max_batch,
                                max_seq, ln_eps)
         self.handle = None
-        rc, need, _ = ernie_init_weights(self.cfg, None, None)
+        var = None
+        if any(weights.get(k) is not None for k in VARIANT_KEYS):
+            var = ErnieVariants()
+            for k in VARIANT_KEYS:          # the size query looks at NULL-ness only
+                setattr(var, k.replace("_kept", ""), 1 if weights.get(k) is not None else None)
+        rc, need, _ = ernie_init_weights_ex(self.cfg, None, var, None)
         if rc != ERNIE_OK:
-            raise ErnieError(rc, "ernie_init_weights(size query)")
+            raise ErnieError(rc, "ernie_init_weights_ex(size query)")
         self.arena_bytes = need
         self.arena = torch.empty(need, dtype=torch.uint8, device=self.device)
         assert self.arena.data_ptr() % 256 == 0
@@ -272,9 +303,13 @@ class ErnieEngine:
                 t = dev(weights["layers"][l][k]); keep.append(t); arr[l] = t.data_ptr()
             arrays[k] = arr
             setattr(w, k, C.cast(arr, _PP))
-        rc, _, handle = ernie_init_weights(self.cfg, w, self.arena)
+        if var is not None:
+            for k in VARIANT_KEYS:
+                if weights.get(k) is not None:
+                    t = dev(weights[k]); keep.append(t); setattr(var, k.replace("_kept", ""), t.data_ptr())
+        rc, _, handle = ernie_init_weights_ex(self.cfg, w, var, self.arena)
         if rc != ERNIE_OK:
-            raise ErnieError(rc, "ernie_init_weights")
+            raise ErnieError(rc, "ernie_init_weights_ex")
         torch.cuda.synchronize(self.device)
         del keep
         self.handle = handle
@@ -354,6 +389,8 @@ def engine_from_workload(wl, *, max_batch=None, max_seq=None, device="cuda:0") -
     sh = wl.shape
     weights = dict(wl.weights)
     weights["tok_emb_kept"] = np.ascontiguousarray(wl.weights["tok_emb"][wl.kept_ids])
+    if wl.weights.get("out_bias") is not None:
+        weights["out_bias_kept"] = np.ascontiguousarray(wl.weights["out_bias"][wl.kept_ids])
     return ErnieEngine(n_layers=sh.n_layers, d_model=sh.d_model, n_heads=sh.n_heads, d_ffn=sh.d_ffn,
                        vocab_full=sh.vocab_full, vocab_kept=sh.vocab_kept, max_pos=sh.max_pos,
                        max_batch=max_batch or sh.batch, max_seq=max_seq or (sh.prompt_len + sh.n_gen),

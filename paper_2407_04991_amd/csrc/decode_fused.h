@@ -41,7 +41,7 @@ struct DecGemmArgs {
   half_t* xout;       // gemm_dec_ln: normalised rows [B, K] fp16, written by the strip-0 workgroups; may be null
   // outputs
   float* rout;        // EPI_RAW: [gridDim.y][B][N]
-  const float* bias_out;  // EPI_GELU16: [N] bias of THIS GEMM
+  const float* bias_out;  // EPI_GELU16: [N] bias of THIS GEMM; EPI_ARGMAX: optional [N] output bias (may be null)
   half_t* g16;        // EPI_GELU16: gelu(acc + bias_out) as fp16 [B, N]; needs gridDim.y == 1
   float* logits_out;  // EPI_ARGMAX: [B, N] or null
   float* strip_val;   // EPI_ARGMAX: [B, strips]
@@ -58,6 +58,7 @@ __device__ __forceinline__ void dec_epilogue(const DecGemmArgs& p, int nt, int l
   } else if constexpr (EPI == EPI_GELU16) {
     if (row < B && col < p.N) p.g16[(size_t)row * p.N + col] = (half_t)gelu_erf(s + p.bias_out[col]);
   } else {
+    if (p.bias_out && col < p.N) s += p.bias_out[col];      // optional output bias of the projection
     if (p.logits_out && row < B && col < p.N) p.logits_out[(size_t)row * p.N + col] = s;
     float bv = (col < p.N) ? s : -INFINITY;      // best of this strip for `row`: reduce over the 32 lanes of a half-wave
     int bi = col;
@@ -325,9 +326,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   }
 }
 
-// X = LayerNorm(sum_k partial_k + bias + residual), one wave per row.  `advance_len` (may be null) is the
-// per-sequence cached length, not touched here; `hidden_out` optionally receives the fp32 widening of X.
-template <int RC>
+// X = LayerNorm(sum_k partial_k + bias + residual), one wave per row; `hidden_out` optionally receives the
+// fp32 widening of X.  HEAD = true is the output-head transform instead: X = LayerNorm(gelu(sum_k partial_k
+// + bias)), no residual (`res` is not read).
+template <int RC, bool HEAD = false>
 __global__ __launch_bounds__(256) void ln_partials_kernel(const float* __restrict__ r32, int sk_in,
                                                           const float* __restrict__ bias,
                                                           const half_t* __restrict__ res, int rows, int d,
@@ -342,7 +344,8 @@ __global__ __launch_bounds__(256) void ln_partials_kernel(const float* __restric
 #pragma unroll
   for (int c = 0; c < RC; ++c) {
     const int cc = min(c * 64 + lane, chunks - 1);      // clamped: the duplicated tail chunk is never stored
-    const half8 rs = *reinterpret_cast<const half8*>(res + (size_t)r * d + cc * 8);
+    half8 rs = {0, 0, 0, 0, 0, 0, 0, 0};
+    if constexpr (!HEAD) rs = *reinterpret_cast<const half8*>(res + (size_t)r * d + cc * 8);
     const float4 b0 = *reinterpret_cast<const float4*>(bias + cc * 8), b1 = *reinterpret_cast<const float4*>(bias + cc * 8 + 4);
     v.v[c][0] = b0.x + (float)rs[0]; v.v[c][1] = b0.y + (float)rs[1]; v.v[c][2] = b0.z + (float)rs[2];
     v.v[c][3] = b0.w + (float)rs[3]; v.v[c][4] = b1.x + (float)rs[4]; v.v[c][5] = b1.y + (float)rs[5];
@@ -372,6 +375,12 @@ __global__ __launch_bounds__(256) void ln_partials_kernel(const float* __restric
         v.v[c][6] += live * x1[u][c].z; v.v[c][7] += live * x1[u][c].w;
       }
     }
+  }
+  if constexpr (HEAD) {
+#pragma unroll
+    for (int c = 0; c < RC; ++c)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v.v[c][j] = gelu_erf(v.v[c][j]);
   }
   row_layernorm_store(v, d, lane, gamma, beta, eps, X + (size_t)r * d);
   if (hidden_out) {

@@ -43,14 +43,19 @@ struct ArenaPlan {
   struct L { size_t wqkv, wo, w1, w2, bqkv, bo, b1, b2, ln1_g, ln1_b, ln2_g, ln2_b; };
   std::vector<L> layers;
   size_t r_qkv, r_out, r_f1, r_f2, zero_bias;
+  size_t type_emb, head_w, head_b, head_g, head_beta, out_bias;   // optional variants (0 bytes when off)
+  bool has_type, has_head, has_bias;
   size_t kv, X, X1, Y, Q, O, G, Yf, hlast, strip_val, strip_idx, cu, lens, tok_seq, tok_pos, tok_prev;
   size_t total;
   int vocab_tiles, strips;
   size_t t_max;
 };
 
-ArenaPlan make_plan(const ErnieConfig& c) {
+ArenaPlan make_plan(const ErnieConfig& c, const ErnieVariants* var) {
   ArenaPlan p;
+  p.has_type = var && var->type_emb;
+  p.has_head = var && var->head_w;
+  p.has_bias = var && var->out_bias;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   const size_t d = c.d_model, f = c.d_ffn, V = c.vocab_kept, P = c.max_pos;
@@ -79,6 +84,11 @@ ArenaPlan make_plan(const ErnieConfig& c) {
   p.r_qkv = take((size_t)kBigMaxSplitK * Bm * 3 * d * 4); p.r_out = take((size_t)kBigMaxSplitK * Bm * d * 4);
   p.r_f1 = take((size_t)kBigMaxSplitK * Bm * f * 4); p.r_f2 = take((size_t)kBigMaxSplitK * Bm * d * 4);
   p.zero_bias = take((3 * d > f ? 3 * d : f) * 4);
+  p.type_emb = take(p.has_type ? 2 * d * 2 : 0);
+  p.head_w = take(p.has_head ? d * d * 2 : 0);
+  p.head_b = take(p.has_head ? d * 4 : 0); p.head_g = take(p.has_head ? d * 4 : 0);
+  p.head_beta = take(p.has_head ? d * 4 : 0);
+  p.out_bias = take(p.has_bias ? V * 4 : 0);
   p.hlast = take(Bm * d * 2);
   p.strip_val = take(Bm * p.strips * 4); p.strip_idx = take(Bm * p.strips * 4);
   p.cu = take((Bm + 1) * 4); p.lens = take(Bm * 4);
@@ -123,6 +133,8 @@ struct ErnieHandle {
   std::vector<LayerPtrs> layers;
   half_t *kv, *X, *X1, *Y, *Q, *O, *G, *hlast;
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
+  half_t *type_emb = nullptr, *head_w = nullptr;                      // optional variants, null when off
+  float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
   int sk_out, sk_f2, fused_decode, attn_dec;   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   int* staging;          // pinned host: kStagingSlots x (max_batch + 1) ints
@@ -208,7 +220,8 @@ template <int MT, int NW>
 void launch_logits_t(ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s) {
   const size_t lds = (size_t)NW * MT * 16 * 64 * 4;
   hipLaunchKernelGGL((logits_argmax_kernel<MT, NW>), dim3(h->plan.strips), dim3(NW * 64), lds, s, X, h->tok_p, B,
-                     h->cfg.vocab_kept, h->cfg.d_model, logits_out, h->strip_val, h->strip_idx, h->plan.strips);
+                     h->cfg.vocab_kept, h->cfg.d_model, h->out_bias, logits_out, h->strip_val, h->strip_idx,
+                     h->plan.strips);
 }
 
 void launch_logits(ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s) {
@@ -315,6 +328,8 @@ bool fused_decode_fits(const ErnieHandle* h, int B) {
          (d / 16) % h->sk_out == 0 && (f / 16) % h->sk_f2 == 0;
 }
 
+const half_t* apply_head(ErnieHandle* h, const half_t* x, int B, hipStream_t s);
+
 int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hipStream_t s) {
   const ErnieConfig& c = h->cfg;
   const int B = h->B, d = c.d_model, f = c.d_ffn;
@@ -355,7 +370,8 @@ int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hi
   { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_f2, h->sk_f2, P.b2, h->X1, B, d,
                      P.ln2_g, P.ln2_b, c.ln_eps, h->X, hidden_out)); }
   DecGemmArgs z{};
-  z.B = B; z.Wp = h->tok_p; z.N = c.vocab_kept; z.K = d; z.a16 = h->X; z.logits_out = logits_out;
+  z.B = B; z.Wp = h->tok_p; z.N = c.vocab_kept; z.K = d; z.a16 = apply_head(h, h->X, B, s); z.logits_out = logits_out;
+  z.bias_out = h->out_bias;
   z.strip_val = h->strip_val; z.strip_idx = h->strip_idx; z.strips = h->plan.strips;
   rc |= launch_gemm_dec<EPI_ARGMAX>(h, z, 1, s);
   return rc ? ERNIE_EHIP : ERNIE_OK;
@@ -383,6 +399,21 @@ void launch_gemm_splitk(ErnieHandle* h, const half_t* A, const half_t* Wp, int M
   hipLaunchKernelGGL((gemm_prefill2_kernel<2, 2, 2, 1, 32, 3, EpiRaw32>), dim3(tiles_m * tiles_n, sk), dim3(256),
                      P::kLdsBytes, s, A, Wp, h->zero_bias, M, N, K, (N + 31) / 32, tiles_n,
                      EpiRaw32{out, N, (size_t)M * N});
+}
+
+// Optional output head: t = LayerNorm(gelu(head_w x + head_b)) for the B final rows `x`, written to hlast
+// (x may be hlast itself: the GEMM has consumed it before the row kernel overwrites it).  Returns the rows
+// the tied projection reads.
+const half_t* apply_head(ErnieHandle* h, const half_t* x, int B, hipStream_t s) {
+  if (!h->head_w) return x;
+  const int d = h->cfg.d_model;
+  const int sk = pick_gemm_split(B, d, d);
+  launch_gemm_splitk(h, x, h->head_w, B, d, d, h->r_out, sk, s);
+  ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
+  ROW_DISPATCH(d, hipLaunchKernelGGL((ln_partials_kernel<RC, true>), dim3((B + 3) / 4), dim3(256), 0, s, h->r_out, sk,
+                                     h->head_b, (const half_t*)nullptr, B, d, h->head_g, h->head_beta, h->cfg.ln_eps,
+                                     h->hlast, (float*)nullptr));
+  return h->hlast;
 }
 
 // Larger batches (B > 64): split-K MFMA GEMMs write fp32 partials; the attention prologue and two row
@@ -415,8 +446,9 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
       ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_f2, sk_2,
                                          L.b2, h->X1, B, d, L.ln2_g, L.ln2_b, c.ln_eps, h->X, hid)); }
   }
+  const half_t* x = apply_head(h, h->X, B, s);
   { ProfScope prof(h, ERNIE_PROF_LOGITS, s, 2.0 * c.vocab_kept * d, 2.0 * B * c.vocab_kept * d);
-    launch_logits(h, h->X, B, logits_out, s); }
+    launch_logits(h, x, B, logits_out, s); }
   return ERNIE_OK;
 }
 
@@ -449,9 +481,19 @@ const char* ernie_error_string(int code) {
 
 int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* w, void* arena_dev, size_t arena_bytes,
                        size_t* arena_needed, void* stream, ErnieHandle** out) {
+  return ernie_init_weights_ex(cfg, w, nullptr, arena_dev, arena_bytes, arena_needed, stream, out);
+}
+
+int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* w, const ErnieVariants* var, void* arena_dev,
+                          size_t arena_bytes, size_t* arena_needed, void* stream, ErnieHandle** out) {
   const int rc = check_config(cfg);
   if (rc != ERNIE_OK) return rc;
-  ArenaPlan plan = make_plan(*cfg);
+  if (var) {
+    const int n_head = (var->head_w != nullptr) + (var->head_b != nullptr) + (var->head_ln_g != nullptr) +
+                       (var->head_ln_b != nullptr);
+    if (n_head != 0 && n_head != 4) return ERNIE_EINVAL;
+  }
+  ArenaPlan plan = make_plan(*cfg, var);
   if (arena_needed) *arena_needed = plan.total;
   if (!arena_dev) return arena_needed ? ERNIE_OK : ERNIE_EINVAL;
   if (!w || !out) return ERNIE_EINVAL;
@@ -522,6 +564,21 @@ int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* w, void* aren
     cvt_into(w->ln1_g[l], L.ln1_g, d, s); cvt_into(w->ln1_b[l], L.ln1_b, d, s);
     cvt_into(w->ln2_g[l], L.ln2_g, d, s); cvt_into(w->ln2_b[l], L.ln2_b, d, s);
   }
+  if (plan.has_type) {
+    h->type_emb = H16(plan.type_emb);
+    copies_ok &= hipMemcpyAsync(h->type_emb, var->type_emb, (size_t)2 * d * 2, hipMemcpyDeviceToDevice, s) == hipSuccess;
+  }
+  if (plan.has_head) {
+    h->head_w = H16(plan.head_w); h->head_b = F32(plan.head_b); h->head_g = F32(plan.head_g);
+    h->head_beta = F32(plan.head_beta);
+    pack_into(var->head_w, h->head_w, d, d, s);
+    cvt_into(var->head_b, h->head_b, d, s); cvt_into(var->head_ln_g, h->head_g, d, s);
+    cvt_into(var->head_ln_b, h->head_beta, d, s);
+  }
+  if (plan.has_bias) {
+    h->out_bias = F32(plan.out_bias);
+    cvt_into(var->out_bias, h->out_bias, V, s);
+  }
   if (launch_status() != ERNIE_OK || !copies_ok) {
     (void)hipHostFree(h->staging);
     delete h;
@@ -558,7 +615,7 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); hipLaunchKernelGGL(token_map_kernel, dim3((T + 255) / 256), dim3(256), 0, s, h->cu, B, T, h->tok_seq, h->tok_pos,
                      h->lens); }
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_prefill_kernel<RC>, dim3((T + 3) / 4), dim3(256), 0, s, ids_dev, Lmax, h->tok_seq,
-                     h->tok_pos, T, h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X)); }
+                     h->tok_pos, T, h->tok_rm, h->pos, h->type_emb, h->emb_g, h->emb_b, c.ln_eps, d, h->X)); }
   const int q_tiles = (max_len + kAttnQTile - 1) / kAttnQTile;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerPtrs& L = h->layers[l];
@@ -578,8 +635,9 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
                        h->X)); }
   }
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); hipLaunchKernelGGL(gather_last_rows_kernel, dim3(B), dim3(256), 0, s, h->X, h->cu, B, d, h->hlast, hidden_out_dev); }
+  const half_t* xhead = apply_head(h, h->hlast, B, s);
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0);
-  launch_logits(h, h->hlast, B, logits_out_dev, s);
+  launch_logits(h, xhead, B, logits_out_dev, s);
   }
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0);
   hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->plan.strips,
@@ -602,7 +660,7 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_o
   const int B = h->B, d = c.d_model;
   const int* tok = tok_in_dev ? tok_in_dev : h->tok_prev;
   { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_decode_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, tok, h->lens, B, c.max_pos,
-                     h->tok_rm, h->pos, h->emb_g, h->emb_b, c.ln_eps, d, h->X)); }
+                     h->tok_rm, h->pos, h->type_emb ? h->type_emb + d : nullptr, h->emb_g, h->emb_b, c.ln_eps, d, h->X)); }
   const int rc = fused_decode_fits(h, B) ? decode_layers_fused(h, logits_out_dev, hidden_out_dev, s)
                                          : decode_layers_big(h, logits_out_dev, hidden_out_dev, s);
   if (rc != ERNIE_OK) return rc;

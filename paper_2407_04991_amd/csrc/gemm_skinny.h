@@ -17,7 +17,8 @@ namespace ernie {
 template <int MT, int NW>
 __global__ __launch_bounds__(NW * 64) void logits_argmax_kernel(const half_t* __restrict__ X,
                                                                 const half_t* __restrict__ Ep, int B, int N,
-                                                                int K, float* __restrict__ logits_out,
+                                                                int K, const float* __restrict__ out_bias,
+                                                                float* __restrict__ logits_out,
                                                                 float* __restrict__ strip_val,
                                                                 int* __restrict__ strip_idx, int strips) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -62,6 +63,7 @@ __global__ __launch_bounds__(NW * 64) void logits_argmax_kernel(const half_t* __
 #pragma unroll
       for (int w = 0; w < NW; ++w) s += red[((w * MT + m) * 16 + v) * 64 + lane];
       const int row = m * 32 + mfma32_row(v, lane);
+      if (out_bias && col < N) s += out_bias[col];            // optional output bias of the projection
       if (logits_out && row < B && col < N) logits_out[(size_t)row * N + col] = s;
       // best of this strip for `row`: reduce over the 32 lanes that share lane / 32
       float bv = (col < N) ? s : -INFINITY;

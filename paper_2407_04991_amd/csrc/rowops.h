@@ -100,8 +100,8 @@ __global__ void token_map_kernel(const int* __restrict__ cu, int B, int T, int* 
 template <int RC>
 __global__ __launch_bounds__(256) void embed_ln_prefill_kernel(
     const int* __restrict__ ids, int Lmax, const int* __restrict__ tok_seq, const int* __restrict__ tok_pos, int T,
-    const half_t* __restrict__ tok_emb, const half_t* __restrict__ pos_emb, const float* __restrict__ gamma,
-    const float* __restrict__ beta, float eps, int d, half_t* __restrict__ X) {
+    const half_t* __restrict__ tok_emb, const half_t* __restrict__ pos_emb, const half_t* __restrict__ seg_row,
+    const float* __restrict__ gamma, const float* __restrict__ beta, float eps, int d, half_t* __restrict__ X) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
@@ -119,6 +119,11 @@ __global__ __launch_bounds__(256) void embed_ln_prefill_kernel(
       const half8 q = *reinterpret_cast<const half8*>(p + ch * 8);
 #pragma unroll
       for (int j = 0; j < 8; ++j) r.v[c][j] = (float)a[j] + (float)q[j];
+      if (seg_row) {                              // optional segment embedding: one row for the whole launch
+        const half8 g = *reinterpret_cast<const half8*>(seg_row + ch * 8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r.v[c][j] += (float)g[j];
+      }
     }
   }
   row_layernorm_store(r, d, lane, gamma, beta, eps, X + (size_t)t * d);
@@ -129,8 +134,8 @@ __global__ __launch_bounds__(256) void embed_ln_prefill_kernel(
 template <int RC>
 __global__ __launch_bounds__(256) void embed_ln_decode_kernel(
     const int* __restrict__ tok, const int* __restrict__ cache_len, int B, int max_pos,
-    const half_t* __restrict__ tok_emb, const half_t* __restrict__ pos_emb, const float* __restrict__ gamma,
-    const float* __restrict__ beta, float eps, int d, half_t* __restrict__ X) {
+    const half_t* __restrict__ tok_emb, const half_t* __restrict__ pos_emb, const half_t* __restrict__ seg_row,
+    const float* __restrict__ gamma, const float* __restrict__ beta, float eps, int d, half_t* __restrict__ X) {
   const int lane = threadIdx.x & 63;
   const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (b >= B) return;
@@ -147,6 +152,11 @@ __global__ __launch_bounds__(256) void embed_ln_decode_kernel(
       const half8 q = *reinterpret_cast<const half8*>(p + ch * 8);
 #pragma unroll
       for (int j = 0; j < 8; ++j) r.v[c][j] = (float)a[j] + (float)q[j];
+      if (seg_row) {                              // optional segment embedding: one row for the whole launch
+        const half8 g = *reinterpret_cast<const half8*>(seg_row + ch * 8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r.v[c][j] += (float)g[j];
+      }
     }
   }
   row_layernorm_store(r, d, lane, gamma, beta, eps, X + (size_t)b * d);

@@ -110,3 +110,22 @@ def test_trimming_entry_points_reject_bad_arguments_before_any_device_call():
     assert lib.ernie_remap_ids(fake, -1, fake, 10, 0, fake, None) == E.ERNIE_EINVAL
     assert lib.ernie_remap_ids(None, 0, fake, 10, 0, None, None) == E.ERNIE_OK                    # empty stream: no-op
     assert lib.ernie_vocab_count(None, 0, 100, fake, None) == E.ERNIE_OK
+
+
+def test_variant_size_query_and_partial_head():
+    """ernie_init_weights_ex: each optional variant adds its repacked parameters to the arena; the four head
+    parameters come together or not at all (only NULL-ness matters for the size query)."""
+    cfg = base_cfg()
+    rc, plain, _ = E.ernie_init_weights_ex(cfg, None, None, None)
+    assert rc == E.ERNIE_OK and plain == E.ernie_init_weights(cfg, None, None)[1]
+    d, V = 768, 18000
+    for fields, extra in [(("type_emb",), 2 * d * 2), (("out_bias",), V * 4),
+                          (("head_w", "head_b", "head_ln_g", "head_ln_b"), d * d * 2 + 3 * d * 4)]:
+        var = E.ErnieVariants()
+        for f in fields:
+            setattr(var, f, 0x1000)
+        rc, need, _ = E.ernie_init_weights_ex(cfg, None, var, None)
+        assert rc == E.ERNIE_OK and extra <= need - plain <= extra + 6 * 256, (fields, need - plain)
+    var = E.ErnieVariants()
+    var.head_w = 0x1000; var.head_b = 0x1000
+    assert E.ernie_init_weights_ex(cfg, None, var, None)[0] == E.ERNIE_EINVAL

@@ -23,9 +23,10 @@ def _say(msg):
     print(msg, flush=True)
 
 
-@pytest.mark.parametrize("name", ["tiny", "tiny_affine"])
+@pytest.mark.parametrize("name", ["tiny", "tiny_affine", "tiny_head"])
 def test_tiny_all_rows_against_the_definition(E, name):
-    """cfg 0 / 0b: every row, every step, against the full-recompute definition."""
+    """cfg 0 / 0b / 0c (0b plus segment embedding, output-head transform and output bias): every row, every step,
+    against the full-recompute definition."""
     _say(f"[parity] {name}")
     wl = make_workload(name)
     sh = wl.shape
@@ -231,6 +232,47 @@ def test_decode_paths_by_batch_size(E, B):
     st = check_rows(orc, toks, hid, lg, f"batch{B}")
     _say(f"[parity] batch {B}: {st}")
     eng.close()
+
+
+@pytest.mark.parametrize("keys", [("type_emb",), ("head_w", "head_b", "head_ln_g", "head_ln_b"), ("out_bias",)])
+def test_each_optional_variant_alone(E, keys):
+    """One variant switched on at a time, ragged lengths: a variant wired to the wrong place cannot hide behind another."""
+    lengths = [1, 9, 33, 40]
+    n_gen = 5
+    wl = _ragged_workload(lengths, name="tiny_head", max_pos=64, n_gen=n_gen)
+    for k in ("type_emb", "head_w", "head_b", "head_ln_g", "head_ln_b", "out_bias"):
+        if k not in keys:
+            wl.weights.pop(k)
+    eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
+    ids, lens = wl.padded(0)
+    _say(f"[parity] variant {keys[0]} alone")
+    orc = oracle_generate(wl, 0, range(len(lengths)), n_gen, definition=True)
+    toks, hid, lg = gpu_generate(eng, ids, lens, n_gen, {r: orc[r]["tokens"] for r in orc})
+    check_rows(orc, toks, hid, lg, f"variant-{keys[0]}")
+    eng.close()
+
+
+@pytest.mark.parametrize("B", [70, 256])
+def test_variants_on_the_large_batch_decode_path(E, B):
+    rng = np.random.default_rng(1000 + B)
+    lengths = [int(x) for x in rng.integers(3, 40, size=B)]
+    n_gen = 4
+    wl = _ragged_workload(lengths, name="tiny_head", max_pos=64, n_gen=n_gen)
+    eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
+    ids, lens = wl.padded(0)
+    rows = [0, B // 2, B - 1]
+    _say(f"[parity] variants, batch {B} rows {rows}")
+    orc = oracle_generate(wl, 0, rows, n_gen)
+    toks, hid, lg = gpu_generate(eng, ids, lens, n_gen, {r: orc[r]["tokens"] for r in orc})
+    check_rows(orc, toks, hid, lg, f"variants-batch{B}")
+    eng.close()
+
+
+def test_partial_head_parameters_are_rejected(E):
+    wl = make_workload("tiny_head")
+    wl.weights.pop("head_ln_b")
+    with pytest.raises(E.ErnieError):
+        E.engine_from_workload(wl)
 
 
 def test_decode_tuning_variants_agree(E):
