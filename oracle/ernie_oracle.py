@@ -34,7 +34,10 @@ with the lowest index winning exact ties; the first generated token is
 emitted from the last prompt position.  Optional variants, off unless the
 weight dictionary carries them: a two-row segment embedding (prompt /
 generated), an output-head transform LN(gelu(W h + b)) before the tied
-projection, and a per-row output bias.
+projection, and a per-row output bias.  End of sequence (optional `eos`
+argument of the generators): a sequence that has emitted the end-of-sequence
+token is finished; nothing more is computed for it and it keeps emitting that
+token.
 
 Pins: every function here is pinned by tests/test_oracle_*.py (brute force
 written independently with scalar loops, closed forms, invariants, torch CPU
@@ -207,24 +210,33 @@ def top2_gap(z: np.ndarray) -> float:
     return float(part[-1] - part[-2])
 
 
-def generate_full_recompute(p: Params, prompt_full: np.ndarray, n_gen: int, kept_ids: np.ndarray):
+def generate_full_recompute(p: Params, prompt_full: np.ndarray, n_gen: int, kept_ids: np.ndarray,
+                            eos: int | None = None):
     """Greedy generation by the definition: every token re-runs the whole forward.
 
     Returns dict with
       tokens  [n_gen]      trimmed indices k (full id = kept_ids[k])
       hidden  [n_gen, d]   final hidden state at the emitting position
       logits  [n_gen, V']  logits over the kept rows
+    `eos` (a trimmed index, optional): once the sequence has emitted it, generation of this sequence is
+    over -- nothing more is computed, every later token is `eos` and the later hidden / logits rows are NaN.
     """
     prompt_full = np.asarray(prompt_full)
     L = len(prompt_full)
     seq = list(prompt_full)
     toks, hid, lg = [], [], []
+    done = False
     for _ in range(n_gen):
+        if done:
+            toks.append(eos); hid.append(np.full(p.d, np.nan)); lg.append(np.full(len(kept_ids), np.nan))
+            continue
         H = forward_full(p, np.array(seq), L)
         h = H[-1]
         z = logits_kept(p, h, kept_ids)
         k = greedy(z)
         toks.append(k); hid.append(h); lg.append(z)
+        if eos is not None and k == eos:
+            done = True
         seq.append(int(kept_ids[k]))
     return {"tokens": np.array(toks, dtype=np.int32), "hidden": np.array(hid), "logits": np.array(lg)}
 
@@ -291,20 +303,32 @@ class CachedSequence:
 
 
 def generate_cached(p: Params, prompt_full: np.ndarray, n_gen: int, kept_ids: np.ndarray,
-                    forced_tokens: np.ndarray | None = None):
+                    forced_tokens: np.ndarray | None = None, eos: int | None = None):
     """Greedy generation with the key/value cache.  Same return value as the full-recompute form.
 
     `forced_tokens` (trimmed indices) replaces the fed-back token at each step
     (the emitted argmax is still reported), for teacher-forced comparisons.
+    `eos`: the sequence is over once the token fed back is `eos` (free-running: once it has emitted it);
+    later tokens are `eos`, later hidden / logits rows NaN, and no further step is computed.
+    "steps" in the result counts the forward steps actually run (prefill included).
     """
     cs = CachedSequence(p)
     toks, hid, lg = [], [], []
     h = cs.prefill(prompt_full)
+    done, steps = False, 1
     for t in range(n_gen):
+        if done:
+            toks.append(eos); hid.append(np.full(p.d, np.nan)); lg.append(np.full(len(kept_ids), np.nan))
+            continue
         z = logits_kept(p, h, kept_ids)
         k = greedy(z)
         toks.append(k); hid.append(h); lg.append(z)
         if t + 1 < n_gen:
             feed = k if forced_tokens is None else int(forced_tokens[t])
-            h = cs.step(int(kept_ids[feed]))
-    return {"tokens": np.array(toks, dtype=np.int32), "hidden": np.array(hid), "logits": np.array(lg)}
+            if eos is not None and feed == eos:
+                done = True
+            else:
+                h = cs.step(int(kept_ids[feed]))
+                steps += 1
+    return {"tokens": np.array(toks, dtype=np.int32), "hidden": np.array(hid), "logits": np.array(lg),
+            "steps": steps}
