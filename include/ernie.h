@@ -174,6 +174,42 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev,
                       float* logits_out_dev, float* hidden_out_dev, int32_t* tok_out_dev,
                       void* stream);
 
+/*
+ * End of sequence, batch compaction and batching order.  The paper orders its inputs
+ * before inference and lets the batch size follow the input sizes (Introduction; Related
+ * work, "Dynamic Batch Size") without giving a procedure; these entry points are the
+ * mechanism a caller needs for both.
+ *
+ * ernie_set_eos -- eos_id is a trimmed id in [0, vocab_kept), or -1 (default) for none.
+ * With an id set, a sequence that is FED that id by a decode step (the token it emitted in
+ * free-running mode, tok_in_dev[b] under teacher forcing) is finished from that step on:
+ * its cache is neither read nor extended, its length stops advancing and it emits eos_id
+ * at every later step; its logits / hidden output rows are unspecified.  Other sequences
+ * are unaffected.  A prefill clears all finished flags.  Error: ERNIE_EINVAL (id out of range).
+ *
+ * ernie_batch_state -- copies the per-sequence cached lengths and finished flags (0 / 1) of
+ * the current batch into caller buffers of B int32 each (either may be NULL), on `stream`.
+ *
+ * ernie_compact -- drops sequences from the batch in flight: row i of the new batch is old
+ * row keep_rows_host[i] (strictly ascending, n_keep >= 1 of them, read before the call
+ * returns).  Cache contents do not move (rows are reached through a device-side row map);
+ * later decode steps run with B = n_keep and their outputs have n_keep rows.  A captured
+ * graph of decode steps is tied to the batch size it was captured with.
+ * Errors: ERNIE_ESEQUENCE (no prefill yet), ERNIE_EINVAL (bad list), ERNIE_EHIP.
+ *
+ * ernie_plan_batches -- host-only: orders n requests by prompt length (ascending, equal
+ * lengths in arrival order) and cuts the order greedily into batches of at most max_batch
+ * rows and at most max_tokens padded tokens (rows x longest prompt of the batch).
+ *   order_out_host [n], starts_out_host [n + 1] (the first *n_batches_out + 1 entries are
+ *   the cut points into order_out_host).  Error: ERNIE_EINVAL (NULL pointer, n < 0,
+ *   limits < 1, a length < 1 or a prompt that alone exceeds max_tokens).
+ */
+int ernie_set_eos(ErnieHandle* h, int32_t eos_id);
+int ernie_batch_state(ErnieHandle* h, int32_t* lens_out_dev, int32_t* finished_out_dev, void* stream);
+int ernie_compact(ErnieHandle* h, int32_t n_keep, const int32_t* keep_rows_host, void* stream);
+int ernie_plan_batches(const int32_t* lens_host, int32_t n, int32_t max_batch, int64_t max_tokens,
+                       int32_t* order_out_host, int32_t* starts_out_host, int32_t* n_batches_out);
+
 /* ernie_free -- releases the host-side handle (the arena stays the caller's). NULL is a no-op. */
 void ernie_free(ErnieHandle* h);
 

@@ -21,7 +21,7 @@ ERNIE_OK, ERNIE_EINVAL, ERNIE_ECAPACITY, ERNIE_EARENA, ERNIE_ESEQUENCE, ERNIE_EH
 
 EXPORTS = ("ernie_init_weights", "ernie_init_weights_ex", "ernie_prefill", "ernie_decode_step", "ernie_free",
            "ernie_debug_buffer", "ernie_debug_tune", "ernie_profile", "ernie_profile_read",
-           "ernie_error_string",
+           "ernie_error_string", "ernie_set_eos", "ernie_batch_state", "ernie_compact", "ernie_plan_batches",
            "ernie_vocab_count", "ernie_vocab_select", "ernie_vocab_gather_rows", "ernie_remap_ids")
 
 PROF_CATEGORIES = ("gemm_dec", "gemm_dec_ln", "attn_dec", "gemm_prefill", "attn_prefill", "logits",
@@ -95,6 +95,15 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
                                        C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.ernie_error_string.restype = C.c_char_p
     lib.ernie_error_string.argtypes = [C.c_int]
+    lib.ernie_set_eos.restype = C.c_int
+    lib.ernie_set_eos.argtypes = [C.c_void_p, C.c_int32]
+    lib.ernie_batch_state.restype = C.c_int
+    lib.ernie_batch_state.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.ernie_compact.restype = C.c_int
+    lib.ernie_compact.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_void_p]
+    lib.ernie_plan_batches.restype = C.c_int
+    lib.ernie_plan_batches.argtypes = [C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_int64, C.POINTER(C.c_int32),
+                                       C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.ernie_vocab_count.restype = C.c_int
     lib.ernie_vocab_count.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
     lib.ernie_vocab_select.restype = C.c_int
@@ -166,6 +175,33 @@ def ernie_decode_step(handle, tok_in: Optional[torch.Tensor], logits_out: Option
 
 def ernie_free(handle) -> None:
     load_library().ernie_free(handle)
+
+
+def ernie_set_eos(handle, eos_id: int) -> int:
+    return load_library().ernie_set_eos(handle, int(eos_id))
+
+
+def ernie_batch_state(handle, lens_out: Optional[torch.Tensor], finished_out: Optional[torch.Tensor], stream=None) -> int:
+    return load_library().ernie_batch_state(handle, _ptr(lens_out), _ptr(finished_out), _stream_ptr(stream))
+
+
+def ernie_compact(handle, keep_rows_host, stream=None) -> int:
+    keep = np.ascontiguousarray(keep_rows_host, dtype=np.int32)
+    return load_library().ernie_compact(handle, keep.size, keep.ctypes.data_as(C.POINTER(C.c_int32)),
+                                        _stream_ptr(stream))
+
+
+def ernie_plan_batches(lens_host, max_batch: int, max_tokens: int):
+    """Host-only.  Returns (rc, order [n], starts [n_batches + 1])."""
+    lens = np.ascontiguousarray(lens_host, dtype=np.int32)
+    n = lens.size
+    order = np.zeros(max(n, 1), dtype=np.int32)
+    starts = np.zeros(n + 1, dtype=np.int32)
+    nb = C.c_int32(0)
+    rc = load_library().ernie_plan_batches(lens.ctypes.data_as(C.POINTER(C.c_int32)), n, int(max_batch), int(max_tokens),
+                                           order.ctypes.data_as(C.POINTER(C.c_int32)),
+                                           starts.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(nb))
+    return rc, order[:n], starts[:nb.value + 1]
 
 
 # ---- vocabulary trimming (include/ernie_prune.h) ------------------------------
@@ -343,6 +379,20 @@ class ErnieEngine:
         if rc != ERNIE_OK:
             raise ErnieError(rc, "ernie_decode_step")
         return tok, lo, ho
+
+    def set_eos(self, eos_id: int):
+        _check(ernie_set_eos(self.handle, eos_id), "ernie_set_eos")
+
+    def state(self):
+        """(cached lengths, finished flags) of the batch in flight, as device int32 tensors."""
+        lens = torch.empty(self.B, dtype=torch.int32, device=self.device)
+        fin = torch.empty(self.B, dtype=torch.int32, device=self.device)
+        _check(ernie_batch_state(self.handle, lens, fin), "ernie_batch_state")
+        return lens, fin
+
+    def compact(self, keep_rows):
+        _check(ernie_compact(self.handle, keep_rows), "ernie_compact")
+        self.B = len(keep_rows)
 
     def debug_buffer(self, name: str):
         ptr = C.c_void_p(None); n = C.c_size_t(0)

@@ -193,14 +193,18 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_fused_kernel(const float*
                                                                     const float* __restrict__ bqkv,   // [3d]
                                                                     half_t* __restrict__ Kc, half_t* __restrict__ Vc,
                                                                     const int* __restrict__ cache_len, int H, int S,
-                                                                    int d, half_t* __restrict__ O) {
+                                                                    int d, half_t* __restrict__ O,
+                                                                    const int* __restrict__ finished,   // [B] or null (no end-of-sequence id set)
+                                                                    const int* __restrict__ slot) {     // cache row of batch row b; null = b
   __shared__ float sm[NW][8][10];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int h = blockIdx.x, b = blockIdx.y;
   const int ec = lane & 7, team = lane >> 3;
-  half_t* Kb = Kc + ((size_t)b * H + h) * S * 64 + ec * 8;
-  half_t* Vb = Vc + ((size_t)b * H + h) * S * 64 + ec * 8;
+  if (finished && finished[b]) return;           // finished sequence: no cache stream, no append; its output row is not used
+  const int cb = slot ? slot[b] : b;             // after a batch compaction the cache rows are no longer the batch rows
+  half_t* Kb = Kc + ((size_t)cb * H + h) * S * 64 + ec * 8;
+  half_t* Vb = Vc + ((size_t)cb * H + h) * S * 64 + ec * 8;
 
   half8 kf[U], vf[U];
   int key[U];

@@ -6,6 +6,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -46,6 +47,7 @@ struct ArenaPlan {
   size_t type_emb, head_w, head_b, head_g, head_beta, out_bias;   // optional variants (0 bytes when off)
   bool has_type, has_head, has_bias;
   size_t kv, X, X1, Y, Q, O, G, Yf, hlast, strip_val, strip_idx, cu, lens, tok_seq, tok_pos, tok_prev;
+  size_t finished, slot, keep;
   size_t total;
   int vocab_tiles, strips;
   size_t t_max;
@@ -93,6 +95,7 @@ ArenaPlan make_plan(const ErnieConfig& c, const ErnieVariants* var) {
   p.strip_val = take(Bm * p.strips * 4); p.strip_idx = take(Bm * p.strips * 4);
   p.cu = take((Bm + 1) * 4); p.lens = take(Bm * 4);
   p.tok_seq = take(p.t_max * 4); p.tok_pos = take(p.t_max * 4); p.tok_prev = take(Bm * 4);
+  p.finished = take(Bm * 4); p.slot = take(Bm * 4); p.keep = take(Bm * 4);
   p.total = off;
   return p;
 }
@@ -137,6 +140,10 @@ struct ErnieHandle {
   float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
   int sk_out, sk_f2, fused_decode, attn_dec;   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
+  int *finished, *slot, *keep;   // per-sequence finished flag, cache row of each batch row, compaction list
+  int eos = -1;                  // end-of-sequence id (trimmed), -1 = none
+  bool compacted = false;        // some row map entry differs from its index
+  std::vector<int> row_len;      // host copy of the prompt lengths of the batch in flight
   int* staging;          // pinned host: kStagingSlots x (max_batch + 1) ints
   int staging_next;
   // state of the batch in flight
@@ -185,7 +192,8 @@ void launch_attn_decode(const ErnieHandle* h, const float* rqkv, int sk_in, int 
   if (v == 0) v = 1;   // measured: the three shapes are within 5 % of each other at every cache length tried
 #define ATTN_DEC_LAUNCH(NW, U)                                                                                  \
   hipLaunchKernelGGL((attn_decode_fused_kernel<NW, U>), dim3(H, B), dim3(NW * 64), 0, s, rqkv, sk_in, B, bqkv, \
-                     kc, vc, h->lens, H, S, d, h->O)
+                     kc, vc, h->lens, H, S, d, h->O, h->eos >= 0 ? h->finished : nullptr,                    \
+                     h->compacted ? h->slot : nullptr)
   if (v == 2) ATTN_DEC_LAUNCH(8, 3);
   else if (v == 3) ATTN_DEC_LAUNCH(8, 4);
   else ATTN_DEC_LAUNCH(4, 4);
@@ -528,6 +536,7 @@ int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* w, const E
   h->sk_f2 = pick_split_k(cfg->d_model / 32, cfg->d_ffn / 16, 4);
   h->strip_idx = I32(plan.strip_idx); h->cu = I32(plan.cu); h->lens = I32(plan.lens);
   h->tok_seq = I32(plan.tok_seq); h->tok_pos = I32(plan.tok_pos); h->tok_prev = I32(plan.tok_prev);
+  h->finished = I32(plan.finished); h->slot = I32(plan.slot); h->keep = I32(plan.keep);
   h->prefilled = false; h->B = 0; h->max_len = 0; h->steps = 0; h->sum_len = h->sum_len2 = 0.0;
   h->staging = nullptr; h->staging_next = 0;
 
@@ -613,7 +622,7 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
 
   const int d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); hipLaunchKernelGGL(token_map_kernel, dim3((T + 255) / 256), dim3(256), 0, s, h->cu, B, T, h->tok_seq, h->tok_pos,
-                     h->lens); }
+                     h->lens, h->finished, h->slot); }
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_prefill_kernel<RC>, dim3((T + 3) / 4), dim3(256), 0, s, ids_dev, Lmax, h->tok_seq,
                      h->tok_pos, T, h->tok_rm, h->pos, h->type_emb, h->emb_g, h->emb_b, c.ln_eps, d, h->X)); }
   const int q_tiles = (max_len + kAttnQTile - 1) / kAttnQTile;
@@ -641,8 +650,10 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
   }
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0);
   hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->plan.strips,
-                     tok_out_dev, h->tok_prev, h->lens, 0, S, c.vocab_kept);
+                     tok_out_dev, h->tok_prev, h->lens, 0, S, c.vocab_kept, (const int*)nullptr, -1);
   }
+  h->compacted = false;
+  h->row_len.assign(prompt_lens_host, prompt_lens_host + B);
   h->prefilled = true; h->B = B; h->max_len = max_len; h->steps = 0;
   h->sum_len = sum_len; h->sum_len2 = sum_len2;
   return launch_status();
@@ -660,16 +671,91 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_o
   const int B = h->B, d = c.d_model;
   const int* tok = tok_in_dev ? tok_in_dev : h->tok_prev;
   { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_decode_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, tok, h->lens, B, c.max_pos,
-                     h->tok_rm, h->pos, h->type_emb ? h->type_emb + d : nullptr, h->emb_g, h->emb_b, c.ln_eps, d, h->X)); }
+                     h->tok_rm, h->pos, h->type_emb ? h->type_emb + d : nullptr, h->emb_g, h->emb_b, c.ln_eps, d, h->X,
+                     h->eos, h->finished)); }
   const int rc = fused_decode_fits(h, B) ? decode_layers_fused(h, logits_out_dev, hidden_out_dev, s)
                                          : decode_layers_big(h, logits_out_dev, hidden_out_dev, s);
   if (rc != ERNIE_OK) return rc;
   { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
   hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->plan.strips,
-                     tok_out_dev, h->tok_prev, h->lens, 1, c.max_seq, c.vocab_kept);
+                     tok_out_dev, h->tok_prev, h->lens, 1, c.max_seq, c.vocab_kept,
+                     h->eos >= 0 ? h->finished : (const int*)nullptr, h->eos);
   }
   h->steps += 1;
   return launch_status();
+}
+
+int ernie_set_eos(ErnieHandle* h, int32_t eos_id) {
+  if (!h || eos_id < -1 || eos_id >= h->cfg.vocab_kept) return ERNIE_EINVAL;
+  h->eos = eos_id;
+  return ERNIE_OK;
+}
+
+int ernie_batch_state(ErnieHandle* h, int32_t* lens_out_dev, int32_t* finished_out_dev, void* stream) {
+  if (!h) return ERNIE_EINVAL;
+  if (!h->prefilled) return ERNIE_ESEQUENCE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int B = h->B;
+  if (lens_out_dev) hipLaunchKernelGGL(copy_ints_kernel, dim3((B + 255) / 256), dim3(256), 0, s, h->lens, lens_out_dev, B);
+  if (finished_out_dev)
+    hipLaunchKernelGGL(copy_ints_kernel, dim3((B + 255) / 256), dim3(256), 0, s, h->finished, finished_out_dev, B);
+  return launch_status();
+}
+
+int ernie_compact(ErnieHandle* h, int32_t n_keep, const int32_t* keep_rows_host, void* stream) {
+  if (!h || !keep_rows_host) return ERNIE_EINVAL;
+  if (!h->prefilled) return ERNIE_ESEQUENCE;
+  if (n_keep < 1 || n_keep > h->B) return ERNIE_EINVAL;
+  for (int i = 0; i < n_keep; ++i) {
+    const int r = keep_rows_host[i];
+    if (r < 0 || r >= h->B || (i > 0 && r <= keep_rows_host[i - 1])) return ERNIE_EINVAL;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int* stage = h->staging + (size_t)h->staging_next * (h->cfg.max_batch + 1);
+  h->staging_next = (h->staging_next + 1) % kStagingSlots;
+  bool identity = true;
+  for (int i = 0; i < n_keep; ++i) { stage[i] = keep_rows_host[i]; identity &= (keep_rows_host[i] == i); }
+  if (!identity) {
+    HIP_OK(hipMemcpyAsync(h->keep, stage, sizeof(int) * n_keep, hipMemcpyHostToDevice, s));
+    hipLaunchKernelGGL(batch_compact_kernel, dim3(1), dim3(256), 0, s, h->keep, n_keep, h->lens, h->tok_prev,
+                       h->finished, h->slot);
+    h->compacted = true;
+  }
+  double sum_len = 0.0, sum_len2 = 0.0;
+  for (int i = 0; i < n_keep; ++i) {
+    const int L = h->row_len[keep_rows_host[i]];
+    h->row_len[i] = L;
+    sum_len += L; sum_len2 += (double)L * L;
+  }
+  h->row_len.resize(n_keep);
+  h->sum_len = sum_len; h->sum_len2 = sum_len2;
+  h->B = n_keep;
+  return launch_status();
+}
+
+int ernie_plan_batches(const int32_t* lens_host, int32_t n, int32_t max_batch, int64_t max_tokens,
+                       int32_t* order_out_host, int32_t* starts_out_host, int32_t* n_batches_out) {
+  if (n < 0 || max_batch < 1 || max_tokens < 1 || !n_batches_out || !starts_out_host) return ERNIE_EINVAL;
+  if (n > 0 && (!lens_host || !order_out_host)) return ERNIE_EINVAL;
+  for (int i = 0; i < n; ++i)
+    if (lens_host[i] < 1 || lens_host[i] > max_tokens) return ERNIE_EINVAL;
+  for (int i = 0; i < n; ++i) order_out_host[i] = i;
+  std::stable_sort(order_out_host, order_out_host + n,
+                   [&](int32_t a, int32_t b) { return lens_host[a] < lens_host[b]; });
+  int nb = 0;
+  int64_t rows = 0;
+  starts_out_host[0] = 0;
+  for (int pos = 0; pos < n; ++pos) {
+    const int64_t L = lens_host[order_out_host[pos]];     // ascending: the candidate is the longest of its batch
+    if (rows + 1 > max_batch || (rows + 1) * L > max_tokens) {
+      starts_out_host[++nb] = pos;
+      rows = 0;
+    }
+    ++rows;
+  }
+  if (n > 0) starts_out_host[++nb] = n;
+  *n_batches_out = nb;
+  return ERNIE_OK;
 }
 
 void ernie_free(ErnieHandle* h) {

@@ -81,11 +81,12 @@ __device__ __forceinline__ void row_layernorm_store(RowRegs<RC>& r, int d, int l
 // ---------------------------------------------------------------- prefill set-up
 
 // tok_seq[t], tok_pos[t] for the packed token axis t = cu[b] + pos; also resets
-// the cached lengths to the prompt lengths.
+// the per-sequence state: cached length = prompt length, not finished, cache row = batch row.
 __global__ void token_map_kernel(const int* __restrict__ cu, int B, int T, int* __restrict__ tok_seq,
-                                 int* __restrict__ tok_pos, int* __restrict__ cache_len) {
+                                 int* __restrict__ tok_pos, int* __restrict__ cache_len,
+                                 int* __restrict__ finished, int* __restrict__ slot) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t < B) cache_len[t] = cu[t + 1] - cu[t];
+  if (t < B) { cache_len[t] = cu[t + 1] - cu[t]; finished[t] = 0; slot[t] = t; }
   if (t >= T) return;
   int lo = 0, hi = B - 1;            // largest b with cu[b] <= t
   while (lo < hi) {
@@ -135,10 +136,14 @@ template <int RC>
 __global__ __launch_bounds__(256) void embed_ln_decode_kernel(
     const int* __restrict__ tok, const int* __restrict__ cache_len, int B, int max_pos,
     const half_t* __restrict__ tok_emb, const half_t* __restrict__ pos_emb, const half_t* __restrict__ seg_row,
-    const float* __restrict__ gamma, const float* __restrict__ beta, float eps, int d, half_t* __restrict__ X) {
+    const float* __restrict__ gamma, const float* __restrict__ beta, float eps, int d, half_t* __restrict__ X,
+    int eos, int* __restrict__ finished) {
   const int lane = threadIdx.x & 63;
   const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (b >= B) return;
+  // a sequence that is fed the end-of-sequence token is finished from this step on (sticky until the next
+  // prefill): later kernels of the step skip its cache and its emitted token is the end token again
+  if (eos >= 0 && lane == 0 && tok[b] == eos) finished[b] = 1;
   const int pos = min(cache_len[b], max_pos - 1);
   const half_t* e = tok_emb + (size_t)tok[b] * d;
   const half_t* p = pos_emb + (size_t)pos * d;
@@ -200,11 +205,13 @@ __global__ void gather_last_rows_kernel(const half_t* __restrict__ X, const int*
 
 // Second argmax stage: one block per sequence reduces the per-strip candidates
 // (value, index); the lowest index wins exact ties.  Also advances the cached
-// length of the sequence after a decode step (advance = 1).
+// length of the sequence after a decode step (advance = 1).  A finished sequence
+// (`finished` non-null and set) emits `eos` and does not advance.
 __global__ __launch_bounds__(256) void argmax_final_kernel(const float* __restrict__ strip_val,
                                                            const int* __restrict__ strip_idx, int strips,
                                                            int* __restrict__ tok_out, int* __restrict__ tok_keep,
-                                                           int* __restrict__ cache_len, int advance, int max_seq, int vocab) {
+                                                           int* __restrict__ cache_len, int advance, int max_seq, int vocab,
+                                                           const int* __restrict__ finished, int eos) {
   __shared__ float sv[4];
   __shared__ int si[4];
   const int b = blockIdx.x;
@@ -223,13 +230,35 @@ __global__ __launch_bounds__(256) void argmax_final_kernel(const float* __restri
   if (threadIdx.x == 0) {
     for (int w = 1; w < 4; ++w) argmax_merge(v, i, sv[w], si[w]);
     if (i < 0 || i >= vocab) i = 0;   // only reachable if every logit is NaN
+    const bool done = finished && finished[b];
+    if (done) i = eos;
     tok_out[b] = i;
     if (tok_keep != tok_out) tok_keep[b] = i;
-    if (advance) {
+    if (advance && !done) {
       const int n = cache_len[b];
       if (n < max_seq) cache_len[b] = n + 1;
     }
   }
+}
+
+// Batch compaction: row i of the per-sequence state takes the values of row keep[i] (keep ascending,
+// n_keep <= 256).  One workgroup: every thread reads its source row before anyone writes.
+__global__ __launch_bounds__(256) void batch_compact_kernel(const int* __restrict__ keep, int n_keep,
+                                                            int* __restrict__ cache_len, int* __restrict__ tok_prev,
+                                                            int* __restrict__ finished, int* __restrict__ slot) {
+  const int t = threadIdx.x;
+  int a = 0, b = 0, c = 0, e = 0;
+  if (t < n_keep) {
+    const int src = keep[t];
+    a = cache_len[src]; b = tok_prev[src]; c = finished[src]; e = slot[src];
+  }
+  __syncthreads();
+  if (t < n_keep) { cache_len[t] = a; tok_prev[t] = b; finished[t] = c; slot[t] = e; }
+}
+
+__global__ __launch_bounds__(256) void copy_ints_kernel(const int* __restrict__ src, int* __restrict__ dst, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = src[i];
 }
 
 }  // namespace ernie

@@ -129,3 +129,25 @@ def test_variant_size_query_and_partial_head():
     var = E.ErnieVariants()
     var.head_w = 0x1000; var.head_b = 0x1000
     assert E.ernie_init_weights_ex(cfg, None, var, None)[0] == E.ERNIE_EINVAL
+
+
+def test_batch_planning_matches_the_oracle_bit_for_bit():
+    """ernie_plan_batches is host-only C++: compared with oracle/schedule_oracle.py on random and edge inputs."""
+    import numpy as np
+    from oracle import schedule_oracle as S
+    rng = np.random.default_rng(0)
+    cases = [([5, 2, 9, 2, 7, 3, 9], 3, 16), ([1], 1, 1), ([], 4, 10), ([7] * 50, 8, 10 ** 9)]
+    for _ in range(40):
+        n = int(rng.integers(1, 300))
+        cases.append((rng.integers(1, 257, size=n).tolist(), int(rng.integers(1, 65)), int(rng.integers(256, 5000))))
+    for lens, mb, mt in cases:
+        rc, order, starts = E.ernie_plan_batches(lens, mb, mt)
+        o, s = S.plan_batches(lens, mb, mt)
+        assert rc == E.ERNIE_OK and np.array_equal(order, o) and np.array_equal(starts, s), (lens[:8], mb, mt)
+    for lens, mb, mt in [([3, 0], 4, 10), ([3], 0, 10), ([3], 4, 0), ([11], 4, 10)]:
+        assert E.ernie_plan_batches(lens, mb, mt)[0] == E.ERNIE_EINVAL
+    lib = E.load_library()
+    assert lib.ernie_plan_batches(None, 3, 4, 10, None, None, None) == E.ERNIE_EINVAL
+    assert lib.ernie_set_eos(None, 0) == E.ERNIE_EINVAL
+    assert lib.ernie_compact(None, 1, None, None) == E.ERNIE_EINVAL
+    assert lib.ernie_batch_state(None, None, None, None) == E.ERNIE_EINVAL
