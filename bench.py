@@ -223,6 +223,80 @@ def trim_sweep(args):
                       "kernels": kernels, "sweep": rows}), flush=True)
 
 
+def eos_sweep(args):
+    """Finished-sequence handling measured on a decode-heavy workload: every sequence gets a seeded stop step
+    (uniform in [N/4, N]); the same teacher-forced token stream is decoded (a) with no end token set, (b) with
+    the end token set, so finished rows skip their cache stream, (c) additionally compacting the batch every
+    `--compact-every` steps from the finished flags read back from the device.  Eager launches (the batch size
+    changes under compaction, so one graph cannot cover the pass).  Prints ONE JSON line."""
+    import numpy as np
+    import torch
+    import paper_2407_04991_amd as E
+    from synth import make_workload
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
+    name = args.workload if args.workload != "base" else "decode_bound"
+    wl = make_workload(name)
+    sh = wl.shape
+    eng = E.engine_from_workload(wl)
+    ids_np, lens = wl.padded(0)
+    B, N, Vk = sh.batch, sh.n_gen, sh.vocab_kept
+    rng = np.random.default_rng(6000 + sh.cfg)
+    stop = rng.integers(N // 4, N + 1, size=B)                 # tokens a sequence produces before it is finished
+    eos = 0
+    forced = rng.integers(1, Vk, size=(N - 1, B)).astype(np.int32)
+    for b in range(B):
+        if stop[b] <= N - 1:
+            forced[stop[b] - 1:, b] = eos                      # fed the end token at decode step stop[b]
+    forced_dev = torch.as_tensor(forced).to("cuda:0")
+    ids = torch.as_tensor(ids_np).to("cuda:0")
+    useful = int(np.minimum(stop, N).sum())
+    h = eng.handle
+
+    def one_pass(mode):
+        eng.set_eos(eos if mode != "none" else -1)
+        tok = torch.empty(B, dtype=torch.int32, device="cuda:0")
+        assert E.ernie_prefill(h, B, ids.shape[1], ids, lens, None, None, tok) == 0
+        rows = torch.arange(B, device="cuda:0")
+        for t in range(1, N):
+            if mode == "compact" and t % args.compact_every == 0:
+                fin = torch.empty(rows.numel(), dtype=torch.int32, device="cuda:0")
+                assert E.ernie_batch_state(h, None, fin) == 0
+                keep = torch.nonzero(fin == 0).flatten()        # host read: the caller decides who stays
+                if 0 < keep.numel() < rows.numel():
+                    assert E.ernie_compact(h, keep.cpu().numpy()) == 0
+                    rows = rows[keep]
+                elif keep.numel() == 0:
+                    break
+            feed = forced_dev[t - 1] if rows.numel() == B else forced_dev[t - 1][rows]
+            tok = torch.empty(rows.numel(), dtype=torch.int32, device="cuda:0")
+            assert E.ernie_decode_step(h, feed.contiguous(), None, None, tok) == 0
+        return rows.numel()
+
+    out_modes = {}
+    for mode in ("none", "skip", "compact"):
+        for _ in range(args.warmup):
+            one_pass(mode)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            left = one_pass(mode)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        out_modes[mode] = {"ms_per_pass": dt * 1e3, "useful_tokens_per_s": useful / dt, "rows_left_at_end": int(left)}
+    base = out_modes["none"]["useful_tokens_per_s"]
+    for m in out_modes.values():
+        m["speedup_vs_none"] = m["useful_tokens_per_s"] / base
+    eng.close()
+    print(json.dumps({"metric": "useful generated tokens/sec with per-sequence stop steps (1 GPU)", "unit": "tokens/s",
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": "f16", "data": "synthetic",
+                      "launch": "eager",
+                      "config": {"workload": f"{sh.name}: batch {B}, prompt {int(lens.max())}, up to {N} tokens, stop steps "
+                                             f"uniform in [{N // 4}, {N}] (mean {float(stop.mean()):.1f}), compaction every "
+                                             f"{args.compact_every} steps"},
+                      "useful_tokens": useful, "all_tokens": B * N, "modes": out_modes}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -237,6 +311,9 @@ def main():
                     help="also run one plain device copy of this many MiB (reference for scaling HBM counters)")
     ap.add_argument("--trim-sweep", default="", help="comma-separated kept-row counts: run the vocabulary-trimming "
                     "sweep instead of the headline benchmark, e.g. 18000,12000,8000,6000,4000,2000")
+    ap.add_argument("--eos-sweep", action="store_true", help="run the finished-sequence / compaction comparison "
+                    "(default workload decode_bound) instead of the headline benchmark")
+    ap.add_argument("--compact-every", type=int, default=16, help="eos sweep: steps between batch compactions")
     ap.add_argument("--corpus-mtok", type=int, default=64, help="trim sweep: corpus size in Mi tokens")
     ap.add_argument("--tune", action="append", default=[], help="decode tuning knob, key=value (repeatable)")
     args = ap.parse_args()
@@ -246,6 +323,8 @@ def main():
         sys.exit(2)
     if args.trim_sweep:
         return trim_sweep(args)
+    if args.eos_sweep:
+        return eos_sweep(args)
 
     import numpy as np
     import torch
