@@ -105,3 +105,28 @@ def test_eos_under_teacher_forcing_follows_the_fed_token(tiny):
     ref = O.generate_cached(p, prompt, 8, wl.kept_ids, forced_tokens=forced)
     assert np.allclose(g["logits"][:3], ref["logits"][:3], atol=1e-12)       # steps fed 5, 9 ran; feeding eos ends it
     assert np.isnan(g["logits"][3:]).all() and np.all(g["tokens"][3:] == eos) and g["steps"] == 3
+
+
+# ---------------------------------------------------------------- whole job
+
+def test_job_is_per_request_preprocess_generate_postprocess(tiny):
+    from oracle import job_oracle as J
+    from oracle import prune_oracle as P
+    wl, p = tiny
+    kept = wl.kept_ids
+    V = wl.shape.vocab_full
+    unk = int(kept[3])
+    fmap = P.full_to_trimmed_map(kept, V, unk)
+    rng = np.random.default_rng(4)
+    prompts = [rng.integers(0, V, size=n).astype(np.int32) for n in (3, 11, 6)]       # contain dropped ids
+    assert any(np.setdiff1d(q, kept).size for q in prompts)
+    toks, gaps = J.run_job(p, prompts, fmap, kept, 5)
+    assert toks.shape == (3, 5) and toks.dtype == np.int32 and np.all(gaps > 0)
+    assert np.all(np.isin(toks, kept))                                                # full ids of kept rows only
+    for r, q in enumerate(prompts):
+        seen = np.where(np.isin(q, kept), q, unk)                                     # dropped ids -> unknown-word id
+        g = O.generate_full_recompute(p, seen, 5, kept)                               # the definition, not the cached path
+        assert toks[r].tolist() == kept[g["tokens"]].tolist()
+    # request order is the caller's order whatever the lengths
+    toks2, _ = J.run_job(p, prompts[::-1], fmap, kept, 5)
+    assert np.array_equal(toks2, toks[::-1])
