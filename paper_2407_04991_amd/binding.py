@@ -21,7 +21,7 @@ ERNIE_OK, ERNIE_EINVAL, ERNIE_ECAPACITY, ERNIE_EARENA, ERNIE_ESEQUENCE, ERNIE_EH
 
 EXPORTS = ("ernie_init_weights", "ernie_init_weights_ex", "ernie_prefill", "ernie_decode_step", "ernie_free",
            "ernie_debug_buffer", "ernie_debug_tune", "ernie_profile", "ernie_profile_read",
-           "ernie_error_string", "ernie_set_eos", "ernie_batch_state", "ernie_compact", "ernie_plan_batches",
+           "ernie_error_string", "ernie_get_config", "ernie_job_workspace_bytes", "ernie_run_job", "ernie_set_eos", "ernie_batch_state", "ernie_compact", "ernie_plan_batches",
            "ernie_vocab_count", "ernie_vocab_select", "ernie_vocab_gather_rows", "ernie_remap_ids")
 
 PROF_CATEGORIES = ("gemm_dec", "gemm_dec_ln", "attn_dec", "gemm_prefill", "attn_prefill", "logits",
@@ -49,6 +49,19 @@ class ErnieVariants(C.Structure):
 
 
 VARIANT_KEYS = ("type_emb", "head_w", "head_b", "head_ln_g", "head_ln_b", "out_bias_kept")
+
+
+class ErnieJob(C.Structure):
+    _fields_ = [("n_requests", C.c_int32), ("prompt_offsets_host", C.POINTER(C.c_int32)),
+                ("prompt_ids_host", C.POINTER(C.c_int32)), ("full_to_trimmed_host", C.POINTER(C.c_int32)),
+                ("kept_ids_host", C.POINTER(C.c_int32)), ("n_gen", C.c_int32), ("max_batch", C.c_int32),
+                ("max_tokens", C.c_int64), ("overlap", C.c_int32), ("workspace_dev", C.c_void_p),
+                ("workspace_bytes", C.c_size_t), ("tokens_out_host", C.POINTER(C.c_int32))]
+
+
+class ErnieJobStats(C.Structure):
+    _fields_ = [("pre_s", C.c_double), ("enqueue_s", C.c_double), ("post_s", C.c_double), ("wall_s", C.c_double),
+                ("n_batches", C.c_int32)]
 
 
 class ErnieError(RuntimeError):
@@ -95,6 +108,12 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
                                        C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.ernie_error_string.restype = C.c_char_p
     lib.ernie_error_string.argtypes = [C.c_int]
+    lib.ernie_get_config.restype = C.c_int
+    lib.ernie_get_config.argtypes = [C.c_void_p, C.POINTER(ErnieConfig)]
+    lib.ernie_job_workspace_bytes.restype = C.c_size_t
+    lib.ernie_job_workspace_bytes.argtypes = [C.c_void_p, C.c_int32]
+    lib.ernie_run_job.restype = C.c_int
+    lib.ernie_run_job.argtypes = [C.c_void_p, C.POINTER(ErnieJob), C.POINTER(ErnieJobStats), C.c_void_p]
     lib.ernie_set_eos.restype = C.c_int
     lib.ernie_set_eos.argtypes = [C.c_void_p, C.c_int32]
     lib.ernie_batch_state.restype = C.c_int
@@ -175,6 +194,36 @@ def ernie_decode_step(handle, tok_in: Optional[torch.Tensor], logits_out: Option
 
 def ernie_free(handle) -> None:
     load_library().ernie_free(handle)
+
+
+def ernie_get_config(handle):
+    """Returns (rc, ErnieConfig)."""
+    cfg = ErnieConfig()
+    return load_library().ernie_get_config(handle, C.byref(cfg)), cfg
+
+
+def ernie_job_workspace_bytes(handle, n_gen: int) -> int:
+    return load_library().ernie_job_workspace_bytes(handle, int(n_gen))
+
+
+def ernie_run_job(handle, prompts_full, full_to_trimmed_host, kept_ids_host, n_gen: int, max_batch: int,
+                  max_tokens: int, overlap: bool, workspace: Optional[torch.Tensor], stream=None):
+    """Marshals a list of int32 prompt arrays into the ragged layout of ErnieJob and runs it.
+    Returns (rc, tokens [n_requests, n_gen] int32 full ids, ErnieJobStats)."""
+    n = len(prompts_full)
+    offs = np.zeros(n + 1, dtype=np.int32)
+    offs[1:] = np.cumsum([len(q) for q in prompts_full])
+    flat = np.ascontiguousarray(np.concatenate(prompts_full) if n else np.zeros(0), dtype=np.int32)
+    fmap = np.ascontiguousarray(full_to_trimmed_host, dtype=np.int32)
+    kept = np.ascontiguousarray(kept_ids_host, dtype=np.int32)
+    out = np.zeros((n, n_gen), dtype=np.int32)
+    P32 = C.POINTER(C.c_int32)
+    job = ErnieJob(n, offs.ctypes.data_as(P32), flat.ctypes.data_as(P32), fmap.ctypes.data_as(P32),
+                   kept.ctypes.data_as(P32), int(n_gen), int(max_batch), int(max_tokens), int(bool(overlap)),
+                   _ptr(workspace), workspace.numel() if workspace is not None else 0, out.ctypes.data_as(P32))
+    stats = ErnieJobStats()
+    rc = load_library().ernie_run_job(handle, C.byref(job), C.byref(stats), _stream_ptr(stream))
+    return rc, out, stats
 
 
 def ernie_set_eos(handle, eos_id: int) -> int:

@@ -18,9 +18,10 @@ HIPCC_FLAGS = [
 
 
 def build_library(verbose: bool = True) -> str:
-    """Compile csrc/ernie_api.hip and csrc/prune_api.hip (which include every kernel header) into libernie_hip.so."""
+    """Compile csrc/ernie_api.hip, csrc/prune_api.hip and csrc/job_api.hip (which include every kernel header) into libernie_hip.so."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + [os.path.join(CSRC, "ernie_api.hip"), os.path.join(CSRC, "prune_api.hip"), "-o", LIB_PATH]
+    cmd = [hipcc] + HIPCC_FLAGS + [os.path.join(CSRC, "ernie_api.hip"), os.path.join(CSRC, "prune_api.hip"), os.path.join(CSRC, "job_api.hip"),
+                                "-lpthread", "-o", LIB_PATH]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -3,6 +3,7 @@
 // enqueued on the caller's stream; nothing here allocates device memory.
 
 #include "../../include/ernie.h"
+#include "../../include/ernie_job.h"
 
 #include <hip/hip_runtime.h>
 
@@ -683,6 +684,12 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_o
   }
   h->steps += 1;
   return launch_status();
+}
+
+int ernie_get_config(const ErnieHandle* h, ErnieConfig* out) {
+  if (!h || !out) return ERNIE_EINVAL;
+  *out = h->cfg;
+  return ERNIE_OK;
 }
 
 int ernie_set_eos(ErnieHandle* h, int32_t eos_id) {

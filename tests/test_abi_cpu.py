@@ -151,3 +151,10 @@ def test_batch_planning_matches_the_oracle_bit_for_bit():
     assert lib.ernie_set_eos(None, 0) == E.ERNIE_EINVAL
     assert lib.ernie_compact(None, 1, None, None) == E.ERNIE_EINVAL
     assert lib.ernie_batch_state(None, None, None, None) == E.ERNIE_EINVAL
+
+
+def test_job_entry_points_reject_null_handles():
+    lib = E.load_library()
+    assert lib.ernie_job_workspace_bytes(None, 4) == 0
+    assert lib.ernie_get_config(None, None) == E.ERNIE_EINVAL
+    assert lib.ernie_run_job(None, None, None, None) == E.ERNIE_EINVAL
