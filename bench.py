@@ -297,6 +297,54 @@ def eos_sweep(args):
                       "useful_tokens": useful, "all_tokens": B * N, "modes": out_modes}), flush=True)
 
 
+def pipeline_bench(args):
+    """The host pipeline on ERNIE-base-shaped requests: the same job with the stages one after another and side
+    by side.  Requests are full-vocabulary prompts (Zipf ids, lengths as in the named workload), kept rows and
+    maps as in that workload.  Prints ONE JSON line."""
+    import numpy as np
+    import torch
+    import paper_2407_04991_amd as E
+    from synth import make_workload
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
+    wl = make_workload(args.workload)
+    sh = wl.shape
+    eng = E.engine_from_workload(wl)
+    kept = wl.kept_ids
+    fmap = np.zeros(sh.vocab_full, dtype=np.int32)                  # dropped ids -> trimmed row 0, as the workload does
+    fmap[kept] = np.arange(len(kept), dtype=np.int32)
+    rng = np.random.default_rng(7000 + sh.cfg)
+    n_req = args.requests
+    pool = [s for b in wl.batches_full for s in b]
+    prompts = [pool[i % len(pool)].copy() for i in range(n_req)]
+    for q in prompts:                                               # fresh ids of the same lengths
+        q[:] = rng.integers(0, sh.vocab_full, size=len(q))
+    ws = torch.empty(E.ernie_job_workspace_bytes(eng.handle, sh.n_gen), dtype=torch.uint8, device="cuda:0")
+    max_tokens = sh.batch * sh.prompt_len
+    res = {}
+    ref = None
+    for name, ov in (("one_after_another", False), ("side_by_side", True)):
+        best = None
+        for _ in range(args.warmup + args.steps):
+            rc, toks, st = E.ernie_run_job(eng.handle, prompts, fmap, kept, sh.n_gen, sh.batch, max_tokens, ov, ws)
+            assert rc == 0, rc
+            if best is None or st.wall_s < best.wall_s:
+                best = st
+        ref = toks if ref is None else ref
+        assert np.array_equal(ref, toks), "the two modes disagree"
+        res[name] = {"wall_ms": best.wall_s * 1e3, "tokens_per_s": n_req * sh.n_gen / best.wall_s,
+                     "pre_ms": best.pre_s * 1e3, "enqueue_ms": best.enqueue_s * 1e3, "post_ms": best.post_s * 1e3,
+                     "batches": best.n_batches}
+    eng.close()
+    print(json.dumps({"metric": "generated tokens/sec through the host pipeline (1 GPU)", "unit": "tokens/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "dtype": "f16", "data": "synthetic", "launch": "eager",
+                      "config": {"workload": f"{sh.name} shape, {n_req} requests in batches of <= {sh.batch} rows / "
+                                             f"{max_tokens} padded tokens, {sh.n_gen} tokens each"},
+                      "modes": res,
+                      "speedup_side_by_side": res["side_by_side"]["tokens_per_s"] / res["one_after_another"]["tokens_per_s"]}),
+          flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -313,6 +361,9 @@ def main():
                     "sweep instead of the headline benchmark, e.g. 18000,12000,8000,6000,4000,2000")
     ap.add_argument("--eos-sweep", action="store_true", help="run the finished-sequence / compaction comparison "
                     "(default workload decode_bound) instead of the headline benchmark")
+    ap.add_argument("--pipeline", action="store_true", help="run the host-pipeline comparison (ernie_run_job with the "
+                    "stages one after another vs side by side) instead of the headline benchmark")
+    ap.add_argument("--requests", type=int, default=512, help="pipeline: number of requests in the job")
     ap.add_argument("--compact-every", type=int, default=16, help="eos sweep: steps between batch compactions")
     ap.add_argument("--corpus-mtok", type=int, default=64, help="trim sweep: corpus size in Mi tokens")
     ap.add_argument("--tune", action="append", default=[], help="decode tuning knob, key=value (repeatable)")
@@ -325,6 +376,8 @@ def main():
         return trim_sweep(args)
     if args.eos_sweep:
         return eos_sweep(args)
+    if args.pipeline:
+        return pipeline_bench(args)
 
     import numpy as np
     import torch
