@@ -366,6 +366,8 @@ def main():
     ap.add_argument("--requests", type=int, default=512, help="pipeline: number of requests in the job")
     ap.add_argument("--compact-every", type=int, default=16, help="eos sweep: steps between batch compactions")
     ap.add_argument("--corpus-mtok", type=int, default=64, help="trim sweep: corpus size in Mi tokens")
+    ap.add_argument("--shape", action="append", default=[], help="override an integer field of the workload shape, "
+                    "key=value (repeatable; e.g. prompt_len=8): for sensitivity runs, not the headline number")
     ap.add_argument("--tune", action="append", default=[], help="decode tuning knob, key=value (repeatable)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -385,7 +387,7 @@ def main():
     from synth import make_workload
 
     assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
-    wl = make_workload(args.workload)
+    wl = make_workload(args.workload, **{kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.shape})
     sh = wl.shape
     eng = E.engine_from_workload(wl)
     ids_np, lens = wl.padded(0)

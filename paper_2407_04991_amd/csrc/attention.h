@@ -187,7 +187,15 @@ __device__ __forceinline__ void softmax_merge(SoftmaxPart& a, float om, float ol
 // the cached length is known (bounded by the capacity S only: the cache is allocated up to S, and
 // whatever lies past the valid length is masked out after the fact), so the length, the cache
 // stream and the raw q, k, v are all fetched in one memory round trip instead of three.
-template <int NW, int U>
+template <bool NT>
+__device__ __forceinline__ half8 load_kv(const half_t* p) {
+  // NT: streaming hint -- the cache rows are read once per step and should not displace the weights
+  // from the caches in front of HBM
+  if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const half8*>(p));
+  else return *reinterpret_cast<const half8*>(p);
+}
+
+template <int NW, int U, bool NT = false>
 __global__ __launch_bounds__(NW * 64) void attn_decode_fused_kernel(const float* __restrict__ Rqkv,   // [sk_in][B, 3d] fp32 split-K partials
                                                                     int sk_in, int B,
                                                                     const float* __restrict__ bqkv,   // [3d]
@@ -214,8 +222,8 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_fused_kernel(const float*
   for (int u = 0; u < U; ++u) {
     key[u] = (g0 + u) * 8 + team;
     const size_t row = (size_t)min(key[u], S - 1) * 64;
-    kf[u] = *reinterpret_cast<const half8*>(Kb + row);
-    vf[u] = *reinterpret_cast<const half8*>(Vb + row);
+    kf[u] = load_kv<NT>(Kb + row);
+    vf[u] = load_kv<NT>(Vb + row);
   }
   const int len = cache_len[b];
 
@@ -277,8 +285,8 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_fused_kernel(const float*
       for (int u = 0; u < U; ++u) {
         key[u] = (g0 + u) * 8 + team;
         const size_t row = (size_t)min(key[u], S - 1) * 64;
-        kf[u] = *reinterpret_cast<const half8*>(Kb + row);
-        vf[u] = *reinterpret_cast<const half8*>(Vb + row);
+        kf[u] = load_kv<NT>(Kb + row);
+        vf[u] = load_kv<NT>(Vb + row);
       }
     }
     if (mx != -INFINITY) {

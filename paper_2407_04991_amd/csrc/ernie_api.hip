@@ -139,7 +139,7 @@ struct ErnieHandle {
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
   half_t *type_emb = nullptr, *head_w = nullptr;                      // optional variants, null when off
   float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
-  int sk_out, sk_f2, fused_decode, attn_dec;   // decode tuning (see ernie_debug_tune)
+  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1;   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   int *finished, *slot, *keep;   // per-sequence finished flag, cache row of each batch row, compaction list
   int eos = -1;                  // end-of-sequence id (trimmed), -1 = none
@@ -191,13 +191,14 @@ void launch_attn_decode(const ErnieHandle* h, const float* rqkv, int sk_in, int 
   const int H = h->cfg.n_heads, S = h->cfg.max_seq, d = h->cfg.d_model;
   int v = h->attn_dec;
   if (v == 0) v = 1;   // measured: the three shapes are within 5 % of each other at every cache length tried
-#define ATTN_DEC_LAUNCH(NW, U)                                                                                  \
-  hipLaunchKernelGGL((attn_decode_fused_kernel<NW, U>), dim3(H, B), dim3(NW * 64), 0, s, rqkv, sk_in, B, bqkv, \
-                     kc, vc, h->lens, H, S, d, h->O, h->eos >= 0 ? h->finished : nullptr,                    \
+#define ATTN_DEC_LAUNCH(NW, U, NT)                                                                                  \
+  hipLaunchKernelGGL((attn_decode_fused_kernel<NW, U, NT>), dim3(H, B), dim3(NW * 64), 0, s, rqkv, sk_in, B, bqkv, \
+                     kc, vc, h->lens, H, S, d, h->O, h->eos >= 0 ? h->finished : nullptr,                        \
                      h->compacted ? h->slot : nullptr)
-  if (v == 2) ATTN_DEC_LAUNCH(8, 3);
-  else if (v == 3) ATTN_DEC_LAUNCH(8, 4);
-  else ATTN_DEC_LAUNCH(4, 4);
+  if (v == 2) ATTN_DEC_LAUNCH(8, 3, false);
+  else if (v == 3) ATTN_DEC_LAUNCH(8, 4, false);
+  else if (h->attn_nt) ATTN_DEC_LAUNCH(4, 4, true);
+  else ATTN_DEC_LAUNCH(4, 4, false);
 #undef ATTN_DEC_LAUNCH
 }
 
@@ -822,6 +823,7 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
 int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!h || !key) return ERNIE_EINVAL;
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
+  if (!strcmp(key, "attn_nt")) { h->attn_nt = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "attn_dec")) {
     if (value < 0 || value > 3) return ERNIE_EINVAL;
     h->attn_dec = value;

@@ -313,9 +313,10 @@ def test_decode_attention_shapes_and_poisoned_cache_tail(E):
     orc = oracle_generate(wl, 0, range(len(lengths)), n_gen)
     forced = {r: orc[r]["tokens"] for r in orc}
     hip = C.CDLL("libamdhip64.so.7")
-    for variant in (0, 1, 2, 3):
+    for variant, nt in ((0, 1), (1, 0), (1, 1), (2, 0), (3, 0)):
         eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
         eng.tune("attn_dec", variant)
+        eng.tune("attn_nt", nt)              # cache rows read with / without the streaming (non-temporal) hint
         ptr, nbytes = eng.debug_buffer("kv")
         torch.cuda.synchronize()
         assert hip.hipMemset(C.c_void_p(ptr), 0xFF, C.c_size_t(nbytes)) == 0     # fp16 0xFFFF is a NaN
