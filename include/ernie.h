@@ -256,6 +256,8 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
  *   "sk_out", "sk_f2"   split of the contraction of the attention-output / second FFN GEMM over workgroups
  *   "attn_dec" 0..3     decode attention shape: 0 = chosen from max_seq, 1 = 4 waves x 4 key groups in flight,
  *                       2 = 8 waves x 3, 3 = 8 waves x 4 (a batch of waves x groups x 8 keys per memory round trip)
+ *   "ln_ns" 0/1/2/4     32-column strips per workgroup of the decode GEMMs with the LayerNorm prologue (0 = chosen
+ *                       from the batch size); "ln_rpw" 1/2 rows normalised per wave in that prologue
  *   "attn_nt" 0/1       decode attention reads the cache with the non-temporal (streaming) hint, so that the
  *                       once-per-step cache stream does not displace the weights from the caches (default 1)
  * Splits are 1, 2 or 4.  Results are deterministic for any fixed setting.  Returns ERNIE_EINVAL for an

@@ -163,35 +163,41 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_kernel(DecGemmArgs p) {
 }
 
 // A = LayerNorm(sum_k partial_k + bias + residual), normalised in the prologue.
-// grid = (column strips, 1, ceil(B / R)), R = NW * RPW: a workgroup owns R batch rows (RPW per
-// wave) of one 32-column strip, so the redundant normalisation work per workgroup
-// is R rows, not the whole batch; the row groups of a strip read the same weight
-// fragments (from L2 after the first).  The MFMA tile is fed rows 0..R-1 repeated;
-// only the accumulator registers that hold rows < R are reduced and stored.
-template <int NW, int EPI, int RC, int SKIN, int RPW>
+// grid = (ceil(column strips / NS), 1, ceil(B / R)), R = NW * RPW: a workgroup owns R batch rows (RPW per
+// wave) of NS adjacent 32-column strips, so the redundant normalisation work per workgroup
+// is R rows, not the whole batch, and it is shared by NS strips (every workgroup re-reads its rows'
+// partials from L2: with one strip per workgroup that traffic is several times the weight bytes);
+// the row groups of a strip read the same weight fragments (from L2 after the first).  The MFMA tile
+// is fed rows 0..R-1 repeated; only the accumulator registers that hold rows < R are reduced and stored.
+template <int NW, int EPI, int RC, int SKIN, int RPW, int NS = 1>
 __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   constexpr int R = NW * RPW;                 // rows per workgroup: 8, 16 or 32
   constexpr int NV = R / 2;                   // accumulator registers holding rows < R (row = 8(v/4) + 4(lane/32) + v%4)
   static_assert(NW == 8 && (RPW == 1 || RPW == 2 || RPW == 4), "row groups of 8, 16 or 32 rows");
   extern __shared__ __align__(16) unsigned char smem_raw[];
   half_t* sA = reinterpret_cast<half_t*>(smem_raw);            // [R][K + 8]
-  float* red = reinterpret_cast<float*>(smem_raw);             // [NW][NV][64], reused after the MFMA loop
+  float* red = reinterpret_cast<float*>(smem_raw);             // [NW][NS * NV][64], reused after the MFMA loop
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int nt = blockIdx.x;
   const int K = p.K, B = p.B;
   const int k_tiles = K / 16;
+  const int n_tiles = (p.N + 31) / 32;
   const int pitch = K + 8;
   const int kb = k_tiles * wave / NW, ke = k_tiles * (wave + 1) / NW;
   const int row0 = blockIdx.z * R;
 
-  const half_t* wp = p.Wp + packed_frag_offset(nt, 0, k_tiles) + lane * 8;
-  half8 wf[kDecMaxFrag];
+  // strip n of this workgroup is blockIdx.x * NS + n; strips past the end re-read the last one and are not stored
+  const half_t* wp[NS];
+  half8 wf[NS][kDecMaxFrag];
 #pragma unroll
-  for (int u = 0; u < kDecMaxFrag; ++u) {
-    const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-    wf[u] = (kb + u < ke) ? *reinterpret_cast<const half8*>(wp + (size_t)(kb + u) * 512) : z;
+  for (int n = 0; n < NS; ++n) {
+    wp[n] = p.Wp + packed_frag_offset(min((int)blockIdx.x * NS + n, n_tiles - 1), 0, k_tiles) + lane * 8;
+#pragma unroll
+    for (int u = 0; u < kDecMaxFrag; ++u) {
+      const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+      wf[n][u] = (kb + u < ke) ? *reinterpret_cast<const half8*>(wp[n] + (size_t)(kb + u) * 512) : z;
+    }
   }
 
   // prologue: wave w normalises rows row0 + w * RPW + i.  Loads are unconditional with clamped addresses
@@ -296,33 +302,45 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   }
   __syncthreads();
 
-  floatx16 acc;
+  floatx16 acc[NS];
 #pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int n = 0; n < NS; ++n)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
   const half_t* ap = sA + (lane & (R - 1)) * pitch + 8 * (lane >> 5);    // tile rows R..31 repeat rows 0..R-1
   for (int base = kb; base < ke; base += kDecMaxFrag) {
 #pragma unroll
     for (int u = 0; u < kDecMaxFrag; ++u)
-      if (base + u < ke) acc = mfma32(*reinterpret_cast<const half8*>(ap + (base + u) * 16), wf[u], acc);
+      if (base + u < ke) {
+        const half8 a = *reinterpret_cast<const half8*>(ap + (base + u) * 16);
+#pragma unroll
+        for (int n = 0; n < NS; ++n) acc[n] = mfma32(a, wf[n][u], acc[n]);
+      }
     if (base + kDecMaxFrag < ke) {
 #pragma unroll
-      for (int u = 0; u < kDecMaxFrag; ++u) {
-        const int kt = base + kDecMaxFrag + u;
-        const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-        wf[u] = (kt < ke) ? *reinterpret_cast<const half8*>(wp + (size_t)kt * 512) : z;
-      }
+      for (int n = 0; n < NS; ++n)
+#pragma unroll
+        for (int u = 0; u < kDecMaxFrag; ++u) {
+          const int kt = base + kDecMaxFrag + u;
+          const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+          wf[n][u] = (kt < ke) ? *reinterpret_cast<const half8*>(wp[n] + (size_t)kt * 512) : z;
+        }
     }
   }
   __syncthreads();
 
 #pragma unroll
-  for (int v = 0; v < NV; ++v) red[(wave * NV + v) * 64 + lane] = acc[v];
+  for (int n = 0; n < NS; ++n)
+#pragma unroll
+    for (int v = 0; v < NV; ++v) red[(wave * NS * NV + n * NV + v) * 64 + lane] = acc[n][v];
   __syncthreads();
-  for (int v = wave; v < NV; v += NW) {
+  for (int nv = wave; nv < NS * NV; nv += NW) {
+    const int n = nv / NV, v = nv - n * NV;
+    const int nt = blockIdx.x * NS + n;
     float s = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) s += red[(w * NV + v) * 64 + lane];
-    dec_epilogue<EPI>(p, nt, lane, row0 + mfma32_row(v, lane), nt * 32 + (lane & 31), s);
+    for (int w = 0; w < NW; ++w) s += red[(w * NS * NV + nv) * 64 + lane];
+    if (nt < n_tiles) dec_epilogue<EPI>(p, nt, lane, row0 + mfma32_row(v, lane), nt * 32 + (lane & 31), s);
   }
 }
 

@@ -283,12 +283,12 @@ def test_decode_tuning_variants_agree(E):
     orc = oracle_generate(wl, 0, range(sh.batch), sh.n_gen)
     forced = {r: orc[r]["tokens"] for r in orc}
     ref = None
-    for fused, sk_out, sk_f2 in [(1, 1, 1), (0, 1, 1), (1, 2, 2), (1, 4, 2), (1, 1, 4)]:
+    for fused, sk_out, sk_f2, ln_ns in [(1, 1, 1, 1), (0, 1, 1, 1), (1, 2, 2, 1), (1, 4, 2, 2), (1, 1, 4, 4), (1, 2, 4, 2)]:
         eng = E.engine_from_workload(wl)
-        eng.tune("fused_decode", fused); eng.tune("sk_out", sk_out); eng.tune("sk_f2", sk_f2)
-        _say(f"[parity] variant fused={fused} sk_out={sk_out} sk_f2={sk_f2}")
+        eng.tune("fused_decode", fused); eng.tune("sk_out", sk_out); eng.tune("sk_f2", sk_f2); eng.tune("ln_ns", ln_ns)
+        _say(f"[parity] variant fused={fused} sk_out={sk_out} sk_f2={sk_f2} ln_ns={ln_ns}")
         toks, hid, lg = gpu_generate(eng, ids, lens, sh.n_gen, forced)
-        check_rows(orc, toks, hid, lg, f"variant{(fused, sk_out, sk_f2)}")
+        check_rows(orc, toks, hid, lg, f"variant{(fused, sk_out, sk_f2, ln_ns)}")
         if ref is None:
             ref = lg
         assert np.max(np.abs(lg - ref)) < 2e-3
