@@ -236,8 +236,8 @@ int ernie_debug_buffer(ErnieHandle* h, const char* name, void** ptr_dev, size_t*
  * visible positions for decode attention, 2*M*N*K flops for GEMMs and 4*sum(L_b^2)*d for prefill
  * attention.
  */
-#define ERNIE_PROF_GEMM_DEC      0   /* decode GEMM on fp16 activations (attention output, FFN2, layer-0 QKV) */
-#define ERNIE_PROF_GEMM_DEC_LN   1   /* decode GEMM with the LayerNorm prologue (QKV, FFN1) */
+#define ERNIE_PROF_GEMM_DEC      0   /* decode GEMM on fp16 activations (attention output, FFN2) */
+#define ERNIE_PROF_GEMM_DEC_LN   1   /* decode GEMM with a LayerNorm prologue (QKV incl. the embedding LayerNorm of layer 0, FFN1) */
 #define ERNIE_PROF_ATTN_DEC      2   /* decode attention over the key/value cache */
 #define ERNIE_PROF_GEMM_PREFILL  3   /* prefill MFMA GEMMs */
 #define ERNIE_PROF_ATTN_PREFILL  4   /* prefill attention */

@@ -39,6 +39,15 @@ struct DecGemmArgs {
   const float* beta;
   float eps;
   half_t* xout;       // gemm_dec_ln: normalised rows [B, K] fp16, written by the strip-0 workgroups; may be null
+  // gemm_dec_ln with SKIN = 0 (embedding prologue): A = LayerNorm(E'[tok[b]] + Epos[len[b]] (+ segment row))
+  const int* tok;         // [B] ids fed to this step
+  const int* cache_len;   // [B] position of the new token
+  const half_t* tok_emb;  // [V', K] row-major trimmed table
+  const half_t* pos_emb;  // [P, K]
+  const half_t* seg_row;  // [K] or null
+  int max_pos;
+  int eos;                // >= 0: a row fed this id is marked finished (by the strip-0 workgroups)
+  int* finished;
   // outputs
   float* rout;        // EPI_RAW: [gridDim.y][B][N]
   const float* bias_out;  // EPI_GELU16: [N] bias of THIS GEMM; EPI_ARGMAX: optional [N] output bias (may be null)
@@ -162,7 +171,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_kernel(DecGemmArgs p) {
   }
 }
 
-// A = LayerNorm(sum_k partial_k + bias + residual), normalised in the prologue.
+// A = LayerNorm(sum_k partial_k + bias + residual), normalised in the prologue (SKIN = 0: A = the
+// embedding LayerNorm of the tokens fed to the step instead, see DecGemmArgs).
 // grid = (ceil(column strips / NS), 1, ceil(B / R)), R = NW * RPW: a workgroup owns R batch rows (RPW per
 // wave) of NS adjacent 32-column strips, so the redundant normalisation work per workgroup
 // is R rows, not the whole batch, and it is shared by NS strips (every workgroup re-reads its rows'
@@ -210,8 +220,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
 #pragma unroll
     for (int c = 0; c < RC; ++c) {
       const int cc = min(c * 64 + lane, chunks - 1);
-      const float4 b0 = *reinterpret_cast<const float4*>(p.bias + cc * 8);
-      const float4 b1 = *reinterpret_cast<const float4*>(p.bias + cc * 8 + 4);
+      float4 b0 = {0.f, 0.f, 0.f, 0.f}, b1 = {0.f, 0.f, 0.f, 0.f};
+      if constexpr (SKIN > 0) {
+        b0 = *reinterpret_cast<const float4*>(p.bias + cc * 8);
+        b1 = *reinterpret_cast<const float4*>(p.bias + cc * 8 + 4);
+      }
       const float4 g0 = *reinterpret_cast<const float4*>(p.gamma + cc * 8);
       const float4 g1 = *reinterpret_cast<const float4*>(p.gamma + cc * 8 + 4);
       const float4 t0 = *reinterpret_cast<const float4*>(p.beta + cc * 8);
@@ -226,14 +239,33 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
       const int rr = min(row0 + wave * RPW + i, B - 1);
+      if constexpr (SKIN == 0) {
+        // embedding prologue: token row + position row (+ segment row); the sum is not biased
+        const int id = p.tok[rr];
+        const int pos = min(p.cache_len[rr], p.max_pos - 1);
+        if (p.eos >= 0 && blockIdx.x == 0 && lane == 0 && row0 + wave * RPW + i < B && id == p.eos) p.finished[rr] = 1;
+#pragma unroll
+        for (int c = 0; c < RC; ++c) {
+          const int cc = min(c * 64 + lane, chunks - 1);
+          const half8 e = *reinterpret_cast<const half8*>(p.tok_emb + (size_t)id * K + cc * 8);
+          const half8 q = *reinterpret_cast<const half8*>(p.pos_emb + (size_t)pos * K + cc * 8);
+          half8 g8 = {0, 0, 0, 0, 0, 0, 0, 0};
+          if (p.seg_row) g8 = *reinterpret_cast<const half8*>(p.seg_row + cc * 8);
+          const float live = (c * 64 + lane < chunks) ? 1.f : 0.f;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) v[i][c][j] = ((float)e[j] + (float)q[j] + (float)g8[j]) * live;
+        }
+        continue;
+      }
+      constexpr int SKL = SKIN > 0 ? SKIN : 1;
       half8 rs[RC];
-      float4 y0[SKIN][RC], y1[SKIN][RC];
+      float4 y0[SKL][RC], y1[SKL][RC];
 #pragma unroll
       for (int c = 0; c < RC; ++c) {
         const int cc = min(c * 64 + lane, chunks - 1);
         rs[c] = *reinterpret_cast<const half8*>(p.res + (size_t)rr * K + cc * 8);
 #pragma unroll
-        for (int s = 0; s < SKIN; ++s) {
+        for (int s = 0; s < SKL; ++s) {
           const float* src = p.r32 + ((size_t)s * B + rr) * K + cc * 8;
           y0[s][c] = *reinterpret_cast<const float4*>(src);
           y1[s][c] = *reinterpret_cast<const float4*>(src + 4);
@@ -243,7 +275,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
       for (int c = 0; c < RC; ++c) {
         float a[8] = {y0[0][c].x, y0[0][c].y, y0[0][c].z, y0[0][c].w, y1[0][c].x, y1[0][c].y, y1[0][c].z, y1[0][c].w};
 #pragma unroll
-        for (int s = 1; s < SKIN; ++s) {
+        for (int s = 1; s < SKL; ++s) {
           a[0] += y0[s][c].x; a[1] += y0[s][c].y; a[2] += y0[s][c].z; a[3] += y0[s][c].w;
           a[4] += y1[s][c].x; a[5] += y1[s][c].y; a[6] += y1[s][c].z; a[7] += y1[s][c].w;
         }

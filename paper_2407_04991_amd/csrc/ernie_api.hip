@@ -261,6 +261,7 @@ int configure_kernels() {
   rc |= allow_lds(logits_argmax_kernel<8, 4>, big);
 #define LN_LDS1(EPI, SK, RPW) rc |= allow_lds(gemm_dec_ln_kernel<8, EPI, 2, SK, RPW, 1>, kMaxLds); rc |= allow_lds(gemm_dec_ln_kernel<8, EPI, 2, SK, RPW, 2>, kMaxLds); rc |= allow_lds(gemm_dec_ln_kernel<8, EPI, 2, SK, RPW, 4>, kMaxLds)
 #define LN_LDS(EPI, SK) LN_LDS1(EPI, SK, 1); LN_LDS1(EPI, SK, 2)
+  LN_LDS(EPI_RAW, 0);
   LN_LDS(EPI_RAW, 1); LN_LDS(EPI_RAW, 2); LN_LDS(EPI_RAW, 4); LN_LDS(EPI_GELU16, 1); LN_LDS(EPI_GELU16, 2); LN_LDS(EPI_GELU16, 4);
 #undef LN_LDS
 #undef LN_LDS1
@@ -327,6 +328,7 @@ int launch_gemm_dec_ln(ErnieHandle* h, DecGemmArgs a, hipStream_t s) {
 #define LN_BY_NS(SK, RPW) do { if (ns == 1) LN_LAUNCH(SK, RPW, 1); else if (ns == 2) LN_LAUNCH(SK, RPW, 2); else LN_LAUNCH(SK, RPW, 4); } while (0)
 #define LN_BY_RPW(SK) do { if (rpw == 1) LN_BY_NS(SK, 1); else LN_BY_NS(SK, 2); } while (0)
   switch (a.sk_in) {      // the count of split-K partials to add is a template parameter of the prologue
+    case 0: if constexpr (EPI == EPI_RAW) { LN_BY_RPW(0); break; } else return ERNIE_EINVAL;   // embedding prologue
     case 1: LN_BY_RPW(1); break;
     case 2: LN_BY_RPW(2); break;
     case 4: LN_BY_RPW(4); break;
@@ -348,7 +350,7 @@ bool fused_decode_fits(const ErnieHandle* h, int B) {
 
 const half_t* apply_head(ErnieHandle* h, const half_t* x, int B, hipStream_t s);
 
-int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hipStream_t s) {
+int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float* hidden_out, hipStream_t s) {
   const ErnieConfig& c = h->cfg;
   const int B = h->B, d = c.d_model, f = c.d_ffn;
   int rc = ERNIE_OK;
@@ -359,8 +361,11 @@ int decode_layers_fused(ErnieHandle* h, float* logits_out, float* hidden_out, hi
     // QKV: layer 0 reads the embedding rows; later layers normalise the previous FFN2 output on the fly
     a.Wp = L.wqkv; a.N = 3 * d; a.K = d; a.rout = h->r_qkv;
     if (l == 0) {
-      a.a16 = h->X;
-      rc |= launch_gemm_dec<EPI_RAW>(h, a, 1, s);
+      // the embedding LayerNorm of the fed tokens is this GEMM's prologue (no separate embedding launch)
+      a.sk_in = 0; a.tok = tok; a.cache_len = h->lens; a.tok_emb = h->tok_rm; a.pos_emb = h->pos;
+      a.seg_row = h->type_emb ? h->type_emb + d : nullptr; a.max_pos = c.max_pos; a.eos = h->eos; a.finished = h->finished;
+      a.gamma = h->emb_g; a.beta = h->emb_b; a.xout = h->X;
+      rc |= launch_gemm_dec_ln<EPI_RAW>(h, a, s);
     } else {
       const LayerPtrs& P = h->layers[l - 1];
       a.r32 = h->r_f2; a.sk_in = h->sk_f2; a.bias = P.b2; a.res = h->X1; a.gamma = P.ln2_g; a.beta = P.ln2_b;
@@ -680,11 +685,15 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_o
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int B = h->B, d = c.d_model;
   const int* tok = tok_in_dev ? tok_in_dev : h->tok_prev;
-  { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_decode_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, tok, h->lens, B, c.max_pos,
-                     h->tok_rm, h->pos, h->type_emb ? h->type_emb + d : nullptr, h->emb_g, h->emb_b, c.ln_eps, d, h->X,
-                     h->eos, h->finished)); }
-  const int rc = fused_decode_fits(h, B) ? decode_layers_fused(h, logits_out_dev, hidden_out_dev, s)
-                                         : decode_layers_big(h, logits_out_dev, hidden_out_dev, s);
+  int rc;
+  if (fused_decode_fits(h, B)) {
+    rc = decode_layers_fused(h, tok, logits_out_dev, hidden_out_dev, s);
+  } else {
+    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_decode_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, tok, h->lens, B, c.max_pos,
+                       h->tok_rm, h->pos, h->type_emb ? h->type_emb + d : nullptr, h->emb_g, h->emb_b, c.ln_eps, d, h->X,
+                       h->eos, h->finished)); }
+    rc = decode_layers_big(h, logits_out_dev, hidden_out_dev, s);
+  }
   if (rc != ERNIE_OK) return rc;
   { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
   hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->plan.strips,

@@ -349,7 +349,8 @@ def test_profile_hooks_count_launches(E):
     assert p["gemm_prefill"][1] == 4 * Nl and p["attn_prefill"][1] == Nl
     assert p["attn_dec"][1] == 3 * Nl and p["logits"][1] == 3
     assert p["gemm_dec"][1] + p["gemm_dec_ln"][1] == 3 * 4 * Nl          # four projections per layer per step
-    assert p["gemm_dec_ln"][1] == 3 * (2 * Nl - 1)                       # QKV of layers >= 1 and every FFN1
+    assert p["gemm_dec_ln"][1] == 3 * 2 * Nl                             # every QKV (layer 0: embedding prologue) and FFN1
+    assert p["row_dec"][1] == 3 * 2                                      # final LayerNorm and second argmax stage per step
     w_layer = (4 * d * d + 2 * d * f) * 2
     assert abs(p["gemm_dec"][2] + p["gemm_dec_ln"][2] - 3 * Nl * w_layer) < 1
     kv = sum(2 * (int(lens.sum()) + sh.batch * (t + 1)) * d * 2 for t in range(3)) * Nl
