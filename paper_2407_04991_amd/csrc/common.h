@@ -61,4 +61,11 @@ __device__ __forceinline__ float gelu_erf(float a) {
   return a * 0.5f * (1.0f + erff(a * 0.70710678118654752440f));
 }
 
+// Workgroup id -> logical id such that the workgroups of one XCD (ids congruent mod 8) cover a
+// contiguous range of logical ids: neighbours in the logical order then share that XCD's L2.
+__device__ __forceinline__ int xcd_contiguous_id(int id, int total) {
+  const int x = id & 7, q = total >> 3, r = total & 7;
+  return x * q + min(x, r) + (id >> 3);
+}
+
 }  // namespace ernie

@@ -173,7 +173,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_kernel(DecGemmArgs p) {
 
 // A = LayerNorm(sum_k partial_k + bias + residual), normalised in the prologue (SKIN = 0: A = the
 // embedding LayerNorm of the tokens fed to the step instead, see DecGemmArgs).
-// grid = (ceil(column strips / NS), 1, ceil(B / R)), R = NW * RPW: a workgroup owns R batch rows (RPW per
+// grid = ceil(column strips / NS) * ceil(B / R) workgroups, R = NW * RPW: a workgroup owns R batch rows (RPW per
 // wave) of NS adjacent 32-column strips, so the redundant normalisation work per workgroup
 // is R rows, not the whole batch, and it is shared by NS strips (every workgroup re-reads its rows'
 // partials from L2: with one strip per workgroup that traffic is several times the weight bytes);
@@ -195,14 +195,20 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   const int n_tiles = (p.N + 31) / 32;
   const int pitch = K + 8;
   const int kb = k_tiles * wave / NW, ke = k_tiles * (wave + 1) / NW;
-  const int row0 = blockIdx.z * R;
+  // 1-D grid of (strip groups x row groups)
+  const int zg = (B + R - 1) / R;
+  // XCD-contiguous order, row group fastest: the row groups of a strip group run on one XCD and share its
+  // weight fragments in that L2 (measured: same speed as spreading them over XCDs, 30 % fewer HBM bytes)
+  const int logical = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int sg = logical / zg, zi = logical - sg * zg;
+  const int row0 = zi * R;
 
-  // strip n of this workgroup is blockIdx.x * NS + n; strips past the end re-read the last one and are not stored
+  // strip n of this workgroup is sg * NS + n; strips past the end re-read the last one and are not stored
   const half_t* wp[NS];
   half8 wf[NS][kDecMaxFrag];
 #pragma unroll
   for (int n = 0; n < NS; ++n) {
-    wp[n] = p.Wp + packed_frag_offset(min((int)blockIdx.x * NS + n, n_tiles - 1), 0, k_tiles) + lane * 8;
+    wp[n] = p.Wp + packed_frag_offset(min(sg * NS + n, n_tiles - 1), 0, k_tiles) + lane * 8;
 #pragma unroll
     for (int u = 0; u < kDecMaxFrag; ++u) {
       const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -243,7 +249,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
         // embedding prologue: token row + position row (+ segment row); the sum is not biased
         const int id = p.tok[rr];
         const int pos = min(p.cache_len[rr], p.max_pos - 1);
-        if (p.eos >= 0 && blockIdx.x == 0 && lane == 0 && row0 + wave * RPW + i < B && id == p.eos) p.finished[rr] = 1;
+        if (p.eos >= 0 && sg == 0 && lane == 0 && row0 + wave * RPW + i < B && id == p.eos) p.finished[rr] = 1;
 #pragma unroll
         for (int c = 0; c < RC; ++c) {
           const int cc = min(c * 64 + lane, chunks - 1);
@@ -318,7 +324,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
     for (int i = 0; i < RPW; ++i) {
       const int r = row0 + wave * RPW + i;
       const float rs = rsqrtf(rstd[i] / (float)K + p.eps);
-      const bool writer = p.xout && blockIdx.x == 0 && r < B;
+      const bool writer = p.xout && sg == 0 && r < B;
 #pragma unroll
       for (int c = 0; c < RC; ++c) {
         const int ch = c * 64 + lane;
@@ -368,7 +374,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   __syncthreads();
   for (int nv = wave; nv < NS * NV; nv += NW) {
     const int n = nv / NV, v = nv - n * NV;
-    const int nt = blockIdx.x * NS + n;
+    const int nt = sg * NS + n;
     float s = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) s += red[(w * NS * NV + nv) * 64 + lane];

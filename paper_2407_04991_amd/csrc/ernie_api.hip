@@ -323,7 +323,7 @@ int launch_gemm_dec_ln(ErnieHandle* h, DecGemmArgs a, hipStream_t s) {
   const size_t a_bytes = (size_t)R * (a.K + 8) * 2, r_bytes = (size_t)NW * ns * (R / 2) * 64 * 4;
   const size_t lds = a_bytes > r_bytes ? a_bytes : r_bytes;
   const int strips = (a.N + 31) / 32;
-  const dim3 grid((strips + ns - 1) / ns, 1, (a.B + R - 1) / R), block(NW * 64);
+  const dim3 grid(((strips + ns - 1) / ns) * ((a.B + R - 1) / R)), block(NW * 64);
 #define LN_LAUNCH(SK, RPW, NS) hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2, SK, RPW, NS>), grid, block, lds, s, a)
 #define LN_BY_NS(SK, RPW) do { if (ns == 1) LN_LAUNCH(SK, RPW, 1); else if (ns == 2) LN_LAUNCH(SK, RPW, 2); else LN_LAUNCH(SK, RPW, 4); } while (0)
 #define LN_BY_RPW(SK) do { if (rpw == 1) LN_BY_NS(SK, 1); else LN_BY_NS(SK, 2); } while (0)

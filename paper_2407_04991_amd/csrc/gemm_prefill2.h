@@ -56,13 +56,6 @@ struct GemmPipe {
   static_assert(kAInstr >= 1 && kBM % (kRowsPerInstr * kWaves) == 0, "A tile must split evenly over the waves");
 };
 
-// Workgroup id -> logical tile id such that the workgroups of one XCD (ids congruent mod 8) cover a
-// contiguous range of tiles: they then share A rows and W columns in that XCD's L2.
-__device__ __forceinline__ int xcd_contiguous_id(int id, int total) {
-  const int x = id & 7, q = total >> 3, r = total & 7;
-  return x * q + min(x, r) + (id >> 3);
-}
-
 // DBG (measurement builds only, 0 in the library): 1 = no operand copies after the first stages,
 // 2 = fragments read from LDS once, 4 = no barrier / waits, 8 = no A copies, 16 = no W copies.
 template <int WGM, int WGN, int TM, int TN, int BK, int S, class Epi, int DBG = 0>
