@@ -78,7 +78,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     global _lib
     if _lib is not None and path is None:
         return _lib
-    p = path or LIB_PATH
+    p = path or os.environ.get("ERNIE_HIP_LIB") or LIB_PATH     # the variable selects another build of the same library
     if not os.path.exists(p):
         raise FileNotFoundError(
             f"{p} not found: build it with `python -m paper_2407_04991_amd.build` (there is no CPU fallback)")

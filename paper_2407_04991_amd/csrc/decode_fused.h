@@ -407,11 +407,13 @@ __global__ __launch_bounds__(256) void ln_partials_kernel(const float* __restric
     v.v[c][3] = b0.w + (float)rs[3]; v.v[c][4] = b1.x + (float)rs[4]; v.v[c][5] = b1.y + (float)rs[5];
     v.v[c][6] = b1.z + (float)rs[6]; v.v[c][7] = b1.w + (float)rs[7];
   }
-  // partials are added in index order, four buffers' loads in flight at a time
-  for (int s0 = 0; s0 < sk_in; s0 += 4) {
-    float4 x0[4][RC], x1[4][RC];
+  // partials are added in index order, up to eight buffers' loads in flight at a time (one memory round trip
+  // for every split the host uses)
+  constexpr int kBatch = (RC <= 2) ? 8 : 4;
+  for (int s0 = 0; s0 < sk_in; s0 += kBatch) {
+    float4 x0[kBatch][RC], x1[kBatch][RC];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kBatch; ++u) {
       const int s = min(s0 + u, sk_in - 1);
 #pragma unroll
       for (int c = 0; c < RC; ++c) {
@@ -421,8 +423,9 @@ __global__ __launch_bounds__(256) void ln_partials_kernel(const float* __restric
         x1[u][c] = *reinterpret_cast<const float4*>(src + 4);
       }
     }
+    __builtin_amdgcn_sched_barrier(0);      // every load above is issued before the first sum below waits on one
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kBatch; ++u) {
       const float live = (s0 + u < sk_in) ? 1.f : 0.f;
 #pragma unroll
       for (int c = 0; c < RC; ++c) {

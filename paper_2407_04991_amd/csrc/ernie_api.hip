@@ -257,6 +257,7 @@ int configure_kernels() {
   rc |= allow_lds(gemm_prefill2_kernel<__VA_ARGS__, EpiRaw32>, GemmPipe<__VA_ARGS__>::kLdsBytes)
   GEMM_LDS(4, 4, 2, 2, 32, 3); GEMM_LDS(2, 2, 2, 2, 32, 3); GEMM_LDS(2, 2, 2, 1, 64, 3); GEMM_LDS(2, 2, 2, 1, 32, 3);
 #undef GEMM_LDS
+  rc |= allow_lds(gemm_prefill2_kernel<2, 2, 1, 1, 64, 3, EpiRaw32>, GemmPipe<2, 2, 1, 1, 64, 3>::kLdsBytes);
   const size_t big = (size_t)4 * 8 * 16 * 64 * 4;   // MT = 8, NW = 4
   rc |= allow_lds(logits_argmax_kernel<8, 4>, big);
 #define LN_LDS1(EPI, SK, RPW) rc |= allow_lds(gemm_dec_ln_kernel<8, EPI, 2, SK, RPW, 1>, kMaxLds); rc |= allow_lds(gemm_dec_ln_kernel<8, EPI, 2, SK, RPW, 2>, kMaxLds); rc |= allow_lds(gemm_dec_ln_kernel<8, EPI, 2, SK, RPW, 4>, kMaxLds)
@@ -401,15 +402,18 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
 }
 
 // Decode projections at B > 64: the batch is a real M dimension, so they run on the MFMA GEMM pipeline
-// (128 x 64 tiles) with the contraction split over gridDim.y until about 192 workgroups stream the
-// weights; partial results are fp32 [split][B][N].
+// (64 x 64 tiles, BK = 64: measured 10-20 % faster than 128 x 64 at these shapes) with the contraction split
+// over gridDim.y until about 256 workgroups stream the weights, each keeping a slice of at least 192;
+// partial results are fp32 [split][B][N].
+using SplitPipe = GemmPipe<2, 2, 1, 1, 64, 3>;
+
 int pick_gemm_split(int B, int N, int K) {
-  const long tiles = (long)((B + 127) / 128) * ((N + 63) / 64);
+  const long tiles = (long)((B + SplitPipe::kBM - 1) / SplitPipe::kBM) * ((N + SplitPipe::kBN - 1) / SplitPipe::kBN);
   int best = 1;
   for (int sk = 1; sk <= kBigMaxSplitK; sk *= 2) {
-    if ((K / 32) % sk != 0 || K / sk < 128) break;
+    if ((K / 64) % sk != 0 || (sk > 1 && K / sk < 192)) break;
     best = sk;
-    if (tiles * sk >= 192) break;
+    if (tiles * sk >= 256) break;
   }
   return best;
 }
@@ -417,9 +421,9 @@ int pick_gemm_split(int B, int N, int K) {
 void launch_gemm_splitk(ErnieHandle* h, const half_t* A, const half_t* Wp, int M, int N, int K, float* out, int sk,
                         hipStream_t s) {
   ProfScope prof(h, ERNIE_PROF_GEMM_DEC, s, 2.0 * N * K, 2.0 * M * N * K);
-  using P = GemmPipe<2, 2, 2, 1, 32, 3>;
+  using P = SplitPipe;
   const int tiles_m = (M + P::kBM - 1) / P::kBM, tiles_n = (N + P::kBN - 1) / P::kBN;
-  hipLaunchKernelGGL((gemm_prefill2_kernel<2, 2, 2, 1, 32, 3, EpiRaw32>), dim3(tiles_m * tiles_n, sk), dim3(256),
+  hipLaunchKernelGGL((gemm_prefill2_kernel<2, 2, 1, 1, 64, 3, EpiRaw32>), dim3(tiles_m * tiles_n, sk), dim3(256),
                      P::kLdsBytes, s, A, Wp, h->zero_bias, M, N, K, (N + 31) / 32, tiles_n,
                      EpiRaw32{out, N, (size_t)M * N});
 }
