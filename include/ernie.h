@@ -254,10 +254,13 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
  *   "fused_decode" 0/1  use the small-batch path (row-wise work fused into GEMM prologues) when it fits,
  *                       else the large-batch path (split-K partials summed by row kernels)
  *   "sk_out", "sk_f2"   split of the contraction of the attention-output / second FFN GEMM over workgroups
- *   "attn_dec" 0..3     decode attention shape: 0 = chosen from max_seq, 1 = 4 waves x 4 key groups in flight,
- *                       2 = 8 waves x 3, 3 = 8 waves x 4 (a batch of waves x groups x 8 keys per memory round trip)
+ *   "attn_dec" 0..5     decode attention shape: 0 = chosen from the batch and capacity, 1 = 4 waves x 4 key groups
+ *                       in flight, 2 = 8 waves x 3, 3 = 8 waves x 4, 4 = 4 waves x 2, 5 = 2 waves x 2 (a batch of
+ *                       waves x groups x 8 keys per memory round trip)
  *   "ln_ns" 0/1/2/4     32-column strips per workgroup of the decode GEMMs with the LayerNorm prologue (0 = chosen
  *                       from the batch size); "ln_rpw" 1/2 rows normalised per wave in that prologue
+ *   "big_f1_fused" 0/1  large-batch path: first FFN GEMM unsplit with bias + GELU in its epilogue (default 1), or
+ *                       split over the contraction with a separate GELU row kernel
  *   "attn_nt" 0/1       decode attention reads the cache with the non-temporal (streaming) hint, so that the
  *                       once-per-step cache stream does not displace the weights from the caches (default 1)
  * Splits are 1, 2 or 4.  Results are deterministic for any fixed setting.  Returns ERNIE_EINVAL for an

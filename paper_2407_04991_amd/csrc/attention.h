@@ -233,12 +233,25 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_fused_kernel(const float*
     const float* r = Rqkv + (size_t)b * 3 * d + h * 64 + ec * 8;
     const float* bs = bqkv + h * 64 + ec * 8;
     float aq[8], ak[8], av[8];
+    if (sk_in == 1) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { aq[j] = r[j] + bs[j]; ak[j] = r[d + j] + bs[d + j]; av[j] = r[2 * d + j] + bs[2 * d + j]; }
-    for (int s = 1; s < sk_in; ++s) {                       // further split-K partials, in index order
-      const float* rs = r + (size_t)s * B * 3 * d;
+      for (int j = 0; j < 8; ++j) { aq[j] = r[j] + bs[j]; ak[j] = r[d + j] + bs[d + j]; av[j] = r[2 * d + j] + bs[2 * d + j]; }
+    } else {
+      // split-K partials (at most 8): team t fetches partial t, so all of them arrive in one memory round
+      // trip; the teams are then summed by a fixed butterfly (same order on every run)
+      const float live = (team < sk_in) ? 1.f : 0.f;
+      const float* rs = r + (size_t)min(team, sk_in - 1) * B * 3 * d;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) { aq[j] += rs[j]; ak[j] += rs[d + j]; av[j] += rs[2 * d + j]; }
+      for (int j = 0; j < 8; ++j) { aq[j] = rs[j] * live; ak[j] = rs[d + j] * live; av[j] = rs[2 * d + j] * live; }
+#pragma unroll
+      for (int off = 8; off < 64; off <<= 1) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          aq[j] += __shfl_xor(aq[j], off, 64); ak[j] += __shfl_xor(ak[j], off, 64); av[j] += __shfl_xor(av[j], off, 64);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { aq[j] += bs[j]; ak[j] += bs[d + j]; av[j] += bs[2 * d + j]; }
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {

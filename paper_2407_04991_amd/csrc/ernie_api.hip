@@ -139,7 +139,7 @@ struct ErnieHandle {
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
   half_t *type_emb = nullptr, *head_w = nullptr;                      // optional variants, null when off
   float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
-  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 1;   // decode tuning (see ernie_debug_tune)
+  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 1, big_f1_fused = 1;   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   int *finished, *slot, *keep;   // per-sequence finished flag, cache row of each batch row, compaction list
   int eos = -1;                  // end-of-sequence id (trimmed), -1 = none
@@ -190,13 +190,18 @@ void launch_attn_decode(const ErnieHandle* h, const float* rqkv, int sk_in, int 
                         half_t* vc, hipStream_t s) {
   const int H = h->cfg.n_heads, S = h->cfg.max_seq, d = h->cfg.d_model;
   int v = h->attn_dec;
-  if (v == 0) v = 1;   // measured: the three shapes are within 5 % of each other at every cache length tried
+  // Measured on all benchmark shapes: two key groups in flight per wave (84 registers, five waves per SIMD)
+  // beat four (115 registers) by 0.3-3 %; with thousands of short streams (B x H >= 1024, capacity <= 384
+  // positions) two waves per workgroup beat four by another 1.7 %.
+  if (v == 0) v = ((long)B * H >= 1024 && S <= 384) ? 5 : 4;
 #define ATTN_DEC_LAUNCH(NW, U, NT)                                                                                  \
   hipLaunchKernelGGL((attn_decode_fused_kernel<NW, U, NT>), dim3(H, B), dim3(NW * 64), 0, s, rqkv, sk_in, B, bqkv, \
                      kc, vc, h->lens, H, S, d, h->O, h->eos >= 0 ? h->finished : nullptr,                        \
                      h->compacted ? h->slot : nullptr)
   if (v == 2) ATTN_DEC_LAUNCH(8, 3, false);
   else if (v == 3) ATTN_DEC_LAUNCH(8, 4, false);
+  else if (v == 4) ATTN_DEC_LAUNCH(4, 2, true);
+  else if (v == 5) ATTN_DEC_LAUNCH(2, 2, true);
   else if (h->attn_nt) ATTN_DEC_LAUNCH(4, 4, true);
   else ATTN_DEC_LAUNCH(4, 4, false);
 #undef ATTN_DEC_LAUNCH
@@ -464,11 +469,18 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
     { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
       ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_out, sk_o,
                                          L.bo, h->X, B, d, L.ln1_g, L.ln1_b, c.ln_eps, h->X1, (float*)nullptr)); }
-    launch_gemm_splitk(h, h->X1, L.w1, B, f, d, h->r_f1, sk_1, s);
-    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
+    if (h->big_f1_fused) {
+      // FFN1 keeps its contraction whole: bias + GELU in the GEMM epilogue, no partial buffers and one launch
+      // less (the wide N gives enough 64 x 64 tiles; the unsplit GEMM costs 0.3-1.6 us more, a launch 5-6 us)
+      ProfScope prof(h, ERNIE_PROF_GEMM_DEC, s, 2.0 * f * d, 2.0 * B * f * d);
+      launch_gemm_prefill_t<2, 2, 1, 1, 64, 3>(h->X1, L.w1, L.b1, B, f, d, EpiGelu{h->G, f}, s);
+    } else {
+      launch_gemm_splitk(h, h->X1, L.w1, B, f, d, h->r_f1, sk_1, s);
+      ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
       const size_t n8 = (size_t)B * f / 8;
       hipLaunchKernelGGL(gelu_partials_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, h->r_f1, sk_1, L.b1,
-                         B, f, h->G); }
+                         B, f, h->G);
+    }
     launch_gemm_splitk(h, h->G, L.w2, B, d, f, h->r_f2, sk_2, s);
     { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
       float* hid = (l == c.n_layers - 1) ? hidden_out : nullptr;
@@ -846,6 +858,7 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
 int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!h || !key) return ERNIE_EINVAL;
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
+  if (!strcmp(key, "big_f1_fused")) { h->big_f1_fused = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "ln_rpw")) {
     if (value != 1 && value != 2) return ERNIE_EINVAL;
     h->ln_rpw = value;
@@ -858,7 +871,7 @@ int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   }
   if (!strcmp(key, "attn_nt")) { h->attn_nt = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "attn_dec")) {
-    if (value < 0 || value > 3) return ERNIE_EINVAL;
+    if (value < 0 || value > 5) return ERNIE_EINVAL;
     h->attn_dec = value;
     return ERNIE_OK;
   }

@@ -313,7 +313,7 @@ def test_decode_attention_shapes_and_poisoned_cache_tail(E):
     orc = oracle_generate(wl, 0, range(len(lengths)), n_gen)
     forced = {r: orc[r]["tokens"] for r in orc}
     hip = C.CDLL("libamdhip64.so.7")
-    for variant, nt in ((0, 1), (1, 0), (1, 1), (2, 0), (3, 0)):
+    for variant, nt in ((0, 1), (1, 0), (1, 1), (2, 0), (3, 0), (4, 1), (5, 1)):
         eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
         eng.tune("attn_dec", variant)
         eng.tune("attn_nt", nt)              # cache rows read with / without the streaming (non-temporal) hint
@@ -328,7 +328,7 @@ def test_decode_attention_shapes_and_poisoned_cache_tail(E):
         eng.close()
     eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
     with pytest.raises(E.ErnieError):
-        eng.tune("attn_dec", 4)
+        eng.tune("attn_dec", 6)
     eng.close()
 
 
