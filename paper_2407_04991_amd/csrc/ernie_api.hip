@@ -48,7 +48,7 @@ struct ArenaPlan {
   size_t type_emb, head_w, head_b, head_g, head_beta, out_bias;   // optional variants (0 bytes when off)
   bool has_type, has_head, has_bias;
   size_t kv, X, X1, Y, Q, O, G, Yf, hlast, strip_val, strip_idx, cu, lens, tok_seq, tok_pos, tok_prev;
-  size_t finished, slot, keep;
+  size_t finished, slot, keep, r_logits;
   size_t total;
   int vocab_tiles, strips;
   size_t t_max;
@@ -86,7 +86,9 @@ ArenaPlan make_plan(const ErnieConfig& c, const ErnieVariants* var) {
   // raw fp32 GEMM outputs of the decode step, split over K into up to kBigMaxSplitK partial buffers
   p.r_qkv = take((size_t)kBigMaxSplitK * Bm * 3 * d * 4); p.r_out = take((size_t)kBigMaxSplitK * Bm * d * 4);
   p.r_f1 = take((size_t)kBigMaxSplitK * Bm * f * 4); p.r_f2 = take((size_t)kBigMaxSplitK * Bm * d * 4);
-  p.zero_bias = take((3 * d > f ? 3 * d : f) * 4);
+  p.zero_bias = take(std::max(std::max(3 * d, f), V) * 4);
+  // fp32 partial logits of the large-batch projection (two splits at most); not needed while max_batch <= 64
+  p.r_logits = take(Bm > 64 ? (size_t)2 * Bm * V * 4 : 0);
   p.type_emb = take(p.has_type ? 2 * d * 2 : 0);
   p.head_w = take(p.has_head ? d * d * 2 : 0);
   p.head_b = take(p.has_head ? d * 4 : 0); p.head_g = take(p.has_head ? d * 4 : 0);
@@ -139,8 +141,10 @@ struct ErnieHandle {
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
   half_t *type_emb = nullptr, *head_w = nullptr;                      // optional variants, null when off
   float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
-  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 1, big_f1_fused = 1;   // decode tuning (see ernie_debug_tune)
+  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 1, big_f1_fused = 1, big_logits_gemm = 1;
+  int cand = 0;                  // argmax candidates per row left by the last projection   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
+  float* r_logits = nullptr;     // [2][max_batch][V'] fp32, large-batch projection only
   int *finished, *slot, *keep;   // per-sequence finished flag, cache row of each batch row, compaction list
   int eos = -1;                  // end-of-sequence id (trimmed), -1 = none
   bool compacted = false;        // some row map entry differs from its index
@@ -242,11 +246,17 @@ void launch_logits_t(ErnieHandle* h, const half_t* X, int B, float* logits_out, 
                      h->plan.strips);
 }
 
-void launch_logits(ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s) {
+void launch_logits_big(ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s);
+
+// Leaves per-strip argmax candidates in strip_val / strip_idx; returns how many candidates each row has.
+int launch_logits(ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s) {
+  // (the GEMM epilogue stores runs of 8 columns, so the row length must be a multiple of 8)
+  if (B > 64 && h->big_logits_gemm && h->cfg.vocab_kept % 8 == 0) { launch_logits_big(h, X, B, logits_out, s); return 1; }
   if (B <= 32) launch_logits_t<1, 4>(h, X, B, logits_out, s);
   else if (B <= 64) launch_logits_t<2, 4>(h, X, B, logits_out, s);
   else if (B <= 128) launch_logits_t<4, 4>(h, X, B, logits_out, s);
   else launch_logits_t<8, 4>(h, X, B, logits_out, s);
+  return h->plan.strips;
 }
 
 // Kernels whose dynamic LDS exceeds the 64 KiB default need an explicit opt-in.
@@ -404,6 +414,7 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
   z.B = B; z.Wp = h->tok_p; z.N = c.vocab_kept; z.K = d; z.a16 = apply_head(h, h->X, B, s); z.logits_out = logits_out;
   z.bias_out = h->out_bias;
   z.strip_val = h->strip_val; z.strip_idx = h->strip_idx; z.strips = h->plan.strips;
+  h->cand = h->plan.strips;
   rc |= launch_gemm_dec<EPI_ARGMAX>(h, z, 1, s);
   return rc ? ERNIE_EHIP : ERNIE_OK;
 }
@@ -433,6 +444,20 @@ void launch_gemm_splitk(ErnieHandle* h, const half_t* A, const half_t* Wp, int M
   hipLaunchKernelGGL((gemm_prefill2_kernel<2, 2, 1, 1, 64, 3, EpiRaw32>), dim3(tiles_m * tiles_n, sk), dim3(256),
                      P::kLdsBytes, s, A, Wp, h->zero_bias, M, N, K, (N + 31) / 32, tiles_n,
                      EpiRaw32{out, N, (size_t)M * N});
+}
+
+// Output projection at B > 64 on the MFMA GEMM pipeline: fp32 partial logits (one or two splits of the
+// contraction), then one workgroup per sequence adds them and takes the row argmax.
+void launch_logits_big(ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s) {
+  using P = SplitPipe;
+  const int N = h->cfg.vocab_kept, K = h->cfg.d_model;
+  const int tiles_m = (B + P::kBM - 1) / P::kBM, tiles_n = (N + P::kBN - 1) / P::kBN;
+  const int sk = (tiles_m * tiles_n < 256 && (K / 64) % 2 == 0 && K / 2 >= 192) ? 2 : 1;
+  hipLaunchKernelGGL((gemm_prefill2_kernel<2, 2, 1, 1, 64, 3, EpiRaw32>), dim3(tiles_m * tiles_n, sk), dim3(256),
+                     P::kLdsBytes, s, X, h->tok_p, h->zero_bias, B, N, K, (N + 31) / 32, tiles_n,
+                     EpiRaw32{h->r_logits, N, (size_t)B * N});
+  hipLaunchKernelGGL(logits_rows_argmax_kernel, dim3(B), dim3(256), 0, s, h->r_logits, sk, B, N, h->out_bias, logits_out,
+                     h->strip_val, h->strip_idx);
 }
 
 // Optional output head: t = LayerNorm(gelu(head_w x + head_b)) for the B final rows `x`, written to hlast
@@ -489,7 +514,7 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
   }
   const half_t* x = apply_head(h, h->X, B, s);
   { ProfScope prof(h, ERNIE_PROF_LOGITS, s, 2.0 * c.vocab_kept * d, 2.0 * B * c.vocab_kept * d);
-    launch_logits(h, x, B, logits_out, s); }
+    h->cand = launch_logits(h, x, B, logits_out, s); }
   return ERNIE_OK;
 }
 
@@ -570,6 +595,7 @@ int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* w, const E
   h->strip_idx = I32(plan.strip_idx); h->cu = I32(plan.cu); h->lens = I32(plan.lens);
   h->tok_seq = I32(plan.tok_seq); h->tok_pos = I32(plan.tok_pos); h->tok_prev = I32(plan.tok_prev);
   h->finished = I32(plan.finished); h->slot = I32(plan.slot); h->keep = I32(plan.keep);
+  h->r_logits = F32(plan.r_logits);
   h->prefilled = false; h->B = 0; h->max_len = 0; h->steps = 0; h->sum_len = h->sum_len2 = 0.0;
   h->staging = nullptr; h->staging_next = 0;
 
@@ -583,7 +609,7 @@ int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* w, const E
 
   const int d = cfg->d_model, f = cfg->d_ffn, V = cfg->vocab_kept;
   bool copies_ok = true;
-  copies_ok &= hipMemsetAsync(h->zero_bias, 0, (size_t)(3 * cfg->d_model > cfg->d_ffn ? 3 * cfg->d_model : cfg->d_ffn) * 4, s) == hipSuccess;
+  copies_ok &= hipMemsetAsync(h->zero_bias, 0, (size_t)std::max(std::max(3 * d, f), V) * 4, s) == hipSuccess;
   copies_ok &= hipMemcpyAsync(h->tok_rm, w->tok_emb_kept, (size_t)V * d * 2, hipMemcpyDeviceToDevice, s) == hipSuccess;
   copies_ok &= hipMemcpyAsync(h->pos, w->pos_emb, (size_t)cfg->max_pos * d * 2, hipMemcpyDeviceToDevice, s) == hipSuccess;
   copies_ok &= hipMemcpyAsync(a + plan.kept, w->kept_ids, (size_t)V * 4, hipMemcpyDeviceToDevice, s) == hipSuccess;
@@ -679,10 +705,10 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); hipLaunchKernelGGL(gather_last_rows_kernel, dim3(B), dim3(256), 0, s, h->X, h->cu, B, d, h->hlast, hidden_out_dev); }
   const half_t* xhead = apply_head(h, h->hlast, B, s);
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0);
-  launch_logits(h, xhead, B, logits_out_dev, s);
+  h->cand = launch_logits(h, xhead, B, logits_out_dev, s);
   }
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0);
-  hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->plan.strips,
+  hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->cand,
                      tok_out_dev, h->tok_prev, h->lens, 0, S, c.vocab_kept, (const int*)nullptr, -1);
   }
   h->compacted = false;
@@ -714,7 +740,7 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_o
   }
   if (rc != ERNIE_OK) return rc;
   { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
-  hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->plan.strips,
+  hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->cand,
                      tok_out_dev, h->tok_prev, h->lens, 1, c.max_seq, c.vocab_kept,
                      h->eos >= 0 ? h->finished : (const int*)nullptr, h->eos);
   }
@@ -858,6 +884,7 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
 int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!h || !key) return ERNIE_EINVAL;
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
+  if (!strcmp(key, "big_logits_gemm")) { h->big_logits_gemm = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "big_f1_fused")) { h->big_f1_fused = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "ln_rpw")) {
     if (value != 1 && value != 2) return ERNIE_EINVAL;

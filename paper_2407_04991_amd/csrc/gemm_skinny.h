@@ -82,4 +82,41 @@ __global__ __launch_bounds__(NW * 64) void logits_argmax_kernel(const half_t* __
   }
 }
 
+// First argmax stage over whole rows, for projections computed by the MFMA GEMM pipeline as fp32 partial
+// logits [sk][B][N]: one workgroup per sequence adds the partials in index order (+ optional output bias),
+// optionally writes the logits out, and reports the row's best (value, index) as a single "strip"
+// candidate for argmax_final_kernel (strips = 1).  N % 4 == 0 is not required.
+__global__ __launch_bounds__(256) void logits_rows_argmax_kernel(const float* __restrict__ part, int sk, int B, int N,
+                                                                 const float* __restrict__ out_bias,
+                                                                 float* __restrict__ logits_out,
+                                                                 float* __restrict__ cand_val, int* __restrict__ cand_idx) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const float* row = part + (size_t)b * N;
+  const size_t slab = (size_t)B * N;
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int c = tid; c < N; c += 256) {
+    float z = row[c];
+    for (int s = 1; s < sk; ++s) z += row[(size_t)s * slab + c];
+    if (out_bias) z += out_bias[c];
+    if (logits_out) logits_out[(size_t)b * N + c] = z;
+    argmax_merge(bv, bi, z, c);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(bv, o, 64);
+    const int oi = __shfl_xor(bi, o, 64);
+    argmax_merge(bv, bi, ov, oi);
+  }
+  if ((tid & 63) == 0) { sv[tid >> 6] = bv; si[tid >> 6] = bi; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 4; ++w) argmax_merge(bv, bi, sv[w], si[w]);
+    cand_val[b] = bv;
+    cand_idx[b] = bi;
+  }
+}
+
 }  // namespace ernie

@@ -275,6 +275,28 @@ def test_partial_head_parameters_are_rejected(E):
         E.engine_from_workload(wl)
 
 
+@pytest.mark.parametrize("vocab_kept,knobs", [(512, {"big_logits_gemm": 0}), (512, {"big_f1_fused": 0}), (300, {})])
+def test_large_batch_path_alternatives(E, vocab_kept, knobs):
+    """B > 64 with each alternative of the large-batch path switched: projection by the skinny kernel instead of
+    the GEMM pipeline, first FFN GEMM split with a separate GELU kernel, and a kept-row count that is not a
+    multiple of 8 (which the GEMM-pipeline projection cannot take)."""
+    B = 130
+    rng = np.random.default_rng(4242)
+    lengths = [int(x) for x in rng.integers(3, 40, size=B)]
+    n_gen = 4
+    wl = _ragged_workload(lengths, max_pos=64, n_gen=n_gen, vocab_kept=vocab_kept)
+    eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
+    for k, v in knobs.items():
+        eng.tune(k, v)
+    ids, lens = wl.padded(0)
+    rows = [0, 64, B - 1]
+    _say(f"[parity] large-batch alternatives V'={vocab_kept} {knobs}")
+    orc = oracle_generate(wl, 0, rows, n_gen)
+    toks, hid, lg = gpu_generate(eng, ids, lens, n_gen, {r: orc[r]["tokens"] for r in orc})
+    check_rows(orc, toks, hid, lg, f"big-alt-{vocab_kept}")
+    eng.close()
+
+
 def test_decode_tuning_variants_agree(E):
     """Every split-K setting and both decode paths meet the oracle and agree with each other closely."""
     wl = make_workload("tiny_affine")
