@@ -80,60 +80,67 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const half_t* __restr
     }
     __syncthreads();
 
+    // S^T[key][query] for the 64 keys of the block x this wave's 32 queries (two 32-key MFMA tiles), then ONE
+    // online-softmax update for the whole block
+    floatx16 sc[2];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
-      const int key0 = kb0 + kk * 32;
-      if (key0 < L) {                            // uniform: skip fully masked sub-blocks
-        // S^T[key][query] for 32 keys x 32 queries
-        floatx16 s;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[v] = 0.f;
-        const int krow = key0 + (lane & 31);
+      for (int v = 0; v < 16; ++v) sc[kk][v] = 0.f;
+      const int krow = min(kb0 + kk * 32 + (lane & 31), L - 1);      // rows past the end re-read the last key, masked below
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          half8 kf = {0, 0, 0, 0, 0, 0, 0, 0};
-          if (krow < L) kf = *reinterpret_cast<const half8*>(Kb + (size_t)krow * 64 + 16 * c + 8 * hh);
-          s = mfma32(kf, qf[c], s);
-        }
-        float mx = -INFINITY;
+      for (int c = 0; c < 4; ++c) {
+        const half8 kf = *reinterpret_cast<const half8*>(Kb + (size_t)krow * 64 + 16 * c + 8 * hh);
+        sc[kk] = mfma32(kf, qf[c], sc[kk]);
+      }
+    }
+    if (kb0 + kAttnKBlock > L) {                   // only the last block of a sequence has keys to mask (uniform branch)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = key0 + mfma32_row(v, lane);
-          if (key >= L) s[v] = -INFINITY;
-          mx = fmaxf(mx, s[v]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(row_max, mx);            // finite: key 0 is always valid
-        const float alpha = __expf(row_max - m_new);        // exp(-inf) = 0 on the first block
-        float ps = 0.f;
-        half8 pf[2];
+      for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float p = __expf(s[v] - m_new);
-          ps += p;
-          pf[v >> 3][v & 7] = (half_t)p;
-        }
-        ps += __shfl_xor(ps, 32, 64);
-        row_sum = row_sum * alpha + ps;
-        row_max = m_new;
+        for (int v = 0; v < 16; ++v)
+          if (kb0 + kk * 32 + mfma32_row(v, lane) >= L) sc[kk][v] = -INFINITY;
+    }
+    float mx = -INFINITY;
 #pragma unroll
-        for (int m = 0; m < 2; ++m)
+    for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) o[m][v] *= alpha;
-        // O^T[e][query] += V^T[e][keys] * P^T[keys][query]
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc[kk][v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(row_max, mx);              // finite: the block holds at least one valid key
+    if (__any(m_new > row_max)) {                        // the running maximum rarely moves after the first blocks
+      const float alpha = __expf(row_max - m_new);       // exp(-inf) = 0 on the first block
+      row_sum *= alpha;
 #pragma unroll
-        for (int m = 0; m < 2; ++m) {
-          const half_t* vt = sVt + (32 * m + (lane & 31)) * kAttnVtPitch + kk * 32 + 4 * hh;
+      for (int m = 0; m < 2; ++m)
 #pragma unroll
-          for (int c = 0; c < 2; ++c) {
-            const half4 lo = *reinterpret_cast<const half4*>(vt + 16 * c);
-            const half4 hi = *reinterpret_cast<const half4*>(vt + 16 * c + 8);
-            half8 vf;
-            vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
-            vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
-            o[m] = mfma32(vf, pf[c], o[m]);
-          }
-        }
+        for (int v = 0; v < 16; ++v) o[m][v] *= alpha;
+      row_max = m_new;
+    }
+    float ps = 0.f;
+    half8 pf[4];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float p = __expf(sc[kk][v] - row_max);
+        ps += p;
+        pf[2 * kk + (v >> 3)][v & 7] = (half_t)p;
+      }
+    ps += __shfl_xor(ps, 32, 64);
+    row_sum += ps;
+    // O^T[e][query] += V^T[e][keys] * P^T[keys][query]
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+      const half_t* vt = sVt + (32 * m + (lane & 31)) * kAttnVtPitch + 4 * hh;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const half4 lo = *reinterpret_cast<const half4*>(vt + 16 * c);
+        const half4 hi = *reinterpret_cast<const half4*>(vt + 16 * c + 8);
+        half8 vf;
+        vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
+        vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
+        o[m] = mfma32(vf, pf[c], o[m]);
       }
     }
     __syncthreads();
