@@ -67,16 +67,35 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const half_t* __restr
     for (int v = 0; v < 16; ++v) o[m][v] = 0.f;
   float row_max = -INFINITY, row_sum = 0.f;
 
+  // Operands of a key block are fetched one block ahead: V rows (two 16-byte pieces per thread, transposed into
+  // LDS at the top of the block's iteration) and this wave's K fragments.  Rows past the end of the sequence
+  // re-read its last key (always valid memory); they are masked / zeroed where it matters.
+  half8 vreg[2], kf[2][4];
+  auto fetch_block = [&](int kb0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int id = tid + 256 * i;
+      const int key = min(kb0 + (id >> 3), L - 1), ec = id & 7;
+      vreg[i] = *reinterpret_cast<const half8*>(Vb + (size_t)key * 64 + ec * 8);
+    }
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const int krow = min(kb0 + kk * 32 + (lane & 31), L - 1);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) kf[kk][c] = *reinterpret_cast<const half8*>(Kb + (size_t)krow * 64 + 16 * c + 8 * hh);
+    }
+  };
+  fetch_block(0);
+
   for (int kb0 = 0; kb0 < L; kb0 += kAttnKBlock) {
     // stage V^T of this key block: thread handles key = id / 8, 8 head-dim values at (id % 8) * 8
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int id = tid + 256 * i;
       const int key = id >> 3, ec = id & 7;
-      half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (kb0 + key < L) v = *reinterpret_cast<const half8*>(Vb + (size_t)(kb0 + key) * 64 + ec * 8);
+      const bool live = kb0 + key < L;                      // keys past the end contribute V = 0
 #pragma unroll
-      for (int j = 0; j < 8; ++j) sVt[(ec * 8 + j) * kAttnVtPitch + key] = v[j];
+      for (int j = 0; j < 8; ++j) sVt[(ec * 8 + j) * kAttnVtPitch + key] = live ? vreg[i][j] : (half_t)0.f;
     }
     __syncthreads();
 
@@ -87,13 +106,10 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const half_t* __restr
     for (int kk = 0; kk < 2; ++kk) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) sc[kk][v] = 0.f;
-      const int krow = min(kb0 + kk * 32 + (lane & 31), L - 1);      // rows past the end re-read the last key, masked below
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const half8 kf = *reinterpret_cast<const half8*>(Kb + (size_t)krow * 64 + 16 * c + 8 * hh);
-        sc[kk] = mfma32(kf, qf[c], sc[kk]);
-      }
+      for (int c = 0; c < 4; ++c) sc[kk] = mfma32(kf[kk][c], qf[c], sc[kk]);
     }
+    if (kb0 + kAttnKBlock < L) fetch_block(kb0 + kAttnKBlock);      // next block's loads fly during softmax and P V
     if (kb0 + kAttnKBlock > L) {                   // only the last block of a sequence has keys to mask (uniform branch)
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk)
