@@ -263,6 +263,8 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
  *                       (default 1; needs vocab_kept % 8 == 0), or the table-streaming kernel with per-strip argmax
  *   "big_f1_fused" 0/1  large-batch path: first FFN GEMM unsplit with bias + GELU in its epilogue (default 1), or
  *                       split over the contraction with a separate GELU row kernel
+ *   "dec_nw16" 0..3     decode GEMMs on fp16 activations with 16 instead of 8 waves per workgroup: 0 = never,
+ *                       1 = second FFN GEMM, 2 = also the attention-output GEMM (default), 3 = also the projection
  *   "attn_nt" 0/1       decode attention reads the cache with the non-temporal (streaming) hint, so that the
  *                       once-per-step cache stream does not displace the weights from the caches (default 1)
  * Splits are 1, 2 or 4.  Results are deterministic for any fixed setting.  Returns ERNIE_EINVAL for an

@@ -141,7 +141,7 @@ struct ErnieHandle {
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
   half_t *type_emb = nullptr, *head_w = nullptr;                      // optional variants, null when off
   float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
-  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 1, big_f1_fused = 1, big_logits_gemm = 1;
+  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 1, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2;
   int cand = 0;                  // argmax candidates per row left by the last projection   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   float* r_logits = nullptr;     // [2][max_batch][V'] fp32, large-batch projection only
@@ -277,13 +277,17 @@ int configure_kernels() {
 #undef GEMM_LDS
   const size_t big = (size_t)4 * 8 * 16 * 64 * 4;   // MT = 8, NW = 4
   rc |= allow_lds(logits_argmax_kernel<8, 4>, big);
-#define LN_LDS1(EPI, SK, RPW) rc |= allow_lds(gemm_dec_ln_kernel<8, EPI, 2, SK, RPW, 1>, kMaxLds); rc |= allow_lds(gemm_dec_ln_kernel<8, EPI, 2, SK, RPW, 2>, kMaxLds); rc |= allow_lds(gemm_dec_ln_kernel<8, EPI, 2, SK, RPW, 4>, kMaxLds)
+#define LN_LDS2(NW, EPI, SK, RPW) rc |= allow_lds(gemm_dec_ln_kernel<NW, EPI, 2, SK, RPW, 1>, kMaxLds); rc |= allow_lds(gemm_dec_ln_kernel<NW, EPI, 2, SK, RPW, 2>, kMaxLds); rc |= allow_lds(gemm_dec_ln_kernel<NW, EPI, 2, SK, RPW, 4>, kMaxLds)
+#define LN_LDS1(EPI, SK, RPW) LN_LDS2(8, EPI, SK, RPW)
 #define LN_LDS(EPI, SK) LN_LDS1(EPI, SK, 1); LN_LDS1(EPI, SK, 2)
   LN_LDS(EPI_RAW, 0);
   LN_LDS(EPI_RAW, 1); LN_LDS(EPI_RAW, 2); LN_LDS(EPI_RAW, 4); LN_LDS(EPI_GELU16, 1); LN_LDS(EPI_GELU16, 2); LN_LDS(EPI_GELU16, 4);
 #undef LN_LDS
 #undef LN_LDS1
+#undef LN_LDS2
   rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_RAW>, kMaxLds);
+  rc |= allow_lds(gemm_dec_kernel<1, 16, EPI_RAW>, kMaxLds);
+  rc |= allow_lds(gemm_dec_kernel<1, 16, EPI_ARGMAX>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<2, 8, EPI_RAW>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_ARGMAX>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<2, 8, EPI_ARGMAX>, kMaxLds);
@@ -322,24 +326,23 @@ int launch_gemm_dec(ErnieHandle* h, DecGemmArgs a, int sk, hipStream_t s) {
     if (lds > kMaxLds) return ERNIE_EINVAL;                                                     \
     hipLaunchKernelGGL((gemm_dec_kernel<MTV, NWV, EPI>), grid, dim3(NWV * 64), lds, s, a);      \
   } while (0)
-  if (MT == 1) DEC_LAUNCH(1, 8);
+  const int tiles_wg = a.K / 16 / sk;
+  const bool nw16 = MT == 1 && tiles_wg >= 16 &&
+                    (h->dec_nw16 >= 3 || (h->dec_nw16 == 2 && EPI == EPI_RAW) || (h->dec_nw16 == 1 && EPI == EPI_RAW && a.K >= 2048));
+  if (nw16) DEC_LAUNCH(1, 16);
+  else if (MT == 1) DEC_LAUNCH(1, 8);
   else if (MT == 2) DEC_LAUNCH(2, 8);
   else return ERNIE_EINVAL;
 #undef DEC_LAUNCH
   return ERNIE_OK;
 }
 
-template <int EPI>
-int launch_gemm_dec_ln(ErnieHandle* h, DecGemmArgs a, hipStream_t s) {
-  constexpr int NW = 8;
-  ProfScope prof(h, ERNIE_PROF_GEMM_DEC_LN, s, 2.0 * a.N * a.K, 2.0 * a.B * a.N * a.K);
-  if (a.K > 1024) return ERNIE_EINVAL;                 // the LayerNorm prologue holds rows of <= 1024 features
-  // strips per workgroup (0 = by batch size: two strips halve the redundant prologue traffic and measured
-  // 8 % faster at B = 32, 10 % slower at B = 64), rows per wave
-  const int ns = h->ln_ns ? h->ln_ns : (a.B <= 32 ? 2 : 1), rpw = h->ln_rpw;
+template <int EPI, int NW>
+int launch_gemm_dec_ln_nw(ErnieHandle* h, DecGemmArgs a, int ns, int rpw, hipStream_t s) {
   const int R = NW * rpw;
   const size_t a_bytes = (size_t)R * (a.K + 8) * 2, r_bytes = (size_t)NW * ns * (R / 2) * 64 * 4;
   const size_t lds = a_bytes > r_bytes ? a_bytes : r_bytes;
+  if (lds > kMaxLds) return ERNIE_EINVAL;
   const int strips = (a.N + 31) / 32;
   const dim3 grid(((strips + ns - 1) / ns) * ((a.B + R - 1) / R)), block(NW * 64);
 #define LN_LAUNCH(SK, RPW, NS) hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2, SK, RPW, NS>), grid, block, lds, s, a)
@@ -356,6 +359,17 @@ int launch_gemm_dec_ln(ErnieHandle* h, DecGemmArgs a, hipStream_t s) {
 #undef LN_BY_NS
 #undef LN_LAUNCH
   return ERNIE_OK;
+}
+
+template <int EPI>
+int launch_gemm_dec_ln(ErnieHandle* h, DecGemmArgs a, hipStream_t s) {
+  ProfScope prof(h, ERNIE_PROF_GEMM_DEC_LN, s, 2.0 * a.N * a.K, 2.0 * a.B * a.N * a.K);
+  if (a.K > 1024) return ERNIE_EINVAL;                 // the LayerNorm prologue holds rows of <= 1024 features
+  // strips per workgroup (0 = by batch size: two strips halve the redundant prologue traffic and measured
+  // 8 % faster at B = 32, 10 % slower at B = 64), rows per wave
+  const int ns = h->ln_ns ? h->ln_ns : (a.B <= 32 ? 2 : 1);
+  const int rpw = h->ln_rpw;
+  return launch_gemm_dec_ln_nw<EPI, 8>(h, a, ns, rpw, s);   // sixteen waves measured 6-30 % slower here
 }
 
 // Small batches: every GEMM input fits in LDS, row-wise work lives in consumer prologues (5 launches per layer).
@@ -884,6 +898,7 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
 int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!h || !key) return ERNIE_EINVAL;
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
+  if (!strcmp(key, "dec_nw16")) { h->dec_nw16 = value; return ERNIE_OK; }
   if (!strcmp(key, "big_logits_gemm")) { h->big_logits_gemm = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "big_f1_fused")) { h->big_f1_fused = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "ln_rpw")) {
