@@ -288,6 +288,8 @@ int configure_kernels() {
   rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_RAW>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<1, 16, EPI_RAW>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<1, 16, EPI_ARGMAX>, kMaxLds);
+  rc |= allow_lds(gemm_dec_kernel<2, 16, EPI_RAW>, kMaxLds);
+  rc |= allow_lds(gemm_dec_kernel<2, 16, EPI_ARGMAX>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<2, 8, EPI_RAW>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_ARGMAX>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<2, 8, EPI_ARGMAX>, kMaxLds);
@@ -327,9 +329,10 @@ int launch_gemm_dec(ErnieHandle* h, DecGemmArgs a, int sk, hipStream_t s) {
     hipLaunchKernelGGL((gemm_dec_kernel<MTV, NWV, EPI>), grid, dim3(NWV * 64), lds, s, a);      \
   } while (0)
   const int tiles_wg = a.K / 16 / sk;
-  const bool nw16 = MT == 1 && tiles_wg >= 16 &&
+  const bool nw16 = tiles_wg >= 16 &&
                     (h->dec_nw16 >= 3 || (h->dec_nw16 == 2 && EPI == EPI_RAW) || (h->dec_nw16 == 1 && EPI == EPI_RAW && a.K >= 2048));
-  if (nw16) DEC_LAUNCH(1, 16);
+  if (nw16 && MT == 1) DEC_LAUNCH(1, 16);
+  else if (nw16 && MT == 2) DEC_LAUNCH(2, 16);
   else if (MT == 1) DEC_LAUNCH(1, 8);
   else if (MT == 2) DEC_LAUNCH(2, 8);
   else return ERNIE_EINVAL;
