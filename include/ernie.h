@@ -258,7 +258,7 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
  *                       in flight, 2 = 8 waves x 3, 3 = 8 waves x 4, 4 = 4 waves x 2, 5 = 2 waves x 2 (a batch of
  *                       waves x groups x 8 keys per memory round trip)
  *   "ln_ns" 0/1/2/4     32-column strips per workgroup of the decode GEMMs with the LayerNorm prologue (0 = chosen
- *                       from the batch size); "ln_rpw" 1/2 rows normalised per wave in that prologue
+ *                       automatically); "ln_rpw" 0/1/2 rows normalised per wave in that prologue (0 = chosen from the batch size)
  *   "big_logits_gemm" 0/1  large-batch path: output projection on the MFMA GEMM pipeline followed by a row argmax
  *                       (default 1; needs vocab_kept % 8 == 0), or the table-streaming kernel with per-strip argmax
  *   "big_f1_fused" 0/1  large-batch path: first FFN GEMM unsplit with bias + GELU in its epilogue (default 1), or

@@ -141,7 +141,7 @@ struct ErnieHandle {
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
   half_t *type_emb = nullptr, *head_w = nullptr;                      // optional variants, null when off
   float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
-  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 1, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2;
+  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2;
   int cand = 0;                  // argmax candidates per row left by the last projection   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   float* r_logits = nullptr;     // [2][max_batch][V'] fp32, large-batch projection only
@@ -368,10 +368,12 @@ template <int EPI>
 int launch_gemm_dec_ln(ErnieHandle* h, DecGemmArgs a, hipStream_t s) {
   ProfScope prof(h, ERNIE_PROF_GEMM_DEC_LN, s, 2.0 * a.N * a.K, 2.0 * a.B * a.N * a.K);
   if (a.K > 1024) return ERNIE_EINVAL;                 // the LayerNorm prologue holds rows of <= 1024 features
-  // strips per workgroup (0 = by batch size: two strips halve the redundant prologue traffic and measured
-  // 8 % faster at B = 32, 10 % slower at B = 64), rows per wave
-  const int ns = h->ln_ns ? h->ln_ns : (a.B <= 32 ? 2 : 1);
-  const int rpw = h->ln_rpw;
+  // Two strips per workgroup halve the redundant prologue traffic; the batch is cut into four row groups
+  // (8 rows per group up to B = 32, one row per wave; 16 rows per group above, two rows per wave).  Measured:
+  // 8 % over one strip at B = 32, 6 % over one strip x 8-row groups at B = 64; every other combination of
+  // 1/2/4 strips and 8/16/32 rows is slower at both sizes.  The knobs override the choice (0 = automatic).
+  const int ns = h->ln_ns ? h->ln_ns : 2;
+  const int rpw = h->ln_rpw ? h->ln_rpw : (a.B > 32 ? 2 : 1);
   return launch_gemm_dec_ln_nw<EPI, 8>(h, a, ns, rpw, s);   // sixteen waves measured 6-30 % slower here
 }
 
@@ -905,7 +907,7 @@ int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!strcmp(key, "big_logits_gemm")) { h->big_logits_gemm = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "big_f1_fused")) { h->big_f1_fused = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "ln_rpw")) {
-    if (value != 1 && value != 2) return ERNIE_EINVAL;
+    if (value != 0 && value != 1 && value != 2) return ERNIE_EINVAL;
     h->ln_rpw = value;
     return ERNIE_OK;
   }
