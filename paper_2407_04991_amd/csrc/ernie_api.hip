@@ -250,8 +250,12 @@ void launch_logits_big(ErnieHandle* h, const half_t* X, int B, float* logits_out
 
 // Leaves per-strip argmax candidates in strip_val / strip_idx; returns how many candidates each row has.
 int launch_logits(ErnieHandle* h, const half_t* X, int B, float* logits_out, hipStream_t s) {
-  // (the GEMM epilogue stores runs of 8 columns, so the row length must be a multiple of 8)
-  if (B > 64 && h->big_logits_gemm && h->cfg.vocab_kept % 8 == 0) { launch_logits_big(h, X, B, logits_out, s); return 1; }
+  // (the GEMM epilogue stores runs of 8 columns, so the row length must be a multiple of 8; the row kernel
+  // writes the caller's logits in 16-byte pieces)
+  if (B > 64 && h->big_logits_gemm && h->cfg.vocab_kept % 8 == 0 && (uintptr_t)logits_out % 16 == 0) {
+    launch_logits_big(h, X, B, logits_out, s);
+    return 1;
+  }
   if (B <= 32) launch_logits_t<1, 4>(h, X, B, logits_out, s);
   else if (B <= 64) launch_logits_t<2, 4>(h, X, B, logits_out, s);
   else if (B <= 128) launch_logits_t<4, 4>(h, X, B, logits_out, s);

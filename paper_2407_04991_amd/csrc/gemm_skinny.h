@@ -85,7 +85,7 @@ __global__ __launch_bounds__(NW * 64) void logits_argmax_kernel(const half_t* __
 // First argmax stage over whole rows, for projections computed by the MFMA GEMM pipeline as fp32 partial
 // logits [sk][B][N]: one workgroup per sequence adds the partials in index order (+ optional output bias),
 // optionally writes the logits out, and reports the row's best (value, index) as a single "strip"
-// candidate for argmax_final_kernel (strips = 1).  N % 4 == 0 is not required.
+// candidate for argmax_final_kernel (strips = 1).  N must be a multiple of 4 and the buffers 16-byte aligned.
 __global__ __launch_bounds__(256) void logits_rows_argmax_kernel(const float* __restrict__ part, int sk, int B, int N,
                                                                  const float* __restrict__ out_bias,
                                                                  float* __restrict__ logits_out,
@@ -97,12 +97,20 @@ __global__ __launch_bounds__(256) void logits_rows_argmax_kernel(const float* __
   const size_t slab = (size_t)B * N;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
-  for (int c = tid; c < N; c += 256) {
-    float z = row[c];
-    for (int s = 1; s < sk; ++s) z += row[(size_t)s * slab + c];
-    if (out_bias) z += out_bias[c];
-    if (logits_out) logits_out[(size_t)b * N + c] = z;
-    argmax_merge(bv, bi, z, c);
+  // N is a multiple of 8 on this path (the GEMM epilogue stores runs of 8 columns): 16-byte pieces
+  for (int c = tid * 4; c < N; c += 1024) {
+    float4 z = *reinterpret_cast<const float4*>(row + c);
+    for (int s = 1; s < sk; ++s) {
+      const float4 y = *reinterpret_cast<const float4*>(row + (size_t)s * slab + c);
+      z.x += y.x; z.y += y.y; z.z += y.z; z.w += y.w;
+    }
+    if (out_bias) {
+      const float4 y = *reinterpret_cast<const float4*>(out_bias + c);
+      z.x += y.x; z.y += y.y; z.z += y.z; z.w += y.w;
+    }
+    if (logits_out) *reinterpret_cast<float4*>(logits_out + (size_t)b * N + c) = z;
+    argmax_merge(bv, bi, z.x, c); argmax_merge(bv, bi, z.y, c + 1);
+    argmax_merge(bv, bi, z.z, c + 2); argmax_merge(bv, bi, z.w, c + 3);
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
