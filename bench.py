@@ -26,8 +26,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # 2.0, WRITE_SIZE 1.0); summary and commands in profiles/base_b32_hbm_traffic_pmc.txt.  Counters cannot be
 # read from inside the process, so the figures are carried here for the workload they were measured on.
 MEASURED_HBM_BYTES_PER_LAUNCH = {
-    "base": {"gemm_dec": 4.287e6, "gemm_dec_ln": 7.452e6, "attn_dec": 16.294e6, "logits": 29.289e6,
-             "gemm_prefill": 62.31e6, "attn_prefill": 25.281e6},
+    "base": {"gemm_dec": 4.287e+06, "gemm_dec_ln": 7.445e+06, "attn_dec": 1.548e+07, "logits": 2.929e+07, "gemm_prefill": 6.255e+07, "attn_prefill": 2.528e+07},
 }
 
 
