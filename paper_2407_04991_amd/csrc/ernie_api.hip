@@ -279,6 +279,7 @@ int configure_kernels() {
   rc |= allow_lds(gemm_prefill2_kernel<__VA_ARGS__, EpiRaw32>, GemmPipe<__VA_ARGS__>::kLdsBytes)
   GEMM_LDS(4, 4, 2, 2, 32, 3); GEMM_LDS(2, 2, 2, 2, 32, 3); GEMM_LDS(2, 2, 1, 1, 64, 3);
 #undef GEMM_LDS
+  rc |= allow_lds(gemm_prefill2_kernel<2, 2, 1, 1, 64, 3, EpiGeluFast>, GemmPipe<2, 2, 1, 1, 64, 3>::kLdsBytes);
   const size_t big = (size_t)4 * 8 * 16 * 64 * 4;   // MT = 8, NW = 4
   rc |= allow_lds(logits_argmax_kernel<8, 4>, big);
 #define LN_LDS2(NW, EPI, SK, RPW) rc |= allow_lds(gemm_dec_ln_kernel<NW, EPI, 2, SK, RPW, 1>, kMaxLds); rc |= allow_lds(gemm_dec_ln_kernel<NW, EPI, 2, SK, RPW, 2>, kMaxLds); rc |= allow_lds(gemm_dec_ln_kernel<NW, EPI, 2, SK, RPW, 4>, kMaxLds)
@@ -521,7 +522,7 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
       // FFN1 keeps its contraction whole: bias + GELU in the GEMM epilogue, no partial buffers and one launch
       // less (the wide N gives enough 64 x 64 tiles; the unsplit GEMM costs 0.3-1.6 us more, a launch 5-6 us)
       ProfScope prof(h, ERNIE_PROF_GEMM_DEC, s, 2.0 * f * d, 2.0 * B * f * d);
-      launch_gemm_prefill_t<2, 2, 1, 1, 64, 3>(h->X1, L.w1, L.b1, B, f, d, EpiGelu{h->G, f}, s);
+      launch_gemm_prefill_t<2, 2, 1, 1, 64, 3>(h->X1, L.w1, L.b1, B, f, d, EpiGeluFast{h->G, f}, s);
     } else {
       launch_gemm_splitk(h, h->X1, L.w1, B, f, d, h->r_f1, sk_1, s);
       ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);

@@ -54,17 +54,20 @@ struct EpiResidual {
   }
 };
 
-// FFN1: G = gelu(acc + bias), fp16.
-struct EpiGelu {
+// FFN1: G = gelu(acc + bias), fp16.  FAST picks the branch-free erf (decode step) over the library one (prefill).
+template <bool FAST>
+struct EpiGeluT {
   half_t* g;
   int N;
   __device__ __forceinline__ void store8(int row, int col, const float (&v)[8]) const {
     half8 out;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) out[j] = (half_t)gelu_erf(v[j]);
+    for (int j = 0; j < 8; ++j) out[j] = (half_t)(FAST ? gelu_erf_fast(v[j]) : gelu_erf(v[j]));
     *reinterpret_cast<half8*>(g + (size_t)row * N + col) = out;
   }
 };
+using EpiGelu = EpiGeluT<false>;
+using EpiGeluFast = EpiGeluT<true>;
 
 // Raw fp32 output [gridDim.y][M, N]: one partial buffer per split of the contraction (decode step at
 // large batch: the consumer kernels add the partials, bias and residual).
