@@ -17,19 +17,43 @@ namespace ernie {
 
 constexpr int kAttnQTile = 128;            // queries per workgroup (32 per wave)
 constexpr int kAttnKBlock = 64;            // keys staged per iteration
-constexpr int kAttnVtPitch = kAttnKBlock + 4;   // halves; 136-byte pitch spreads 8-byte reads over all banks
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr int kAttnTile = kAttnKBlock * 128;      // bytes of one staged tile: 64 cache rows (keys) x 128 bytes (head dim)
+constexpr int kAttnLdsBytes = 4 * kAttnTile;      // K and V tiles, double-buffered
 
-// Scores are produced transposed (S^T = K Q^T) so that every lane owns ONE
-// query column: softmax statistics are per-lane plus one exchange with lane^32.
-// The probabilities, still in registers, are directly the B operand of
-// O^T = V^T P^T provided V^T is read with the matching key permutation
-// (slot (half, j) of k-step c  <->  key 16c + 8(j/4) + 4*half + j%4).
-__global__ __launch_bounds__(256) void attn_prefill_kernel(const half_t* __restrict__ Q,      // [H][T][64]
-                                                           const half_t* __restrict__ Kc,     // layer K cache
-                                                           const half_t* __restrict__ Vc,     // layer V cache
-                                                           const int* __restrict__ cu, int T, int H, int S, int d,
-                                                           half_t* __restrict__ O) {           // [T, d]
-  __shared__ __align__(16) half_t sVt[64 * kAttnVtPitch];
+typedef __attribute__((address_space(1))) const void attn_global_cptr_t;
+typedef __attribute__((address_space(3))) void attn_lds_ptr_t;
+typedef short attn_short4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) attn_short4 attn_lds_short4_t;
+
+// The K and V rows of a key block are copied once per workgroup, global -> LDS directly, 64 rows x 128 bytes
+// each, one block ahead of the arithmetic.  16-byte chunk c of row r sits in slot
+//   K tile:  c ^ ((r / 2) % 8)      the 16 lanes served together by a 16-byte read (16 rows, one logical chunk)
+//                                   touch 64 distinct banks
+//   V tile:  c ^ (4 * ((r / 2) % 2))  the 32 lanes served together by an 8-byte transposing read (4 rows x 64
+//                                   bytes) touch 64 distinct banks
+//
+// Scores are produced transposed (S^T = K Q^T) so that every lane owns ONE query column: softmax statistics
+// are per-lane plus one exchange with lane^32, and the probabilities, still in registers, are directly the
+// B operand of O^T = V^T P^T: accumulator registers 8 c .. 8 c + 7 of lane half hh hold keys
+// 16 c + 4 hh + {0..3} and 16 c + 8 + 4 hh + {0..3} of a 32-key tile.  The matching A operand (8 keys of one
+// head-dim index per lane) comes out of the row-major V tile through the LDS transposing read
+// (ds_read_b64_tr_b16): in every group of 16 lanes, lane s supplies the address of 4 consecutive 16-bit
+// elements and lane i receives element i % 4 of the chunks of lanes i / 4, i / 4 + 4, i / 4 + 8, i / 4 + 12.
+// With lane s pointing at key (s / 4), head-dim elements 4 (s % 4) .. + 3 of a 4-key x 16-element patch, lane i
+// receives the patch's 4 keys at element i: two such reads make one fragment.
+// (min 2 waves per SIMD: with a register budget of 256 the compiler keeps the MFMA accumulators in
+// ordinary registers instead of shuttling them through the accumulation file around every block.)
+__global__ __launch_bounds__(256, 2) void attn_prefill_kernel(const half_t* __restrict__ Q,      // [H][T][64]
+                                                              const half_t* __restrict__ Kc,     // layer K cache
+                                                              const half_t* __restrict__ Vc,     // layer V cache
+                                                              const int* __restrict__ cu, int T, int H, int S, int d,
+                                                              half_t* __restrict__ O) {           // [T, d]
+  // Dynamic LDS (kAttnLdsBytes): for a statically declared array the compiler makes every LDS read wait for all
+  // outstanding direct-to-LDS copies, the ones just issued for the other buffer included.
+  extern __shared__ __align__(16) unsigned char smem_attn[];
+  unsigned char (*sK)[kAttnTile] = reinterpret_cast<unsigned char (*)[kAttnTile]>(smem_attn);
+  unsigned char (*sV)[kAttnTile] = reinterpret_cast<unsigned char (*)[kAttnTile]>(smem_attn + 2 * kAttnTile);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
@@ -60,44 +84,53 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const half_t* __restr
   const half_t* Kb = Kc + ((size_t)b * H + h) * S * 64;
   const half_t* Vb = Vc + ((size_t)b * H + h) * S * 64;
 
+  // copies: a wave instruction moves 8 whole rows (lane -> row lane / 8, slot lane % 8); every thread issues two
+  // per tile.  Rows past the end of the sequence re-read its last key (valid memory): their scores are masked,
+  // so their (finite) values only ever meet a zero probability.
+  int st_row[2], st_k[2], st_v[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int id = tid + 256 * i;
+    st_row[i] = id >> 3;
+    st_k[i] = ((id & 7) ^ ((st_row[i] >> 1) & 7)) * 8;            // halves: the global chunk that lands in slot id % 8
+    st_v[i] = ((id & 7) ^ (((st_row[i] >> 1) & 1) << 2)) * 8;
+  }
+  auto fetch_block = [&](int kb0, int buf) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const size_t key = (size_t)min(kb0 + st_row[i], L - 1) * 64;
+      const int dst = (wave * 8 + 32 * i) * 128;
+      __builtin_amdgcn_global_load_lds((attn_global_cptr_t*)(Kb + key + st_k[i]), (attn_lds_ptr_t*)(sK[buf] + dst), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((attn_global_cptr_t*)(Vb + key + st_v[i]), (attn_lds_ptr_t*)(sV[buf] + dst), 16, 0, 0);
+    }
+  };
+  fetch_block(0, 0);
+
+  // K fragment reads: tile row 32 kk + lane % 32, logical chunk 2 c + hh
+  const int r = lane & 31;
+  int k_off[2], k_swz[2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x) { k_off[x] = (32 * x + r) * 128; k_swz[x] = ((32 * x + r) >> 1) & 7; }
+  // V transposing reads: as a source, this lane points at key 4 hh + (lane % 16) / 4 of an 8-key group and at
+  // head-dim elements 16 ((lane / 16) % 2) + 4 (lane % 4) .. + 3 of the 32-element tile half m
+  const int l16 = lane & 15;
+  const int v_row = 4 * hh + (l16 >> 2);                               // + 16 c + 8 t
+  const int v_chunk = 2 * ((lane >> 4) & 1) + ((l16 >> 1) & 1);        // + 4 m, then ^ 4 * ((row / 2) % 2)
+  const int v_base = v_row * 128 + 8 * (l16 & 1);
+  const int v_flip = ((v_row >> 1) & 1) << 2;
+
   floatx16 o[2];
 #pragma unroll
   for (int m = 0; m < 2; ++m)
 #pragma unroll
     for (int v = 0; v < 16; ++v) o[m][v] = 0.f;
-  float row_max = -INFINITY, row_sum = 0.f;
+  float row_max = -INFINITY, row_sum = 0.f;     // row_max is kept pre-multiplied by log2(e)
 
-  // Operands of a key block are fetched one block ahead: V rows (two 16-byte pieces per thread, transposed into
-  // LDS at the top of the block's iteration) and this wave's K fragments.  Rows past the end of the sequence
-  // re-read its last key (always valid memory); they are masked / zeroed where it matters.
-  half8 vreg[2], kf[2][4];
-  auto fetch_block = [&](int kb0) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int id = tid + 256 * i;
-      const int key = min(kb0 + (id >> 3), L - 1), ec = id & 7;
-      vreg[i] = *reinterpret_cast<const half8*>(Vb + (size_t)key * 64 + ec * 8);
-    }
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-      const int krow = min(kb0 + kk * 32 + (lane & 31), L - 1);
-#pragma unroll
-      for (int c = 0; c < 4; ++c) kf[kk][c] = *reinterpret_cast<const half8*>(Kb + (size_t)krow * 64 + 16 * c + 8 * hh);
-    }
-  };
-  fetch_block(0);
-
-  for (int kb0 = 0; kb0 < L; kb0 += kAttnKBlock) {
-    // stage V^T of this key block: thread handles key = id / 8, 8 head-dim values at (id % 8) * 8
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int id = tid + 256 * i;
-      const int key = id >> 3, ec = id & 7;
-      const bool live = kb0 + key < L;                      // keys past the end contribute V = 0
-#pragma unroll
-      for (int j = 0; j < 8; ++j) sVt[(ec * 8 + j) * kAttnVtPitch + key] = live ? vreg[i][j] : (half_t)0.f;
-    }
-    __syncthreads();
+  int buf = 0;
+  for (int kb0 = 0; kb0 < L; kb0 += kAttnKBlock, buf ^= 1) {
+    __syncthreads();            // waits for this wave's copies of the block, then for everybody's
+    // the other buffer pair was last read before that barrier: refill it during this block's arithmetic
+    if (kb0 + kAttnKBlock < L) fetch_block(kb0 + kAttnKBlock, buf ^ 1);
 
     // S^T[key][query] for the 64 keys of the block x this wave's 32 queries (two 32-key MFMA tiles), then ONE
     // online-softmax update for the whole block
@@ -107,9 +140,11 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const half_t* __restr
 #pragma unroll
       for (int v = 0; v < 16; ++v) sc[kk][v] = 0.f;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) sc[kk] = mfma32(kf[kk][c], qf[c], sc[kk]);
+      for (int c = 0; c < 4; ++c) {
+        const half8 kf = *reinterpret_cast<const half8*>(sK[buf] + k_off[kk] + (((2 * c + hh) ^ k_swz[kk]) * 16));
+        sc[kk] = mfma32(kf, qf[c], sc[kk]);
+      }
     }
-    if (kb0 + kAttnKBlock < L) fetch_block(kb0 + kAttnKBlock);      // next block's loads fly during softmax and P V
     if (kb0 + kAttnKBlock > L) {                   // only the last block of a sequence has keys to mask (uniform branch)
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk)
@@ -123,9 +158,10 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const half_t* __restr
 #pragma unroll
       for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc[kk][v]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(row_max, mx);              // finite: the block holds at least one valid key
+    // exp(s - max) = exp2(s * log2(e) - max2): one multiply-add and one exponential per score
+    const float m_new = fmaxf(row_max, mx * kLog2e);     // finite: the block holds at least one valid key
     if (__any(m_new > row_max)) {                        // the running maximum rarely moves after the first blocks
-      const float alpha = __expf(row_max - m_new);       // exp(-inf) = 0 on the first block
+      const float alpha = exp2f(row_max - m_new);        // exp2(-inf) = 0 on the first block
       row_sum *= alpha;
 #pragma unroll
       for (int m = 0; m < 2; ++m)
@@ -139,27 +175,25 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const half_t* __restr
     for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const float p = __expf(sc[kk][v] - row_max);
+        const float p = __builtin_amdgcn_exp2f(fmaf(sc[kk][v], kLog2e, -row_max));
         ps += p;
         pf[2 * kk + (v >> 3)][v & 7] = (half_t)p;
       }
     ps += __shfl_xor(ps, 32, 64);
     row_sum += ps;
-    // O^T[e][query] += V^T[e][keys] * P^T[keys][query]
+    // O^T[e][query] += V^T[e][keys] * P^T[keys][query]; MFMA step c covers keys 16 c .. 16 c + 15 of the block
 #pragma unroll
-    for (int m = 0; m < 2; ++m) {
-      const half_t* vt = sVt + (32 * m + (lane & 31)) * kAttnVtPitch + 4 * hh;
+    for (int m = 0; m < 2; ++m)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const half4 lo = *reinterpret_cast<const half4*>(vt + 16 * c);
-        const half4 hi = *reinterpret_cast<const half4*>(vt + 16 * c + 8);
-        half8 vf;
-        vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
-        vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
+        half4 part[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+          part[t] = __builtin_bit_cast(half4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((attn_lds_short4_t*)(
+              sV[buf] + v_base + (16 * c + 8 * t) * 128 + (((4 * m + v_chunk) ^ v_flip) * 16))));
+        const half8 vf = {part[0][0], part[0][1], part[0][2], part[0][3], part[1][0], part[1][1], part[1][2], part[1][3]};
         o[m] = mfma32(vf, pf[c], o[m]);
       }
-    }
-    __syncthreads();
   }
 
   if (q_ok) {

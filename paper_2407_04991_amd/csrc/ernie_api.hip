@@ -715,7 +715,7 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
     launch_gemm_prefill(h, h->X, L.wqkv, L.bqkv, T, 3 * d, d, eq, s);
     {
       ProfScope prof(h, ERNIE_PROF_ATTN_PREFILL, s, 0.0, 4.0 * sum_len2 * d);
-      hipLaunchKernelGGL(attn_prefill_kernel, dim3(q_tiles, H, B), dim3(256), 0, s, h->Q, kcache(h, l), vcache(h, l),
+      hipLaunchKernelGGL(attn_prefill_kernel, dim3(q_tiles, H, B), dim3(256), kAttnLdsBytes, s, h->Q, kcache(h, l), vcache(h, l),
                          h->cu, T, H, S, d, h->O);
     }
     launch_gemm_prefill(h, h->O, L.wo, L.bo, T, d, d, EpiResidual{h->X, h->Y, d}, s);
