@@ -86,4 +86,51 @@ __device__ __forceinline__ int xcd_contiguous_id(int id, int total) {
   return x * q + min(x, r) + (id >> 3);
 }
 
+// Warm-up of weights that a LATER kernel of the decode step will read.  The decode kernels are short and
+// leave most compute units idle; a few extra workgroups appended to a launch pull the packed weight matrix
+// of the GEMM after next into the L2 of the XCD whose workgroups will read it (workgroup ids congruent mod 8
+// run on one XCD), so that the consumer's single weight round trip ends in that L2 instead of in HBM.  The
+// loaded values are discarded; a wrong guess of the mapping costs time, never correctness.
+struct DecPrefetch {
+  const unsigned char* ptr;   // packed weight matrix (fragment-major strips); null = nothing to do
+  unsigned strip_bytes;       // bytes of one 32-column strip (K * 64), a multiple of 16
+  int n_strips;
+  int mode;                   // 1: strip s is read on XCD s % 8 (2-D grid of strips x splits, strips % 8 == 0)
+                              // 2: the consumer orders its (strip group, row group) ids XCD-contiguously
+  int cons_grid, cons_zg, cons_ns;   // mode 2: consumer's workgroup count, row groups per strip group, strips per group
+  int count;                  // prefetching workgroups (a multiple of 8), ids 0 .. count - 1, id % 8 = its XCD
+};
+
+__device__ __forceinline__ void dec_prefetch_run(const DecPrefetch& f, int idx, int tid, int nthreads) {
+  if (!f.ptr) return;
+  const int x = idx & 7, j = idx >> 3, per = f.count >> 3;
+  int s_lo, s_n, s_stride;
+  if (f.mode == 1) {
+    s_lo = x; s_stride = 8; s_n = (f.n_strips - x + 7) >> 3;
+  } else {
+    const int q = f.cons_grid >> 3, r = f.cons_grid & 7;
+    const int lo = x * q + min(x, r), cnt = q + (x < r ? 1 : 0);
+    if (cnt <= 0) return;
+    s_lo = (lo / f.cons_zg) * f.cons_ns;
+    const int s_hi = min(((lo + cnt - 1) / f.cons_zg + 1) * f.cons_ns, f.n_strips);
+    s_stride = 1; s_n = s_hi - s_lo;
+  }
+  if (s_n <= 0 || per <= 0) return;
+  const unsigned upb = f.strip_bytes >> 4;                       // 16-byte units per strip
+  const unsigned units = (unsigned)s_n * upb;
+  const unsigned u0 = (unsigned)((unsigned long long)units * j / per), u1 = (unsigned)((unsigned long long)units * (j + 1) / per);
+  constexpr int kFlight = 8;
+  for (unsigned u = u0 + tid; u < u1; u += nthreads * kFlight) {
+    uint4 v[kFlight];
+#pragma unroll
+    for (int k = 0; k < kFlight; ++k) {
+      const unsigned uu = min(u + k * nthreads, u1 - 1);           // clamped, not predicated: all loads issue together
+      const unsigned st = uu / upb, off = uu - st * upb;
+      v[k] = *reinterpret_cast<const uint4*>(f.ptr + (size_t)(s_lo + st * s_stride) * f.strip_bytes + (size_t)off * 16);
+    }
+#pragma unroll
+    for (int k = 0; k < kFlight; ++k) asm volatile("" ::"v"(v[k].x), "v"(v[k].y), "v"(v[k].z), "v"(v[k].w));
+  }
+}
+
 }  // namespace ernie

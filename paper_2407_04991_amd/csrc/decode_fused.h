@@ -56,6 +56,10 @@ struct DecGemmArgs {
   float* strip_val;   // EPI_ARGMAX: [B, strips]
   int* strip_idx;
   int strips;
+  // workgroups past the main grid (gemm_dec: blockIdx.x >= n_main; gemm_dec_ln: blockIdx.x >= n_main) only warm
+  // the L2 with a later kernel's weights
+  int n_main;
+  DecPrefetch pf;
 };
 
 // Shared epilogue of the decode GEMMs: `s` is the finished accumulator of (row, col).
@@ -94,6 +98,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_kernel(DecGemmArgs p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int nt = blockIdx.x;
+  if (nt >= p.n_main) {      // uniform for the workgroup
+    dec_prefetch_run(p.pf, (nt - p.n_main) + (gridDim.x - p.n_main) * blockIdx.y, tid, NW * 64);
+    return;
+  }
   const int K = p.K, B = p.B;
   const int k_tiles = K / 16;
   const int tiles_wg = k_tiles / gridDim.y;           // host guarantees divisibility
@@ -190,6 +198,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if ((int)blockIdx.x >= p.n_main) {      // uniform for the workgroup
+    dec_prefetch_run(p.pf, blockIdx.x - p.n_main, tid, NW * 64);
+    return;
+  }
   const int K = p.K, B = p.B;
   const int k_tiles = K / 16;
   const int n_tiles = (p.N + 31) / 32;
@@ -199,7 +211,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   const int zg = (B + R - 1) / R;
   // XCD-contiguous order, row group fastest: the row groups of a strip group run on one XCD and share its
   // weight fragments in that L2 (measured: same speed as spreading them over XCDs, 30 % fewer HBM bytes)
-  const int logical = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int logical = xcd_contiguous_id(blockIdx.x, p.n_main);
   const int sg = logical / zg, zi = logical - sg * zg;
   const int row0 = zi * R;
 

@@ -309,6 +309,7 @@ def test_decode_tuning_variants_agree(E):
         eng = E.engine_from_workload(wl)
         eng.tune("fused_decode", fused); eng.tune("sk_out", sk_out); eng.tune("sk_f2", sk_f2); eng.tune("ln_ns", ln_ns)
         eng.tune("dec_nw16", (sk_out + sk_f2 + ln_ns) % 4)        # every setting of the wave-count knob appears once
+        eng.tune("dec_prefetch", (0, 8, 64, 200, 24, 1024)[(sk_out * 2 + sk_f2 + ln_ns) % 6])   # L2 warm-up workgroups: none .. many
         _say(f"[parity] variant fused={fused} sk_out={sk_out} sk_f2={sk_f2} ln_ns={ln_ns}")
         toks, hid, lg = gpu_generate(eng, ids, lens, sh.n_gen, forced)
         check_rows(orc, toks, hid, lg, f"variant{(fused, sk_out, sk_f2, ln_ns)}")
