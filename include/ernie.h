@@ -265,9 +265,11 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
  *                       split over the contraction with a separate GELU row kernel
  *   "dec_nw16" 0..3     decode GEMMs on fp16 activations with 16 instead of 8 waves per workgroup: 0 = never,
  *                       1 = second FFN GEMM, 2 = also the attention-output GEMM (default), 3 = also the projection
- *   "dec_prefetch" 0..1024  small-batch path: workgroups appended to each decode kernel that pull the weights of
- *                       the next GEMM into the L2 of the XCD that will read them (default 64; 0 = off; rounded up
- *                       to what the launch shape allows).  Does not change any result.
+ *   "dec_prefetch" 0..1024  small-batch path: workgroups appended to the attention-output and second FFN GEMMs that
+ *                       pull what the next kernel reads first (the weights of the following LayerNorm-prologue GEMM,
+ *                       into the L2 of the XCD that will read them, and its bias / scale / shift vectors) out of
+ *                       HBM ahead of time (default 64; 0 = off; rounded up to a multiple of 8 per split).  Does
+ *                       not change any result.
  *   "attn_nt" 0/1       decode attention reads the cache with the non-temporal (streaming) hint, so that the
  *                       once-per-step cache stream does not displace the weights from the caches (default 1)
  * Splits are 1, 2 or 4.  Results are deterministic for any fixed setting.  Returns ERNIE_EINVAL for an

@@ -86,48 +86,57 @@ __device__ __forceinline__ int xcd_contiguous_id(int id, int total) {
   return x * q + min(x, r) + (id >> 3);
 }
 
-// Warm-up of weights that a LATER kernel of the decode step will read.  The decode kernels are short and
-// leave most compute units idle; a few extra workgroups appended to a launch pull the packed weight matrix
-// of the GEMM after next into the L2 of the XCD whose workgroups will read it (workgroup ids congruent mod 8
-// run on one XCD), so that the consumer's single weight round trip ends in that L2 instead of in HBM.  The
-// loaded values are discarded; a wrong guess of the mapping costs time, never correctness.
+// Warm-up of what the NEXT kernel of the decode step will read first.  The decode GEMMs on fp16 activations
+// are short and leave most compute units idle; a few extra workgroups appended to such a launch pull the
+// packed weight matrix of the LayerNorm-prologue GEMM that follows into the L2 of the XCD whose workgroups
+// will read it (workgroup ids congruent mod 8 run on one XCD, and that consumer orders its ids
+// XCD-contiguously), plus the small vectors every consumer workgroup starts with, so that the consumer's
+// memory round trip ends in that L2 instead of in HBM.  The loaded values are discarded; a wrong guess of
+// the mapping costs time, never correctness.
 struct DecPrefetch {
   const unsigned char* ptr;   // packed weight matrix (fragment-major strips); null = nothing to do
   unsigned strip_bytes;       // bytes of one 32-column strip (K * 64), a multiple of 16
   int n_strips;
-  int mode;                   // 1: strip s is read on XCD s % 8 (2-D grid of strips x splits, strips % 8 == 0)
-                              // 2: the consumer orders its (strip group, row group) ids XCD-contiguously
-  int cons_grid, cons_zg, cons_ns;   // mode 2: consumer's workgroup count, row groups per strip group, strips per group
-  int count;                  // prefetching workgroups (a multiple of 8), ids 0 .. count - 1, id % 8 = its XCD
+  // the consumer's grid: `cons_grid` workgroups in XCD-contiguous order, `cons_zg` row groups per strip group,
+  // `cons_ns` strips per group
+  int cons_grid, cons_zg, cons_ns;
+  int count;                  // warming workgroups (a multiple of 8), ids 0 .. count - 1, id % 8 = its XCD
+  // small per-layer vectors (biases, LayerNorm scale / shift) that EVERY workgroup of the consumer, or of the
+  // kernel after it, reads first: each XCD's warming workgroups load all of them (multiples of 16 bytes; null = none)
+  const unsigned char* aux[2];
+  unsigned aux_bytes[2];
 };
 
 __device__ __forceinline__ void dec_prefetch_run(const DecPrefetch& f, int idx, int tid, int nthreads) {
   if (!f.ptr) return;
   const int x = idx & 7, j = idx >> 3, per = f.count >> 3;
-  int s_lo, s_n, s_stride;
-  if (f.mode == 1) {
-    s_lo = x; s_stride = 8; s_n = (f.n_strips - x + 7) >> 3;
-  } else {
-    const int q = f.cons_grid >> 3, r = f.cons_grid & 7;
-    const int lo = x * q + min(x, r), cnt = q + (x < r ? 1 : 0);
-    if (cnt <= 0) return;
-    s_lo = (lo / f.cons_zg) * f.cons_ns;
-    const int s_hi = min(((lo + cnt - 1) / f.cons_zg + 1) * f.cons_ns, f.n_strips);
-    s_stride = 1; s_n = s_hi - s_lo;
+  if (per <= 0) return;
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    if (!f.aux[a]) continue;
+    const unsigned n16 = f.aux_bytes[a] >> 4;
+    for (unsigned u = (unsigned)j * nthreads + tid; u < n16; u += (unsigned)per * nthreads) {
+      const uint4 v = *reinterpret_cast<const uint4*>(f.aux[a] + (size_t)u * 16);
+      asm volatile("" ::"v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w));
+    }
   }
-  if (s_n <= 0 || per <= 0) return;
+  // XCD x runs the consumer's logical ids [lo, lo + cnt), i.e. a contiguous range of strips
+  const int q = f.cons_grid >> 3, r = f.cons_grid & 7;
+  const int lo = x * q + min(x, r), cnt = q + (x < r ? 1 : 0);
+  if (cnt <= 0) return;
+  const int s_lo = (lo / f.cons_zg) * f.cons_ns;
+  const int s_n = min(((lo + cnt - 1) / f.cons_zg + 1) * f.cons_ns, f.n_strips) - s_lo;
+  if (s_n <= 0) return;
   const unsigned upb = f.strip_bytes >> 4;                       // 16-byte units per strip
   const unsigned units = (unsigned)s_n * upb;
   const unsigned u0 = (unsigned)((unsigned long long)units * j / per), u1 = (unsigned)((unsigned long long)units * (j + 1) / per);
   constexpr int kFlight = 8;
+  const unsigned char* base = f.ptr + (size_t)s_lo * f.strip_bytes;      // the XCD's strips are contiguous bytes
   for (unsigned u = u0 + tid; u < u1; u += nthreads * kFlight) {
     uint4 v[kFlight];
 #pragma unroll
-    for (int k = 0; k < kFlight; ++k) {
-      const unsigned uu = min(u + k * nthreads, u1 - 1);           // clamped, not predicated: all loads issue together
-      const unsigned st = uu / upb, off = uu - st * upb;
-      v[k] = *reinterpret_cast<const uint4*>(f.ptr + (size_t)(s_lo + st * s_stride) * f.strip_bytes + (size_t)off * 16);
-    }
+    for (int k = 0; k < kFlight; ++k)      // clamped, not predicated: all loads issue together
+      v[k] = *reinterpret_cast<const uint4*>(base + (size_t)min(u + k * nthreads, u1 - 1) * 16);
 #pragma unroll
     for (int k = 0; k < kFlight; ++k) asm volatile("" ::"v"(v[k].x), "v"(v[k].y), "v"(v[k].z), "v"(v[k].w));
   }

@@ -56,8 +56,7 @@ struct DecGemmArgs {
   float* strip_val;   // EPI_ARGMAX: [B, strips]
   int* strip_idx;
   int strips;
-  // workgroups past the main grid (gemm_dec: blockIdx.x >= n_main; gemm_dec_ln: blockIdx.x >= n_main) only warm
-  // the L2 with a later kernel's weights
+  // gemm_dec: workgroups with blockIdx.x >= n_main only warm the L2 for the next kernel
   int n_main;
   DecPrefetch pf;
 };
@@ -198,10 +197,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  if ((int)blockIdx.x >= p.n_main) {      // uniform for the workgroup
-    dec_prefetch_run(p.pf, blockIdx.x - p.n_main, tid, NW * 64);
-    return;
-  }
   const int K = p.K, B = p.B;
   const int k_tiles = K / 16;
   const int n_tiles = (p.N + 31) / 32;
@@ -211,7 +206,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   const int zg = (B + R - 1) / R;
   // XCD-contiguous order, row group fastest: the row groups of a strip group run on one XCD and share its
   // weight fragments in that L2 (measured: same speed as spreading them over XCDs, 30 % fewer HBM bytes)
-  const int logical = xcd_contiguous_id(blockIdx.x, p.n_main);
+  const int logical = xcd_contiguous_id(blockIdx.x, gridDim.x);
   const int sg = logical / zg, zi = logical - sg * zg;
   const int row0 = zi * R;
 

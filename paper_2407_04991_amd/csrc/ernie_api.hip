@@ -191,25 +191,17 @@ half_t* vcache(const ErnieHandle* h, int layer) {
 // Decode attention: (waves, groups in flight per wave) chosen so that one batch of NW * U * 8 keys covers
 // the whole cache when the capacity allows it (a single memory round trip); long caches stream with 4 waves.
 void launch_attn_decode(const ErnieHandle* h, const float* rqkv, int sk_in, int B, const float* bqkv, half_t* kc,
-                        half_t* vc, hipStream_t s, DecPrefetch pf = DecPrefetch{}) {
+                        half_t* vc, hipStream_t s) {
   const int H = h->cfg.n_heads, S = h->cfg.max_seq, d = h->cfg.d_model;
-  // warming workgroups: whole extra grid rows, a multiple of 8 workgroups after a multiple of 8
-  int extra_rows = 0;
-  if (pf.ptr && pf.count > 0 && ((long)H * B) % 8 == 0) {
-    extra_rows = (pf.count + H - 1) / H;
-    while ((extra_rows * H) % 8 != 0) ++extra_rows;
-  }
-  pf.count = extra_rows * H;
-  if (!extra_rows) pf.ptr = nullptr;
   int v = h->attn_dec;
   // Measured on all benchmark shapes: two key groups in flight per wave (84 registers, five waves per SIMD)
   // beat four (115 registers) by 0.3-3 %; with thousands of short streams (B x H >= 1024, capacity <= 384
   // positions) two waves per workgroup beat four by another 1.7 %.
   if (v == 0) v = ((long)B * H >= 1024 && S <= 384) ? 5 : 4;
 #define ATTN_DEC_LAUNCH(NW, U, NT)                                                                                  \
-  hipLaunchKernelGGL((attn_decode_fused_kernel<NW, U, NT>), dim3(H, B + extra_rows), dim3(NW * 64), 0, s, rqkv, sk_in, B, bqkv, \
+  hipLaunchKernelGGL((attn_decode_fused_kernel<NW, U, NT>), dim3(H, B), dim3(NW * 64), 0, s, rqkv, sk_in, B, bqkv, \
                      kc, vc, h->lens, H, S, d, h->O, h->eos >= 0 ? h->finished : nullptr,                        \
-                     h->compacted ? h->slot : nullptr, pf)
+                     h->compacted ? h->slot : nullptr)
   if (v == 2) ATTN_DEC_LAUNCH(8, 3, false);
   else if (v == 3) ATTN_DEC_LAUNCH(8, 4, false);
   else if (v == 4) ATTN_DEC_LAUNCH(4, 2, true);
@@ -366,12 +358,7 @@ int launch_gemm_dec_ln_nw(ErnieHandle* h, DecGemmArgs a, int ns, int rpw, hipStr
   const size_t lds = a_bytes > r_bytes ? a_bytes : r_bytes;
   if (lds > kMaxLds) return ERNIE_EINVAL;
   const int strips = (a.N + 31) / 32;
-  a.n_main = ((strips + ns - 1) / ns) * ((a.B + R - 1) / R);
-  int extra = 0;
-  if (a.pf.ptr && a.pf.count > 0 && a.n_main % 8 == 0) extra = (a.pf.count + 7) / 8 * 8;
-  a.pf.count = extra;
-  if (!extra) a.pf.ptr = nullptr;
-  const dim3 grid(a.n_main + extra), block(NW * 64);
+  const dim3 grid(((strips + ns - 1) / ns) * ((a.B + R - 1) / R)), block(NW * 64);
 #define LN_LAUNCH(SK, RPW, NS) hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2, SK, RPW, NS>), grid, block, lds, s, a)
 #define LN_BY_NS(SK, RPW) do { if (ns == 1) LN_LAUNCH(SK, RPW, 1); else if (ns == 2) LN_LAUNCH(SK, RPW, 2); else LN_LAUNCH(SK, RPW, 4); } while (0)
 #define LN_BY_RPW(SK) do { if (rpw == 1) LN_BY_NS(SK, 1); else LN_BY_NS(SK, 2); } while (0)
@@ -406,21 +393,16 @@ int launch_gemm_dec_ln(ErnieHandle* h, DecGemmArgs a, hipStream_t s) {
   return launch_gemm_dec_ln_nw<EPI, 8>(h, a, ns, rpw, s);   // sixteen waves measured 6-30 % slower here
 }
 
-// Warm-up descriptors for the weights [N, K] of a later decode GEMM (see DecPrefetch): `ln` says whether the
-// consumer is the LayerNorm-prologue GEMM (XCD-contiguous 1-D grid) or the plain one (strips x splits).
-DecPrefetch prefetch_for(const ErnieHandle* h, const half_t* Wp, int N, int K, int B, bool ln) {
+// Warm-up descriptor (see DecPrefetch) for the weights [N, K] of the LayerNorm-prologue GEMM that runs next.
+DecPrefetch prefetch_for(const ErnieHandle* h, const half_t* Wp, int N, int K, int B) {
   DecPrefetch f{};
-  if (h->dec_prefetch <= 0 || (N % 256) != 0) return f;
+  if (h->dec_prefetch <= 0 || (N % 32) != 0) return f;
+  int ns, rpw;
+  ln_gemm_shape(h, B, &ns, &rpw);
+  const int R = 8 * rpw;
   f.ptr = reinterpret_cast<const unsigned char*>(Wp);
   f.strip_bytes = (unsigned)K * 64u; f.n_strips = N / 32; f.count = h->dec_prefetch;
-  if (ln) {
-    int ns, rpw;
-    ln_gemm_shape(h, B, &ns, &rpw);
-    const int R = 8 * rpw;
-    f.mode = 2; f.cons_ns = ns; f.cons_zg = (B + R - 1) / R; f.cons_grid = ((f.n_strips + ns - 1) / ns) * f.cons_zg;
-  } else {
-    f.mode = 1;
-  }
+  f.cons_ns = ns; f.cons_zg = (B + R - 1) / R; f.cons_grid = ((f.n_strips + ns - 1) / ns) * f.cons_zg;
   return f;
 }
 
@@ -459,21 +441,35 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
     {
       // K and V of every visible position (cached + the appended one), 2 bytes each
       ProfScope prof(h, ERNIE_PROF_ATTN_DEC, s, 2.0 * (h->sum_len + (double)B * (h->steps + 1)) * d * 2.0, 0.0);
-      launch_attn_decode(h, h->r_qkv, 1, B, L.bqkv, kcache(h, l), vcache(h, l), s, prefetch_for(h, L.wo, d, d, B, false));
+      launch_attn_decode(h, h->r_qkv, 1, B, L.bqkv, kcache(h, l), vcache(h, l), s);
     }
     DecGemmArgs o{};
     o.B = B; o.Wp = L.wo; o.N = d; o.K = d; o.a16 = h->O; o.rout = h->r_out;
-    o.pf = prefetch_for(h, L.w1, f, d, B, true);
+    // FFN1 comes next: its weights, and bo, b1, b2, ln1 scale / shift (contiguous in the arena)
+    o.pf = prefetch_for(h, L.w1, f, d, B);
+    if (o.pf.ptr) {
+      o.pf.aux[0] = reinterpret_cast<const unsigned char*>(L.bo);
+      o.pf.aux_bytes[0] = (unsigned)(reinterpret_cast<const unsigned char*>(L.ln1_b + d) - o.pf.aux[0]);
+    }
     rc |= launch_gemm_dec<EPI_RAW>(h, o, h->sk_out, s);
     DecGemmArgs f1{};
     f1.B = B; f1.eps = c.ln_eps; f1.Wp = L.w1; f1.N = f; f1.K = d; f1.r32 = h->r_out; f1.sk_in = h->sk_out;
     f1.bias = L.bo; f1.res = h->X; f1.gamma = L.ln1_g; f1.beta = L.ln1_b; f1.xout = h->X1;
     f1.bias_out = L.b1; f1.g16 = h->G;
-    f1.pf = prefetch_for(h, L.w2, d, f, B, false);
     rc |= launch_gemm_dec_ln<EPI_GELU16>(h, f1, s);
     DecGemmArgs f2{};
     f2.B = B; f2.Wp = L.w2; f2.N = d; f2.K = f; f2.a16 = h->G; f2.rout = h->r_f2;
-    if (l + 1 < c.n_layers) f2.pf = prefetch_for(h, h->layers[l + 1].wqkv, 3 * d, d, B, true);
+    if (l + 1 < c.n_layers) {
+      // the next layer's QKV GEMM comes next: its weights, b2 and ln2 scale / shift of this layer (contiguous
+      // from b2 to ln2_b), and the bqkv that the attention after it starts with
+      f2.pf = prefetch_for(h, h->layers[l + 1].wqkv, 3 * d, d, B);
+      if (f2.pf.ptr) {
+        f2.pf.aux[0] = reinterpret_cast<const unsigned char*>(L.b2);
+        f2.pf.aux_bytes[0] = (unsigned)(reinterpret_cast<const unsigned char*>(L.ln2_b + d) - f2.pf.aux[0]);
+        f2.pf.aux[1] = reinterpret_cast<const unsigned char*>(h->layers[l + 1].bqkv);
+        f2.pf.aux_bytes[1] = (unsigned)(3 * d * 4);
+      }
+    }
     rc |= launch_gemm_dec<EPI_RAW>(h, f2, h->sk_f2, s);
   }
   const LayerPtrs& P = h->layers[c.n_layers - 1];

@@ -214,6 +214,13 @@ def test_base_shape_sampled_rows(E):
     _say(f"[parity] base: {st}")
     assert st["exact_required"] >= st["total"] // 4
     eng.close()
+    # the L2 warm-up workgroups (on by default at this shape) load and discard: any count gives the same bits
+    for count in (0, 8, 200):
+        eng = E.engine_from_workload(wl)
+        eng.tune("dec_prefetch", count)
+        toks2, hid2, lg2 = gpu_generate(eng, ids, lens, 6, forced)
+        assert np.array_equal(lg2, lg[:6]) and np.array_equal(toks2, toks[:6]), f"dec_prefetch={count} changed results"
+        eng.close()
 
 
 @pytest.mark.parametrize("B", [40, 70, 130, 256])
