@@ -270,6 +270,10 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
  *                       into the L2 of the XCD that will read them, and its bias / scale / shift vectors) out of
  *                       HBM ahead of time (default 64; 0 = off; rounded up to a multiple of 8 per split).  Does
  *                       not change any result.
+ *   "kv_prefetch" 0..2048  small-batch path: workgroups appended to the QKV GEMM that stream the cache rows of the
+ *                       attention that follows into the L2 of the XCD that will read them (0 = off, 1 = one
+ *                       workgroup per two (sequence, head) streams (default), larger = that many workgroups,
+ *                       rounded up to a multiple of 8).  Does not change any result.
  *   "attn_nt" 0/1       decode attention reads the cache with the non-temporal (streaming) hint, so that the
  *                       once-per-step cache stream does not displace the weights from the caches (default 1)
  * Splits are 1, 2 or 4.  Results are deterministic for any fixed setting.  Returns ERNIE_EINVAL for an

@@ -100,16 +100,18 @@ struct DecPrefetch {
   // the consumer's grid: `cons_grid` workgroups in XCD-contiguous order, `cons_zg` row groups per strip group,
   // `cons_ns` strips per group
   int cons_grid, cons_zg, cons_ns;
-  int count;                  // warming workgroups (a multiple of 8), ids 0 .. count - 1, id % 8 = its XCD
+  int count;                  // warming workgroups (a multiple of 8)
   // small per-layer vectors (biases, LayerNorm scale / shift) that EVERY workgroup of the consumer, or of the
   // kernel after it, reads first: each XCD's warming workgroups load all of them (multiples of 16 bytes; null = none)
   const unsigned char* aux[2];
   unsigned aux_bytes[2];
 };
 
-__device__ __forceinline__ void dec_prefetch_run(const DecPrefetch& f, int idx, int tid, int nthreads) {
+// idx = rank among the warming workgroups, wg_id = the workgroup's linear id in its grid (its XCD is wg_id % 8);
+// ranks 8 j .. 8 j + 7 must sit on 8 different XCDs (consecutive linear ids)
+__device__ __forceinline__ void dec_prefetch_run(const DecPrefetch& f, int idx, int wg_id, int tid, int nthreads) {
   if (!f.ptr) return;
-  const int x = idx & 7, j = idx >> 3, per = f.count >> 3;
+  const int x = wg_id & 7, j = idx >> 3, per = f.count >> 3;
   if (per <= 0) return;
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
@@ -139,6 +141,45 @@ __device__ __forceinline__ void dec_prefetch_run(const DecPrefetch& f, int idx, 
       v[k] = *reinterpret_cast<const uint4*>(base + (size_t)min(u + k * nthreads, u1 - 1) * 16);
 #pragma unroll
     for (int k = 0; k < kFlight; ++k) asm volatile("" ::"v"(v[k].x), "v"(v[k].y), "v"(v[k].z), "v"(v[k].w));
+  }
+}
+
+// Warm-up of the key/value cache rows the next decode attention will stream: the attention workgroup of
+// (head h, batch row b) has id h + H b, so XCD x reads the streams with (h + H b) % 8 == x.
+struct KvPrefetch {
+  const unsigned char* k;     // layer bases of the K and V caches [Bmax][H][S][64] fp16; null = nothing to do
+  const unsigned char* v;
+  const int* slot;            // cache row of batch row b, or null
+  int B, H, S, rows;          // rows = upper bound of the valid rows of any stream (<= S)
+  int count;                  // warming workgroups (a multiple of 8)
+};
+
+__device__ __forceinline__ void kv_prefetch_run(const KvPrefetch& f, int idx, int wg_id, int tid, int nthreads) {
+  if (!f.k) return;
+  const int x = wg_id & 7, j = idx >> 3, per = f.count >> 3;
+  if (per <= 0) return;
+  const int n_streams = f.B * f.H;
+  // every stream is fetched up to the longest one's length: reading the per-row lengths first would put a
+  // second memory round trip in front of the fetch, which then outlasts the host kernel (measured: a loss)
+  const unsigned units = (unsigned)f.rows * 8;                   // 16-byte units per stream and tensor
+  for (int s = x + 8 * j; s < n_streams; s += 8 * per) {
+    const int b = s / f.H, h = s - b * f.H;
+    const int cb = f.slot ? f.slot[b] : b;
+    const size_t base = ((size_t)cb * f.H + h) * f.S * 128;
+    for (unsigned u = tid; u < units; u += nthreads * 4) {
+      floatx4 kk[4], vv[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {      // clamped, not predicated: all loads issue together
+        const size_t off = base + (size_t)min(u + q * nthreads, units - 1) * 16;
+        kk[q] = *reinterpret_cast<const floatx4*>(f.k + off);
+        vv[q] = *reinterpret_cast<const floatx4*>(f.v + off);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        asm volatile("" ::"v"(kk[q][0]), "v"(kk[q][1]), "v"(kk[q][2]), "v"(kk[q][3]));
+        asm volatile("" ::"v"(vv[q][0]), "v"(vv[q][1]), "v"(vv[q][2]), "v"(vv[q][3]));
+      }
+    }
   }
 }
 

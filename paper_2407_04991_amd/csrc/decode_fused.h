@@ -59,6 +59,7 @@ struct DecGemmArgs {
   // gemm_dec: workgroups with blockIdx.x >= n_main only warm the L2 for the next kernel
   int n_main;
   DecPrefetch pf;
+  KvPrefetch kv;      // warming workgroups past pf.count stream the next attention's cache rows
 };
 
 // Shared epilogue of the decode GEMMs: `s` is the finished accumulator of (row, col).
@@ -98,7 +99,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_kernel(DecGemmArgs p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int nt = blockIdx.x;
   if (nt >= p.n_main) {      // uniform for the workgroup
-    dec_prefetch_run(p.pf, (nt - p.n_main) + (gridDim.x - p.n_main) * blockIdx.y, tid, NW * 64);
+    const int idx = (nt - p.n_main) + (gridDim.x - p.n_main) * blockIdx.y;
+    const int wg_id = nt + gridDim.x * blockIdx.y;
+    if (idx < p.pf.count) dec_prefetch_run(p.pf, idx, wg_id, tid, NW * 64);
+    else kv_prefetch_run(p.kv, idx - p.pf.count, wg_id, tid, NW * 64);
     return;
   }
   const int K = p.K, B = p.B;
@@ -197,6 +201,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if ((int)blockIdx.x >= p.n_main) {      // uniform for the workgroup
+    kv_prefetch_run(p.kv, blockIdx.x - p.n_main, blockIdx.x, tid, NW * 64);
+    return;
+  }
   const int K = p.K, B = p.B;
   const int k_tiles = K / 16;
   const int n_tiles = (p.N + 31) / 32;
@@ -206,7 +214,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
   const int zg = (B + R - 1) / R;
   // XCD-contiguous order, row group fastest: the row groups of a strip group run on one XCD and share its
   // weight fragments in that L2 (measured: same speed as spreading them over XCDs, 30 % fewer HBM bytes)
-  const int logical = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int logical = xcd_contiguous_id(blockIdx.x, p.n_main);
   const int sg = logical / zg, zi = logical - sg * zg;
   const int row0 = zi * R;
 

@@ -141,7 +141,7 @@ struct ErnieHandle {
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
   half_t *type_emb = nullptr, *head_w = nullptr;                      // optional variants, null when off
   float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
-  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2, dec_prefetch = 64;
+  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2, dec_prefetch = 64, kv_prefetch = 1;
   int cand = 0;                  // argmax candidates per row left by the last projection   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   float* r_logits = nullptr;     // [2][max_batch][V'] fp32, large-batch projection only
@@ -327,11 +327,15 @@ int launch_gemm_dec(ErnieHandle* h, DecGemmArgs a, int sk, hipStream_t s) {
   if (sk < 1 || (a.K / 16) % sk != 0) return ERNIE_EINVAL;
   const int kslice = a.K / sk;
   a.n_main = (a.N + 31) / 32;
-  // warming workgroups: extra columns of the grid, a multiple of 8 per split after a multiple of 8 strips
+  // warming workgroups: extra columns of the grid, a multiple of 8 per split (ranks 8 j .. 8 j + 7 then have
+  // consecutive linear ids, i.e. one per XCD)
   int extra = 0;
-  if (a.pf.ptr && a.pf.count > 0 && a.n_main % 8 == 0) extra = ((a.pf.count + sk - 1) / sk + 7) / 8 * 8;
-  a.pf.count = extra * sk;
-  if (!extra) a.pf.ptr = nullptr;
+  const int want_pf = a.pf.ptr ? (a.pf.count + 7) / 8 * 8 : 0, want_kv = a.kv.k ? a.kv.count : 0;
+  if (want_pf + want_kv > 0) extra = ((want_pf + want_kv + sk - 1) / sk + 7) / 8 * 8;
+  a.pf.count = want_kv ? want_pf : extra * sk;
+  a.kv.count = want_kv ? extra * sk - want_pf : 0;
+  if (!a.pf.count) a.pf.ptr = nullptr;
+  if (!a.kv.count) a.kv.k = nullptr;
   const dim3 grid(a.n_main + extra, sk);
 #define DEC_LAUNCH(MTV, NWV)                                                                    \
   do {                                                                                          \
@@ -358,7 +362,10 @@ int launch_gemm_dec_ln_nw(ErnieHandle* h, DecGemmArgs a, int ns, int rpw, hipStr
   const size_t lds = a_bytes > r_bytes ? a_bytes : r_bytes;
   if (lds > kMaxLds) return ERNIE_EINVAL;
   const int strips = (a.N + 31) / 32;
-  const dim3 grid(((strips + ns - 1) / ns) * ((a.B + R - 1) / R)), block(NW * 64);
+  a.n_main = ((strips + ns - 1) / ns) * ((a.B + R - 1) / R);
+  if (!a.kv.k || a.kv.count <= 0) { a.kv.k = nullptr; a.kv.count = 0; }
+  a.kv.count = (a.kv.count + 7) / 8 * 8;
+  const dim3 grid(a.n_main + a.kv.count), block(NW * 64);
 #define LN_LAUNCH(SK, RPW, NS) hipLaunchKernelGGL((gemm_dec_ln_kernel<NW, EPI, 2, SK, RPW, NS>), grid, block, lds, s, a)
 #define LN_BY_NS(SK, RPW) do { if (ns == 1) LN_LAUNCH(SK, RPW, 1); else if (ns == 2) LN_LAUNCH(SK, RPW, 2); else LN_LAUNCH(SK, RPW, 4); } while (0)
 #define LN_BY_RPW(SK) do { if (rpw == 1) LN_BY_NS(SK, 1); else LN_BY_NS(SK, 2); } while (0)
@@ -406,6 +413,21 @@ DecPrefetch prefetch_for(const ErnieHandle* h, const half_t* Wp, int N, int K, i
   return f;
 }
 
+// Warm-up descriptor (see KvPrefetch) for the cache rows that layer `l`'s decode attention of this step will stream.
+KvPrefetch kv_prefetch_for(const ErnieHandle* h, int l, int B) {
+  KvPrefetch f{};
+  const int H = h->cfg.n_heads;
+  if (!h->kv_prefetch) return f;
+  f.k = reinterpret_cast<const unsigned char*>(kcache(h, l)); f.v = reinterpret_cast<const unsigned char*>(vcache(h, l));
+  f.slot = h->compacted ? h->slot : nullptr;
+  f.B = B; f.H = H; f.S = h->cfg.max_seq;
+  f.rows = std::min(h->cfg.max_seq, h->max_len + h->steps);
+  // two (sequence, head) streams per warming workgroup measured best at B = 32 (more contend with the host
+  // kernel, fewer outlast it)
+  f.count = h->kv_prefetch > 1 ? h->kv_prefetch : (H * B / 2 + 7) / 8 * 8;
+  return f;
+}
+
 // Small batches: every GEMM input fits in LDS, row-wise work lives in consumer prologues (5 launches per layer).
 bool fused_decode_fits(const ErnieHandle* h, int B) {
   if (!h->fused_decode || B > kFusedMaxBatch || h->cfg.d_model > 1024) return false;
@@ -431,11 +453,13 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
       a.sk_in = 0; a.tok = tok; a.cache_len = h->lens; a.tok_emb = h->tok_rm; a.pos_emb = h->pos;
       a.seg_row = h->type_emb ? h->type_emb + d : nullptr; a.max_pos = c.max_pos; a.eos = h->eos; a.finished = h->finished;
       a.gamma = h->emb_g; a.beta = h->emb_b; a.xout = h->X;
+      a.kv = kv_prefetch_for(h, l, B);
       rc |= launch_gemm_dec_ln<EPI_RAW>(h, a, s);
     } else {
       const LayerPtrs& P = h->layers[l - 1];
       a.r32 = h->r_f2; a.sk_in = h->sk_f2; a.bias = P.b2; a.res = h->X1; a.gamma = P.ln2_g; a.beta = P.ln2_b;
       a.xout = h->X;
+      a.kv = kv_prefetch_for(h, l, B);
       rc |= launch_gemm_dec_ln<EPI_RAW>(h, a, s);
     }
     {
@@ -950,6 +974,7 @@ int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!h || !key) return ERNIE_EINVAL;
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "dec_nw16")) { h->dec_nw16 = value; return ERNIE_OK; }
+  if (!strcmp(key, "kv_prefetch")) { if (value < 0 || value > 2048) return ERNIE_EINVAL; h->kv_prefetch = value; return ERNIE_OK; }
   if (!strcmp(key, "dec_prefetch")) { if (value < 0 || value > 1024) return ERNIE_EINVAL; h->dec_prefetch = value; return ERNIE_OK; }
   if (!strcmp(key, "big_logits_gemm")) { h->big_logits_gemm = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "big_f1_fused")) { h->big_f1_fused = value != 0; return ERNIE_OK; }

@@ -215,11 +215,11 @@ def test_base_shape_sampled_rows(E):
     assert st["exact_required"] >= st["total"] // 4
     eng.close()
     # the L2 warm-up workgroups (on by default at this shape) load and discard: any count gives the same bits
-    for count in (0, 8, 200):
+    for count, kv in ((0, 0), (8, 8), (200, 1000)):
         eng = E.engine_from_workload(wl)
-        eng.tune("dec_prefetch", count)
+        eng.tune("dec_prefetch", count); eng.tune("kv_prefetch", kv)
         toks2, hid2, lg2 = gpu_generate(eng, ids, lens, 6, forced)
-        assert np.array_equal(lg2, lg[:6]) and np.array_equal(toks2, toks[:6]), f"dec_prefetch={count} changed results"
+        assert np.array_equal(lg2, lg[:6]) and np.array_equal(toks2, toks[:6]), f"dec_prefetch={count} kv_prefetch={kv} changed results"
         eng.close()
 
 
@@ -317,6 +317,7 @@ def test_decode_tuning_variants_agree(E):
         eng.tune("fused_decode", fused); eng.tune("sk_out", sk_out); eng.tune("sk_f2", sk_f2); eng.tune("ln_ns", ln_ns)
         eng.tune("dec_nw16", (sk_out + sk_f2 + ln_ns) % 4)        # every setting of the wave-count knob appears once
         eng.tune("dec_prefetch", (0, 8, 64, 200, 24, 1024)[(sk_out * 2 + sk_f2 + ln_ns) % 6])   # L2 warm-up workgroups: none .. many
+        eng.tune("kv_prefetch", (1, 0, 16, 2048, 1, 40)[(sk_out + sk_f2 * 2 + ln_ns) % 6])
         _say(f"[parity] variant fused={fused} sk_out={sk_out} sk_f2={sk_f2} ln_ns={ln_ns}")
         toks, hid, lg = gpu_generate(eng, ids, lens, sh.n_gen, forced)
         check_rows(orc, toks, hid, lg, f"variant{(fused, sk_out, sk_f2, ln_ns)}")
