@@ -504,6 +504,17 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
   z.bias_out = h->out_bias;
   z.strip_val = h->strip_val; z.strip_idx = h->strip_idx; z.strips = h->plan.strips;
   h->cand = h->plan.strips;
+  {
+    // the next step starts with layer 0's QKV GEMM on the embedding rows: its weights and the embedding
+    // LayerNorm's scale / shift (contiguous) ride along with the projection
+    z.pf = prefetch_for(h, h->layers[0].wqkv, 3 * d, d, B);
+    if (z.pf.ptr) {
+      z.pf.aux[0] = reinterpret_cast<const unsigned char*>(h->emb_g);
+      z.pf.aux_bytes[0] = (unsigned)(reinterpret_cast<const unsigned char*>(h->emb_b + d) - z.pf.aux[0]);
+      z.pf.aux[1] = reinterpret_cast<const unsigned char*>(h->layers[0].bqkv);
+      z.pf.aux_bytes[1] = (unsigned)(3 * d * 4);
+    }
+  }
   rc |= launch_gemm_dec<EPI_ARGMAX>(h, z, 1, s);
   return rc ? ERNIE_EHIP : ERNIE_OK;
 }
