@@ -44,13 +44,14 @@ struct EpiResidual {
   const half_t* res;   // [M, N]
   half_t* y;           // [M, N]
   int N;
-  __device__ __forceinline__ void store8(int row, int col, const float (&v)[8]) const {
-    const size_t o = (size_t)row * N + col;
-    const half8 r = *reinterpret_cast<const half8*>(res + o);
+  __device__ __forceinline__ half8 load8(int row, int col) const {
+    return *reinterpret_cast<const half8*>(res + (size_t)row * N + col);
+  }
+  __device__ __forceinline__ void store8(int row, int col, const float (&v)[8], half8 r) const {
     half8 out;
 #pragma unroll
     for (int j = 0; j < 8; ++j) out[j] = (half_t)(v[j] + (float)r[j]);
-    *reinterpret_cast<half8*>(y + o) = out;
+    *reinterpret_cast<half8*>(y + (size_t)row * N + col) = out;
   }
 };
 

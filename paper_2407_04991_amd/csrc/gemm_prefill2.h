@@ -19,6 +19,8 @@
 // products land in accumulator entries the epilogue never stores).
 #pragma once
 
+#include <type_traits>
+
 #include "common.h"
 #include "gemm_prefill.h"   // epilogue functors
 
@@ -36,6 +38,14 @@ template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
+
+// An epilogue that reads memory (a residual) declares load8(row, col) -> half8 and takes the loaded value as
+// a fourth argument of store8: the kernel then issues every such load of a wave before the first store, so
+// that they are in flight together instead of one dependent round trip per 8 outputs.
+template <class E, class = void>
+struct epi_has_load { static constexpr bool value = false; };
+template <class E>
+struct epi_has_load<E, decltype((void)&E::load8)> { static constexpr bool value = true; };
 
 template <int WGM, int WGN, int TM, int TN, int BK, int S>
 struct GemmPipe {
@@ -77,6 +87,14 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
   // epilogue functor routes the partial result by blockIdx.y (host guarantees divisibility by BK)
   const int steps = K / BK / gridDim.y;
   const int kbeg = blockIdx.y * steps * BK;
+
+  // bias of this lane's TN columns: fetched now, so that the epilogue does not start with a memory round trip
+  float bvv[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int mycol = n0 + wn * 32 * TN + j * 32 + (lane & 31);
+    bvv[j] = (mycol < N) ? bias[mycol] : 0.f;
+  }
 
   // ---- per-lane source addresses of this wave's load instructions (k offset added per step)
   const half_t* a_src[P::kAInstr];
@@ -174,27 +192,51 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
   __syncthreads();                       // all waves have finished reading the last stage
   float* patch = reinterpret_cast<float*>(smem_raw) + wave * (32 * 33);
   static_assert(P::kLdsBytes >= P::kWaves * 32 * 33 * 4, "the stage ring must hold one patch per wave");
+  // Interior tiles (the vast majority) take a copy of the epilogue without bounds checks: with the per-store
+  // branches gone the compiler can count the outstanding loads and stores exactly, instead of draining them
+  // at every join.
+  auto run_epilogue = [&](auto checked_tag) {
+    constexpr bool kChecked = decltype(checked_tag)::value;
+    half8 pre[epi_has_load<Epi>::value ? TN * TM * 2 : 1];
+    if constexpr (epi_has_load<Epi>::value) {
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int colbase = n0 + wn * 32 * TN + j * 32;
-    const int mycol = colbase + (lane & 31);
-    const float bv = (mycol < N) ? bias[mycol] : 0.f;
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) patch[mfma32_row(v, lane) * 33 + (lane & 31)] = acc[i][j][v] + bv;
-      // same-wave LDS traffic: the compiler's lgkmcnt waits order the reads after the writes
+          for (int t = 0; t < 2; ++t) {
+            const int row = m0 + wm * 32 * TM + i * 32 + t * 16 + (lane >> 2), col = n0 + wn * 32 * TN + j * 32 + (lane & 3) * 8;
+            half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (!kChecked || (row < M && col < N)) z = epi.load8(row, col);
+            pre[(j * TM + i) * 2 + t] = z;
+          }
+    }
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int r = t * 16 + (lane >> 2), c8 = (lane & 3) * 8;
-        float o[8];
+    for (int j = 0; j < TN; ++j) {
+      const int colbase = n0 + wn * 32 * TN + j * 32;
+      const float bv = bvv[j];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) o[q] = patch[r * 33 + c8 + q];
-        const int row = m0 + wm * 32 * TM + i * 32 + r, col = colbase + c8;
-        if (row < M && col < N) epi.store8(row, col, o);
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) patch[mfma32_row(v, lane) * 33 + (lane & 31)] = acc[i][j][v] + bv;
+        // same-wave LDS traffic: the compiler's lgkmcnt waits order the reads after the writes
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const int r = t * 16 + (lane >> 2), c8 = (lane & 3) * 8;
+          float o[8];
+#pragma unroll
+          for (int q = 0; q < 8; ++q) o[q] = patch[r * 33 + c8 + q];
+          const int row = m0 + wm * 32 * TM + i * 32 + r, col = colbase + c8;
+          if (!kChecked || (row < M && col < N)) {
+            if constexpr (epi_has_load<Epi>::value) epi.store8(row, col, o, pre[(j * TM + i) * 2 + t]);
+            else epi.store8(row, col, o);
+          }
+        }
       }
     }
-  }
+  };
+  if (m0 + P::kBM <= M && n0 + P::kBN <= N) run_epilogue(std::false_type{});
+  else run_epilogue(std::true_type{});
 }
 
 }  // namespace ernie
