@@ -17,6 +17,8 @@
 // hides under the L2-resident activation work.
 #pragma once
 
+#include <type_traits>
+
 #include "common.h"
 #include "rowops.h"
 
@@ -124,14 +126,40 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_kernel(DecGemmArgs p) {
 
   // 2. prologue: copy the fp16 A tile [MT * 32, kslice] into LDS (rows >= B re-read row B-1; their
   //    products land in accumulator rows that are never stored)
+  //    All pieces of a thread (up to eight 16-byte pieces per batch) are requested together, and the first
+  //    batch, which covers the whole tile at the usual sizes, is straight-line code with exactly as many
+  //    pieces as the tile needs: a loop of one load and one LDS store per trip spends a memory round trip per
+  //    trip, and the compiler drains all outstanding loads (the weight stream above) at a loop header.
+  //    Pieces past the end wrap around (spread over the tile, not piled on one address) and are not stored.
   {
     const int chunks = kslice / 8;
-    for (int id = tid; id < MT * 32 * chunks; id += NW * 64) {
-      const int r = id / chunks, ch = id - r * chunks;
-      const int rr = min(r, B - 1);
-      *reinterpret_cast<half8*>(sA + r * pitch + ch * 8) =
-          *reinterpret_cast<const half8*>(p.a16 + (size_t)rr * K + k0 + ch * 8);
+    const int total = MT * 32 * chunks;
+    auto copy_batch = [&](int id0, auto pieces_tag) {
+      constexpr int kPieces = decltype(pieces_tag)::value;
+      half8 v[kPieces];
+      int dst[kPieces];
+#pragma unroll
+      for (int q = 0; q < kPieces; ++q) {
+        int id = id0 + q * NW * 64;
+        if (id >= total) id -= total;                      // < total: a batch never spans more than the tile twice
+        const int r = id / chunks, ch = id - r * chunks;
+        dst[q] = r * pitch + ch * 8;
+        v[q] = *reinterpret_cast<const half8*>(p.a16 + (size_t)min(r, B - 1) * K + k0 + ch * 8);
+      }
+#pragma unroll
+      for (int q = 0; q < kPieces; ++q)
+        if (id0 + q * NW * 64 < total) *reinterpret_cast<half8*>(sA + dst[q]) = v[q];
+    };
+    const int needed = (total + NW * 64 - 1) / (NW * 64);      // pieces per thread, uniform
+    switch (needed < 8 ? needed : 8) {
+      case 1: copy_batch(tid, std::integral_constant<int, 1>{}); break;
+      case 2: copy_batch(tid, std::integral_constant<int, 2>{}); break;
+      case 3: copy_batch(tid, std::integral_constant<int, 3>{}); break;
+      case 4: copy_batch(tid, std::integral_constant<int, 4>{}); break;
+      case 5: case 6: copy_batch(tid, std::integral_constant<int, 6>{}); break;
+      default: copy_batch(tid, std::integral_constant<int, 8>{}); break;
     }
+    for (int id0 = tid + NW * 64 * 8; id0 < total; id0 += NW * 64 * 4) copy_batch(id0, std::integral_constant<int, 4>{});
   }
   __syncthreads();
 
