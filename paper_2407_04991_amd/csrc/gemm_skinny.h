@@ -97,20 +97,34 @@ __global__ __launch_bounds__(256) void logits_rows_argmax_kernel(const float* __
   const size_t slab = (size_t)B * N;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
-  // N is a multiple of 8 on this path (the GEMM epilogue stores runs of 8 columns): 16-byte pieces
-  for (int c = tid * 4; c < N; c += 1024) {
-    float4 z = *reinterpret_cast<const float4*>(row + c);
-    for (int s = 1; s < sk; ++s) {
-      const float4 y = *reinterpret_cast<const float4*>(row + (size_t)s * slab + c);
-      z.x += y.x; z.y += y.y; z.z += y.z; z.w += y.w;
+  // N is a multiple of 8 on this path (the GEMM epilogue stores runs of 8 columns): 16-byte pieces, four per
+  // thread requested together (addresses clamped, not predicated; a loop of load + compare per piece costs a
+  // memory round trip per trip).  The host splits this projection at most two ways; further partials are added
+  // by the general loop.
+  for (int c0 = tid * 4; c0 < N; c0 += 4096) {
+    float4 z[4], y[4], ob[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = min(c0 + q * 1024, N - 4);
+      z[q] = *reinterpret_cast<const float4*>(row + c);
+      y[q] = *reinterpret_cast<const float4*>(row + (size_t)(sk > 1 ? 1 : 0) * slab + c);
+      ob[q] = out_bias ? *reinterpret_cast<const float4*>(out_bias + c) : float4{0.f, 0.f, 0.f, 0.f};
     }
-    if (out_bias) {
-      const float4 y = *reinterpret_cast<const float4*>(out_bias + c);
-      z.x += y.x; z.y += y.y; z.z += y.z; z.w += y.w;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = c0 + q * 1024;
+      if (c >= N) break;
+      float4 a = z[q];
+      if (sk > 1) { a.x += y[q].x; a.y += y[q].y; a.z += y[q].z; a.w += y[q].w; }
+      for (int s = 2; s < sk; ++s) {
+        const float4 t = *reinterpret_cast<const float4*>(row + (size_t)s * slab + c);
+        a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
+      }
+      a.x += ob[q].x; a.y += ob[q].y; a.z += ob[q].z; a.w += ob[q].w;
+      if (logits_out) *reinterpret_cast<float4*>(logits_out + (size_t)b * N + c) = a;
+      argmax_merge(bv, bi, a.x, c); argmax_merge(bv, bi, a.y, c + 1);
+      argmax_merge(bv, bi, a.z, c + 2); argmax_merge(bv, bi, a.w, c + 3);
     }
-    if (logits_out) *reinterpret_cast<float4*>(logits_out + (size_t)b * N + c) = z;
-    argmax_merge(bv, bi, z.x, c); argmax_merge(bv, bi, z.y, c + 1);
-    argmax_merge(bv, bi, z.z, c + 2); argmax_merge(bv, bi, z.w, c + 3);
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {

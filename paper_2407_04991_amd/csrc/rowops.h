@@ -215,9 +215,28 @@ __global__ __launch_bounds__(256) void argmax_final_kernel(const float* __restri
   __shared__ float sv[4];
   __shared__ int si[4];
   const int b = blockIdx.x;
+  // everything this workgroup reads is requested up front: the row's state for the last step of thread 0 and
+  // the first four candidates of every thread (a loop of load + compare costs a memory round trip per trip)
+  int done_flag = 0, len_now = 0;
+  if (threadIdx.x == 0) {
+    done_flag = finished ? finished[b] : 0;
+    len_now = advance ? cache_len[b] : 0;
+  }
   float v = -INFINITY;
   int i = 0x7fffffff;
-  for (int s = threadIdx.x; s < strips; s += blockDim.x)
+  {
+    float cv[4];
+    int ci[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int s = min((int)threadIdx.x + q * 256, strips - 1);       // clamped: a duplicate candidate changes nothing
+      cv[q] = strip_val[(size_t)b * strips + s];
+      ci[q] = strip_idx[(size_t)b * strips + s];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) argmax_merge(v, i, cv[q], ci[q]);
+  }
+  for (int s = threadIdx.x + 4 * 256; s < strips; s += blockDim.x)
     argmax_merge(v, i, strip_val[(size_t)b * strips + s], strip_idx[(size_t)b * strips + s]);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -230,14 +249,11 @@ __global__ __launch_bounds__(256) void argmax_final_kernel(const float* __restri
   if (threadIdx.x == 0) {
     for (int w = 1; w < 4; ++w) argmax_merge(v, i, sv[w], si[w]);
     if (i < 0 || i >= vocab) i = 0;   // only reachable if every logit is NaN
-    const bool done = finished && finished[b];
+    const bool done = done_flag != 0;
     if (done) i = eos;
     tok_out[b] = i;
     if (tok_keep != tok_out) tok_keep[b] = i;
-    if (advance && !done) {
-      const int n = cache_len[b];
-      if (n < max_seq) cache_len[b] = n + 1;
-    }
+    if (advance && !done && len_now < max_seq) cache_len[b] = len_now + 1;
   }
 }
 
