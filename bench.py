@@ -360,7 +360,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="base")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=16)
+    ap.add_argument("--cpu-rows", type=int, default=32, help="sequences of the batch the CPU oracle is timed on (about 10 s)")
     ap.add_argument("--graph", type=int, default=1, help="replay the pass as HIP graphs (1) or launch eagerly (0)")
     ap.add_argument("--prof-passes", type=int, default=3, help="passes of the event-bracketed per-kernel profile")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
