@@ -416,3 +416,22 @@ def test_full_size_configs_sampled_rows(E, name, rows, batch):
     st = check_rows(orc, toks, hid, lg, name)
     _say(f"[parity] {name}: {st}")
     eng.close()
+
+
+@pytest.mark.parametrize("batch,nw16", [(48, 2), (48, 0), (24, 0)])
+def test_wide_model_on_the_small_batch_path(E, batch, nw16):
+    """ERNIE-large widths (d = 1024, FFN 4096) at batch sizes that take the fused small-batch decode kernels: the
+    activation tile of the second FFN GEMM then needs 8 (16 waves) or 16 (8 waves) pieces per thread, i.e. the
+    straight-line first batch of loads plus, with 8 waves, the loop for the remainder."""
+    wl = make_workload("large", n_layers=2, batch=batch, prompt_len=48, n_gen=4, vocab_full=4096, vocab_kept=2048)
+    sh = wl.shape
+    eng = E.engine_from_workload(wl)
+    eng.tune("dec_nw16", nw16)
+    ids, lens = wl.padded(0)
+    rows = [0, batch // 2, batch - 1]
+    _say(f"[parity] wide small-batch B={batch} dec_nw16={nw16} rows {rows}")
+    orc = oracle_generate(wl, 0, rows, sh.n_gen)
+    toks, hid, lg = gpu_generate(eng, ids, lens, sh.n_gen, {r: orc[r]["tokens"] for r in orc})
+    st = check_rows(orc, toks, hid, lg, f"wide-B{batch}")
+    _say(f"[parity] wide small-batch: {st}")
+    eng.close()
