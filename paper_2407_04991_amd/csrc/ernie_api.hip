@@ -400,6 +400,15 @@ int launch_gemm_dec_ln(ErnieHandle* h, DecGemmArgs a, hipStream_t s) {
   return launch_gemm_dec_ln_nw<EPI, 8>(h, a, ns, rpw, s);   // sixteen waves measured 6-30 % slower here
 }
 
+// Registers the float vectors first .. last_end (one run of the arena: the per-layer vectors are carved
+// back to back) as small-vector region `slot` of a warm-up; a run that is not the expected few KB is skipped.
+void set_aux(DecPrefetch& f, int slot, const float* first, const float* last_end) {
+  const ptrdiff_t bytes = reinterpret_cast<const unsigned char*>(last_end) - reinterpret_cast<const unsigned char*>(first);
+  if (!f.ptr || bytes <= 0 || bytes > (ptrdiff_t)1 << 20 || bytes % 16 != 0) return;
+  f.aux[slot] = reinterpret_cast<const unsigned char*>(first);
+  f.aux_bytes[slot] = (unsigned)bytes;
+}
+
 // Warm-up descriptor (see DecPrefetch) for the weights [N, K] of the LayerNorm-prologue GEMM that runs next.
 DecPrefetch prefetch_for(const ErnieHandle* h, const half_t* Wp, int N, int K, int B) {
   DecPrefetch f{};
@@ -471,10 +480,7 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
     o.B = B; o.Wp = L.wo; o.N = d; o.K = d; o.a16 = h->O; o.rout = h->r_out;
     // FFN1 comes next: its weights, and bo, b1, b2, ln1 scale / shift (contiguous in the arena)
     o.pf = prefetch_for(h, L.w1, f, d, B);
-    if (o.pf.ptr) {
-      o.pf.aux[0] = reinterpret_cast<const unsigned char*>(L.bo);
-      o.pf.aux_bytes[0] = (unsigned)(reinterpret_cast<const unsigned char*>(L.ln1_b + d) - o.pf.aux[0]);
-    }
+    set_aux(o.pf, 0, L.bo, L.ln1_b + d);
     rc |= launch_gemm_dec<EPI_RAW>(h, o, h->sk_out, s);
     DecGemmArgs f1{};
     f1.B = B; f1.eps = c.ln_eps; f1.Wp = L.w1; f1.N = f; f1.K = d; f1.r32 = h->r_out; f1.sk_in = h->sk_out;
@@ -487,12 +493,8 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
       // the next layer's QKV GEMM comes next: its weights, b2 and ln2 scale / shift of this layer (contiguous
       // from b2 to ln2_b), and the bqkv that the attention after it starts with
       f2.pf = prefetch_for(h, h->layers[l + 1].wqkv, 3 * d, d, B);
-      if (f2.pf.ptr) {
-        f2.pf.aux[0] = reinterpret_cast<const unsigned char*>(L.b2);
-        f2.pf.aux_bytes[0] = (unsigned)(reinterpret_cast<const unsigned char*>(L.ln2_b + d) - f2.pf.aux[0]);
-        f2.pf.aux[1] = reinterpret_cast<const unsigned char*>(h->layers[l + 1].bqkv);
-        f2.pf.aux_bytes[1] = (unsigned)(3 * d * 4);
-      }
+      set_aux(f2.pf, 0, L.b2, L.ln2_b + d);
+      set_aux(f2.pf, 1, h->layers[l + 1].bqkv, h->layers[l + 1].bqkv + 3 * d);
     }
     rc |= launch_gemm_dec<EPI_RAW>(h, f2, h->sk_f2, s);
   }
@@ -508,12 +510,8 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
     // the next step starts with layer 0's QKV GEMM on the embedding rows: its weights and the embedding
     // LayerNorm's scale / shift (contiguous) ride along with the projection
     z.pf = prefetch_for(h, h->layers[0].wqkv, 3 * d, d, B);
-    if (z.pf.ptr) {
-      z.pf.aux[0] = reinterpret_cast<const unsigned char*>(h->emb_g);
-      z.pf.aux_bytes[0] = (unsigned)(reinterpret_cast<const unsigned char*>(h->emb_b + d) - z.pf.aux[0]);
-      z.pf.aux[1] = reinterpret_cast<const unsigned char*>(h->layers[0].bqkv);
-      z.pf.aux_bytes[1] = (unsigned)(3 * d * 4);
-    }
+    set_aux(z.pf, 0, h->emb_g, h->emb_b + d);
+    set_aux(z.pf, 1, h->layers[0].bqkv, h->layers[0].bqkv + 3 * d);
   }
   rc |= launch_gemm_dec<EPI_ARGMAX>(h, z, 1, s);
   return rc ? ERNIE_EHIP : ERNIE_OK;
