@@ -260,11 +260,16 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_fused_kernel(const float*
                                                                     const int* __restrict__ cache_len, int H, int S,
                                                                     int d, half_t* __restrict__ O,
                                                                     const int* __restrict__ finished,   // [B] or null (no end-of-sequence id set)
-                                                                    const int* __restrict__ slot) {     // cache row of batch row b; null = b
+                                                                    const int* __restrict__ slot,       // cache row of batch row b; null = b
+                                                                    DecPrefetch warm) {                 // grid rows >= B only warm the L2 (small vectors)
   __shared__ float sm[NW][8][10];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int h = blockIdx.x, b = blockIdx.y;
+  if (b >= B) {      // uniform for the workgroup
+    dec_prefetch_run(warm, h + H * (b - B), h + H * b, tid, NW * 64);
+    return;
+  }
   const int ec = lane & 7, team = lane >> 3;
   if (finished && finished[b]) return;           // finished sequence: no cache stream, no append; its output row is not used
   const int cb = slot ? slot[b] : b;             // after a batch compaction the cache rows are no longer the batch rows

@@ -110,7 +110,6 @@ struct DecPrefetch {
 // idx = rank among the warming workgroups, wg_id = the workgroup's linear id in its grid (its XCD is wg_id % 8);
 // ranks 8 j .. 8 j + 7 must sit on 8 different XCDs (consecutive linear ids)
 __device__ __forceinline__ void dec_prefetch_run(const DecPrefetch& f, int idx, int wg_id, int tid, int nthreads) {
-  if (!f.ptr) return;
   const int x = wg_id & 7, j = idx >> 3, per = f.count >> 3;
   if (per <= 0) return;
 #pragma unroll
@@ -122,6 +121,7 @@ __device__ __forceinline__ void dec_prefetch_run(const DecPrefetch& f, int idx, 
       asm volatile("" ::"v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w));
     }
   }
+  if (!f.ptr) return;
   // XCD x runs the consumer's logical ids [lo, lo + cnt), i.e. a contiguous range of strips
   const int q = f.cons_grid >> 3, r = f.cons_grid & 7;
   const int lo = x * q + min(x, r), cnt = q + (x < r ? 1 : 0);

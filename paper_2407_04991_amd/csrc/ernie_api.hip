@@ -141,7 +141,7 @@ struct ErnieHandle {
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
   half_t *type_emb = nullptr, *head_w = nullptr;                      // optional variants, null when off
   float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
-  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2, dec_prefetch = 64, kv_prefetch = 1;
+  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2, dec_prefetch = 64, kv_prefetch = 1, big_warm = 16;
   int cand = 0;                  // argmax candidates per row left by the last projection   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   float* r_logits = nullptr;     // [2][max_batch][V'] fp32, large-batch projection only
@@ -191,17 +191,24 @@ half_t* vcache(const ErnieHandle* h, int layer) {
 // Decode attention: (waves, groups in flight per wave) chosen so that one batch of NW * U * 8 keys covers
 // the whole cache when the capacity allows it (a single memory round trip); long caches stream with 4 waves.
 void launch_attn_decode(const ErnieHandle* h, const float* rqkv, int sk_in, int B, const float* bqkv, half_t* kc,
-                        half_t* vc, hipStream_t s) {
+                        half_t* vc, hipStream_t s, DecPrefetch warm = DecPrefetch{}) {
   const int H = h->cfg.n_heads, S = h->cfg.max_seq, d = h->cfg.d_model;
+  // warming workgroups: whole extra grid rows, a multiple of 8 workgroups (consecutive ids, one per XCD)
+  int extra_rows = 0;
+  if (warm.count > 0 && (warm.aux[0] || warm.aux[1])) {
+    extra_rows = (warm.count + H - 1) / H;
+    while ((extra_rows * H) % 8 != 0) ++extra_rows;
+  }
+  warm.count = extra_rows * H;
   int v = h->attn_dec;
   // Measured on all benchmark shapes: two key groups in flight per wave (84 registers, five waves per SIMD)
   // beat four (115 registers) by 0.3-3 %; with thousands of short streams (B x H >= 1024, capacity <= 384
   // positions) two waves per workgroup beat four by another 1.7 %.
   if (v == 0) v = ((long)B * H >= 1024 && S <= 384) ? 5 : 4;
 #define ATTN_DEC_LAUNCH(NW, U, NT)                                                                                  \
-  hipLaunchKernelGGL((attn_decode_fused_kernel<NW, U, NT>), dim3(H, B), dim3(NW * 64), 0, s, rqkv, sk_in, B, bqkv, \
+  hipLaunchKernelGGL((attn_decode_fused_kernel<NW, U, NT>), dim3(H, B + extra_rows), dim3(NW * 64), 0, s, rqkv, sk_in, B, bqkv, \
                      kc, vc, h->lens, H, S, d, h->O, h->eos >= 0 ? h->finished : nullptr,                        \
-                     h->compacted ? h->slot : nullptr)
+                     h->compacted ? h->slot : nullptr, warm)
   if (v == 2) ATTN_DEC_LAUNCH(8, 3, false);
   else if (v == 3) ATTN_DEC_LAUNCH(8, 4, false);
   else if (v == 4) ATTN_DEC_LAUNCH(4, 2, true);
@@ -401,10 +408,11 @@ int launch_gemm_dec_ln(ErnieHandle* h, DecGemmArgs a, hipStream_t s) {
 }
 
 // Registers the float vectors first .. last_end (one run of the arena: the per-layer vectors are carved
-// back to back) as small-vector region `slot` of a warm-up; a run that is not the expected few KB is skipped.
+// back to back) as small-vector region `slot` of a warm-up; a run that is not the expected few KB (at most
+// 1 MiB, a multiple of 16 bytes) is skipped.
 void set_aux(DecPrefetch& f, int slot, const float* first, const float* last_end) {
   const ptrdiff_t bytes = reinterpret_cast<const unsigned char*>(last_end) - reinterpret_cast<const unsigned char*>(first);
-  if (!f.ptr || bytes <= 0 || bytes > (ptrdiff_t)1 << 20 || bytes % 16 != 0) return;
+  if (bytes <= 0 || bytes > (ptrdiff_t)1 << 20 || bytes % 16 != 0) return;
   f.aux[slot] = reinterpret_cast<const unsigned char*>(first);
   f.aux_bytes[slot] = (unsigned)bytes;
 }
@@ -480,7 +488,7 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
     o.B = B; o.Wp = L.wo; o.N = d; o.K = d; o.a16 = h->O; o.rout = h->r_out;
     // FFN1 comes next: its weights, and bo, b1, b2, ln1 scale / shift (contiguous in the arena)
     o.pf = prefetch_for(h, L.w1, f, d, B);
-    set_aux(o.pf, 0, L.bo, L.ln1_b + d);
+    if (o.pf.ptr) set_aux(o.pf, 0, L.bo, L.ln1_b + d);
     rc |= launch_gemm_dec<EPI_RAW>(h, o, h->sk_out, s);
     DecGemmArgs f1{};
     f1.B = B; f1.eps = c.ln_eps; f1.Wp = L.w1; f1.N = f; f1.K = d; f1.r32 = h->r_out; f1.sk_in = h->sk_out;
@@ -493,8 +501,10 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
       // the next layer's QKV GEMM comes next: its weights, b2 and ln2 scale / shift of this layer (contiguous
       // from b2 to ln2_b), and the bqkv that the attention after it starts with
       f2.pf = prefetch_for(h, h->layers[l + 1].wqkv, 3 * d, d, B);
-      set_aux(f2.pf, 0, L.b2, L.ln2_b + d);
-      set_aux(f2.pf, 1, h->layers[l + 1].bqkv, h->layers[l + 1].bqkv + 3 * d);
+      if (f2.pf.ptr) {
+        set_aux(f2.pf, 0, L.b2, L.ln2_b + d);
+        set_aux(f2.pf, 1, h->layers[l + 1].bqkv, h->layers[l + 1].bqkv + 3 * d);
+      }
     }
     rc |= launch_gemm_dec<EPI_RAW>(h, f2, h->sk_f2, s);
   }
@@ -510,8 +520,10 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
     // the next step starts with layer 0's QKV GEMM on the embedding rows: its weights and the embedding
     // LayerNorm's scale / shift (contiguous) ride along with the projection
     z.pf = prefetch_for(h, h->layers[0].wqkv, 3 * d, d, B);
-    set_aux(z.pf, 0, h->emb_g, h->emb_b + d);
-    set_aux(z.pf, 1, h->layers[0].bqkv, h->layers[0].bqkv + 3 * d);
+    if (z.pf.ptr) {
+      set_aux(z.pf, 0, h->emb_g, h->emb_b + d);
+      set_aux(z.pf, 1, h->layers[0].bqkv, h->layers[0].bqkv + 3 * d);
+    }
   }
   rc |= launch_gemm_dec<EPI_ARGMAX>(h, z, 1, s);
   return rc ? ERNIE_EHIP : ERNIE_OK;
@@ -586,7 +598,16 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
     launch_gemm_splitk(h, h->X, L.wqkv, B, 3 * d, d, h->r_qkv, sk_q, s);
     {
       ProfScope prof(h, ERNIE_PROF_ATTN_DEC, s, 2.0 * (h->sum_len + (double)B * (h->steps + 1)) * d * 2.0, 0.0);
-      launch_attn_decode(h, h->r_qkv, sk_q, B, L.bqkv, kcache(h, l), vcache(h, l), s);
+      // the attention is the long kernel of the step: a few extra workgroups pull the small vectors that the
+      // row kernels and the FFN1 epilogue of this layer (bo .. ln2_b, contiguous) and the next attention
+      // (its bqkv) start with into every XCD's L2
+      DecPrefetch warm{};
+      if (h->big_warm > 0) {
+        warm.count = h->big_warm;
+        set_aux(warm, 0, L.bo, L.ln2_b + d);
+        if (l + 1 < c.n_layers) set_aux(warm, 1, h->layers[l + 1].bqkv, h->layers[l + 1].bqkv + 3 * d);
+      }
+      launch_attn_decode(h, h->r_qkv, sk_q, B, L.bqkv, kcache(h, l), vcache(h, l), s, warm);
     }
     launch_gemm_splitk(h, h->O, L.wo, B, d, d, h->r_out, sk_o, s);
     { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
@@ -983,6 +1004,7 @@ int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!h || !key) return ERNIE_EINVAL;
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "dec_nw16")) { h->dec_nw16 = value; return ERNIE_OK; }
+  if (!strcmp(key, "big_warm")) { if (value < 0 || value > 256) return ERNIE_EINVAL; h->big_warm = value; return ERNIE_OK; }
   if (!strcmp(key, "kv_prefetch")) { if (value < 0 || value > 2048) return ERNIE_EINVAL; h->kv_prefetch = value; return ERNIE_OK; }
   if (!strcmp(key, "dec_prefetch")) { if (value < 0 || value > 1024) return ERNIE_EINVAL; h->dec_prefetch = value; return ERNIE_OK; }
   if (!strcmp(key, "big_logits_gemm")) { h->big_logits_gemm = value != 0; return ERNIE_OK; }
