@@ -141,7 +141,7 @@ struct ErnieHandle {
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
   half_t *type_emb = nullptr, *head_w = nullptr;                      // optional variants, null when off
   float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
-  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2, dec_prefetch = 64, kv_prefetch = 1, big_warm = 16;
+  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2, dec_prefetch = 64, kv_prefetch = 1, big_warm = 16, pf_tile = 0;
   int cand = 0;                  // argmax candidates per row left by the last projection   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   float* r_logits = nullptr;     // [2][max_batch][V'] fp32, large-batch projection only
@@ -239,9 +239,10 @@ void launch_gemm_prefill(ErnieHandle* h, const half_t* A, const half_t* Wp, cons
   // 256 x 256 when there are at least two rounds of them over the 256 CUs, or a single round that fills at
   // least half the CUs (one tile per CU beats several rounds of smaller tiles); 128 x 128 when they fill the
   // chip one and a half times; otherwise 64 x 64 with BK = 64 (measured 3-15 % faster than 128 x 64 there).
-  if (tiles_256x256 >= 512 || (tiles_256x256 >= 128 && tiles_256x256 <= 256))
+  const int forced = h->pf_tile;          // test hook: 1 / 2 / 3 force the 256 / 128 / 64 tile
+  if (forced == 1 || (!forced && (tiles_256x256 >= 512 || (tiles_256x256 >= 128 && tiles_256x256 <= 256))))
     launch_gemm_prefill_t<4, 4, 2, 2, 32, 3>(A, Wp, bias, M, N, K, epi, s);
-  else if (tiles_128x128 >= 384) launch_gemm_prefill_t<2, 2, 2, 2, 32, 3>(A, Wp, bias, M, N, K, epi, s);
+  else if (forced == 2 || (!forced && tiles_128x128 >= 384)) launch_gemm_prefill_t<2, 2, 2, 2, 32, 3>(A, Wp, bias, M, N, K, epi, s);
   else launch_gemm_prefill_t<2, 2, 1, 1, 64, 3>(A, Wp, bias, M, N, K, epi, s);
 }
 
@@ -1004,6 +1005,7 @@ int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!h || !key) return ERNIE_EINVAL;
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "dec_nw16")) { h->dec_nw16 = value; return ERNIE_OK; }
+  if (!strcmp(key, "pf_tile")) { if (value < 0 || value > 3) return ERNIE_EINVAL; h->pf_tile = value; return ERNIE_OK; }
   if (!strcmp(key, "big_warm")) { if (value < 0 || value > 256) return ERNIE_EINVAL; h->big_warm = value; return ERNIE_OK; }
   if (!strcmp(key, "kv_prefetch")) { if (value < 0 || value > 2048) return ERNIE_EINVAL; h->kv_prefetch = value; return ERNIE_OK; }
   if (!strcmp(key, "dec_prefetch")) { if (value < 0 || value > 1024) return ERNIE_EINVAL; h->dec_prefetch = value; return ERNIE_OK; }

@@ -306,6 +306,32 @@ def test_large_batch_path_alternatives(E, vocab_kept, knobs):
     eng.close()
 
 
+def test_prefill_gemm_tile_shapes_agree(E):
+    """Every tile shape of the prefill GEMM (chosen by problem size, here forced: 256 x 256, 128 x 128, 64 x 64) meets
+    the oracle on a ragged batch whose packed token count spans several tiles with a partial last one and whose
+    widths are below one large tile, and all shapes give bit-identical logits (the contraction order per output
+    element does not depend on the tile)."""
+    B = 70
+    rng = np.random.default_rng(777)
+    lengths = [int(x) for x in rng.integers(3, 40, size=B)]
+    wl = _ragged_workload(lengths, max_pos=64, n_gen=2, vocab_kept=512)
+    ids, lens = wl.padded(0)
+    rows = [0, 33, B - 1]
+    orc = oracle_generate(wl, 0, rows, 2)
+    ref = None
+    for tile in (0, 1, 2, 3):
+        eng = E.engine_from_workload(wl, max_seq=max(lengths) + 2)
+        eng.tune("pf_tile", tile)
+        _say(f"[parity] prefill GEMM tile shape {tile}, {sum(lengths)} packed tokens")
+        toks, hid, lg = gpu_generate(eng, ids, lens, 2, {r: orc[r]["tokens"] for r in orc})
+        check_rows(orc, toks, hid, lg, f"pf-tile-{tile}")
+        if ref is None:
+            ref = lg
+        else:
+            assert np.array_equal(np.asarray(ref), np.asarray(lg)), f"tile shape {tile} changed the logits"
+        eng.close()
+
+
 def test_decode_tuning_variants_agree(E):
     """Every split-K setting and both decode paths meet the oracle and agree with each other closely."""
     wl = make_workload("tiny_affine")
