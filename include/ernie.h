@@ -142,8 +142,14 @@ int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* weights, c
  *
  * Resets the cache: sequence b then holds L_b positions.  Padded positions
  * are never visible as keys.
+ * The lengths reach the device through library-owned pinned memory.  Eager calls
+ * may follow each other without synchronisation (the call blocks only if the
+ * device is eight such copies behind).  A call captured into a graph bakes the
+ * lengths of capture time into the graph; its pinned copy stays valid for every
+ * replay until ernie_free, and a handle has room for eight captured calls of
+ * ernie_prefill / ernie_compact (then ERNIE_ECAPACITY).
  * Errors: ERNIE_EINVAL, ERNIE_ECAPACITY (B > max_batch, Lmax > max_seq,
- * Lmax > max_pos), ERNIE_EHIP.
+ * Lmax > max_pos, capture slots used up), ERNIE_EHIP.
  */
 int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax,
                   const int32_t* ids_dev, const int32_t* prompt_lens_host,
@@ -195,7 +201,8 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev,
  * returns).  Cache contents do not move (rows are reached through a device-side row map);
  * later decode steps run with B = n_keep and their outputs have n_keep rows.  A captured
  * graph of decode steps is tied to the batch size it was captured with.
- * Errors: ERNIE_ESEQUENCE (no prefill yet), ERNIE_EINVAL (bad list), ERNIE_EHIP.
+ * Errors: ERNIE_ESEQUENCE (no prefill yet), ERNIE_EINVAL (bad list), ERNIE_ECAPACITY (captured
+ * call, capture slots used up: see ernie_prefill), ERNIE_EHIP.
  *
  * ernie_plan_batches -- host-only: orders n requests by prompt length (ascending, equal
  * lengths in arrival order) and cuts the order greedily into batches of at most max_batch

@@ -149,12 +149,43 @@ struct ErnieHandle {
   int eos = -1;                  // end-of-sequence id (trimmed), -1 = none
   bool compacted = false;        // some row map entry differs from its index
   std::vector<int> row_len;      // host copy of the prompt lengths of the batch in flight
-  int* staging;          // pinned host: kStagingSlots x (max_batch + 1) ints
-  int staging_next;
+  // Pinned host staging for the small host arrays of prefill / compact: kStagingSlots slots used round-robin by
+  // eager calls (a slot is reused only after the copy that read it has executed: one event per slot), then
+  // kStagingSlots slots handed out once each to calls made under stream capture (a replayed graph reads its
+  // slot again, so it is never reused).  Each slot holds max_batch + 1 ints.
+  int* staging;
+  int staging_next, staging_captured;
+  hipEvent_t stage_ev[kStagingSlots];
+  bool stage_busy[kStagingSlots];
   // state of the batch in flight
   bool prefilled;
   int B, max_len, steps;
 };
+
+// A staging slot for one host -> device copy on stream `s`; *slot_out is the ring slot to pass to
+// stage_release after the copy has been enqueued, or -1 for a capture slot.  Returns null when the stream is
+// capturing and the capture slots are used up.
+int* stage_acquire(ErnieHandle* h, hipStream_t s, int* slot_out) {
+  const size_t pitch = (size_t)h->cfg.max_batch + 1;
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &st) != hipSuccess) { (void)hipGetLastError(); st = hipStreamCaptureStatusNone; }
+  if (st == hipStreamCaptureStatusActive) {
+    *slot_out = -1;
+    if (h->staging_captured >= kStagingSlots) return nullptr;
+    return h->staging + (size_t)(kStagingSlots + h->staging_captured++) * pitch;
+  }
+  const int slot = h->staging_next;
+  h->staging_next = (slot + 1) % kStagingSlots;
+  if (h->stage_busy[slot]) { (void)hipEventSynchronize(h->stage_ev[slot]); h->stage_busy[slot] = false; }
+  *slot_out = slot;
+  return h->staging + (size_t)slot * pitch;
+}
+
+void stage_release(ErnieHandle* h, hipStream_t s, int slot) {
+  if (slot < 0) return;
+  if (hipEventRecord(h->stage_ev[slot], s) == hipSuccess) h->stage_busy[slot] = true;
+  else { (void)hipGetLastError(); (void)hipStreamSynchronize(s); }      // no event: wait for the copy instead
+}
 
 namespace {
 
@@ -717,13 +748,17 @@ int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* w, const E
   h->finished = I32(plan.finished); h->slot = I32(plan.slot); h->keep = I32(plan.keep);
   h->r_logits = F32(plan.r_logits);
   h->prefilled = false; h->B = 0; h->max_len = 0; h->steps = 0; h->sum_len = h->sum_len2 = 0.0;
-  h->staging = nullptr; h->staging_next = 0;
+  h->staging = nullptr; h->staging_next = 0; h->staging_captured = 0;
+  for (int i = 0; i < kStagingSlots; ++i) { h->stage_ev[i] = nullptr; h->stage_busy[i] = false; }
 
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (configure_kernels() != ERNIE_OK ||
-      hipHostMalloc(reinterpret_cast<void**>(&h->staging), sizeof(int) * kStagingSlots * (cfg->max_batch + 1),
-                    hipHostMallocDefault) != hipSuccess) {
-    delete h;
+  bool host_ok = configure_kernels() == ERNIE_OK &&
+                 hipHostMalloc(reinterpret_cast<void**>(&h->staging),
+                               sizeof(int) * 2 * kStagingSlots * (cfg->max_batch + 1), hipHostMallocDefault) == hipSuccess;
+  for (int i = 0; host_ok && i < kStagingSlots; ++i)
+    host_ok = hipEventCreateWithFlags(&h->stage_ev[i], hipEventDisableTiming) == hipSuccess;
+  if (!host_ok) {
+    ernie_free(h);
     return ERNIE_EHIP;
   }
 
@@ -768,8 +803,7 @@ int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* w, const E
     cvt_into(var->out_bias, h->out_bias, V, s);
   }
   if (launch_status() != ERNIE_OK || !copies_ok) {
-    (void)hipHostFree(h->staging);
-    delete h;
+    ernie_free(h);
     return ERNIE_EHIP;
   }
   *out = h;
@@ -792,12 +826,14 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
   }
 
   hipStream_t s = static_cast<hipStream_t>(stream);
-  int* stage = h->staging + (size_t)h->staging_next * (c.max_batch + 1);
-  h->staging_next = (h->staging_next + 1) % kStagingSlots;
+  int stage_slot;
+  int* stage = stage_acquire(h, s, &stage_slot);
+  if (!stage) return ERNIE_ECAPACITY;
   stage[0] = 0;
   for (int b = 0; b < B; ++b) stage[b + 1] = stage[b] + prompt_lens_host[b];
   const int T = stage[B];
   HIP_OK(hipMemcpyAsync(h->cu, stage, sizeof(int) * (B + 1), hipMemcpyHostToDevice, s));
+  stage_release(h, s, stage_slot);
 
   const int d = c.d_model, f = c.d_ffn, H = c.n_heads, S = c.max_seq;
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); hipLaunchKernelGGL(token_map_kernel, dim3((T + 255) / 256), dim3(256), 0, s, h->cu, B, T, h->tok_seq, h->tok_pos,
@@ -900,12 +936,15 @@ int ernie_compact(ErnieHandle* h, int32_t n_keep, const int32_t* keep_rows_host,
     if (r < 0 || r >= h->B || (i > 0 && r <= keep_rows_host[i - 1])) return ERNIE_EINVAL;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  int* stage = h->staging + (size_t)h->staging_next * (h->cfg.max_batch + 1);
-  h->staging_next = (h->staging_next + 1) % kStagingSlots;
   bool identity = true;
-  for (int i = 0; i < n_keep; ++i) { stage[i] = keep_rows_host[i]; identity &= (keep_rows_host[i] == i); }
+  for (int i = 0; i < n_keep; ++i) identity &= (keep_rows_host[i] == i);
   if (!identity) {
+    int stage_slot;
+    int* stage = stage_acquire(h, s, &stage_slot);
+    if (!stage) return ERNIE_ECAPACITY;
+    for (int i = 0; i < n_keep; ++i) stage[i] = keep_rows_host[i];
     HIP_OK(hipMemcpyAsync(h->keep, stage, sizeof(int) * n_keep, hipMemcpyHostToDevice, s));
+    stage_release(h, s, stage_slot);
     hipLaunchKernelGGL(batch_compact_kernel, dim3(1), dim3(256), 0, s, h->keep, n_keep, h->lens, h->tok_prev,
                        h->finished, h->slot);
     h->compacted = true;
@@ -949,6 +988,10 @@ int ernie_plan_batches(const int32_t* lens_host, int32_t n, int32_t max_batch, i
 
 void ernie_free(ErnieHandle* h) {
   if (!h) return;
+  for (int i = 0; i < kStagingSlots; ++i) {
+    if (h->stage_busy[i]) (void)hipEventSynchronize(h->stage_ev[i]);     // the copy still reads the pinned slot
+    if (h->stage_ev[i]) (void)hipEventDestroy(h->stage_ev[i]);
+  }
   if (h->staging) (void)hipHostFree(h->staging);
   for (auto& sl : h->prof.slots) { (void)hipEventDestroy(sl.a); (void)hipEventDestroy(sl.b); }
   delete h;

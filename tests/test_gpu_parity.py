@@ -306,6 +306,64 @@ def test_large_batch_path_alternatives(E, vocab_kept, knobs):
     eng.close()
 
 
+def test_host_lengths_survive_unsynchronised_calls_and_graph_replays(E):
+    """The prompt lengths travel through library-owned pinned memory.  (a) Twenty prefills of two alternating
+    ragged batches issued back to back without synchronisation: the last one decides the state.  (b) A prefill
+    captured into a graph keeps reading the lengths of capture time, however many eager calls with other lengths
+    follow.  (c) The ninth captured prefill on one handle is refused with the capacity error."""
+    import torch
+    la = [5, 17, 9, 30, 3, 12]
+    lb = [30, 4, 22, 7, 15, 6]
+    wl_a = _ragged_workload(la, max_pos=64, n_gen=3, vocab_kept=512)
+    ids_a, _ = wl_a.padded(0)
+    rng = np.random.default_rng(99)
+    ids_b = rng.integers(0, 512, size=ids_a.shape).astype(np.int32)
+    eng = E.engine_from_workload(wl_a, max_seq=40)
+    ref = E.engine_from_workload(wl_a, max_seq=40)
+    dev_a, dev_b = torch.as_tensor(ids_a).cuda(), torch.as_tensor(ids_b).cuda()
+    tok = torch.empty(len(la), dtype=torch.int32, device="cuda:0")
+    tok_ref = torch.empty_like(tok)
+    _say("[parity] twenty unsynchronised prefills")
+    for i in range(20):
+        ids, lens = (dev_a, la) if i % 2 else (dev_b, lb)
+        assert E.ernie_prefill(eng.handle, len(lens), ids.shape[1], ids, lens, None, None, tok) == 0
+    assert E.ernie_decode_step(eng.handle, None, None, None, tok) == 0
+    assert E.ernie_prefill(ref.handle, len(la), dev_a.shape[1], dev_a, la, None, None, tok_ref) == 0
+    assert E.ernie_decode_step(ref.handle, None, None, None, tok_ref) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(tok, tok_ref)
+    lens_dev = torch.empty(len(la), dtype=torch.int32, device="cuda:0")
+    assert E.ernie_batch_state(eng.handle, lens_dev, None) == 0
+    assert lens_dev.cpu().tolist() == [x + 1 for x in la]
+
+    _say("[parity] captured prefill replayed after ten eager prefills with other lengths")
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    tok_g = torch.empty_like(tok)
+    with torch.cuda.graph(g, stream=side):
+        assert E.ernie_prefill(eng.handle, len(la), dev_a.shape[1], dev_a, la, None, None, tok_g) == 0
+        assert E.ernie_decode_step(eng.handle, None, None, None, tok_g) == 0
+    for i in range(10):
+        assert E.ernie_prefill(eng.handle, len(lb), dev_b.shape[1], dev_b, lb, None, None, tok) == 0
+    torch.cuda.synchronize()
+    for _ in range(2):
+        tok_g.zero_()
+        with torch.cuda.stream(side):
+            g.replay()
+        side.synchronize()
+        assert torch.equal(tok_g, tok_ref)
+
+    _say("[parity] capture slots run out")
+    codes = []
+    g2 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g2, stream=side):
+        for i in range(8):
+            codes.append(E.ernie_prefill(eng.handle, len(la), dev_a.shape[1], dev_a, la, None, None, tok_g))
+    assert codes == [0] * 7 + [E.ERNIE_ECAPACITY], codes
+    torch.cuda.synchronize()
+    eng.close(); ref.close()
+
+
 def test_prefill_gemm_tile_shapes_agree(E):
     """Every tile shape of the prefill GEMM (chosen by problem size, here forced: 256 x 256, 128 x 128, 64 x 64) meets
     the oracle on a ragged batch whose packed token count spans several tiles with a partial last one and whose
