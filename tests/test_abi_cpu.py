@@ -158,3 +158,14 @@ def test_job_entry_points_reject_null_handles():
     assert lib.ernie_job_workspace_bytes(None, 4) == 0
     assert lib.ernie_get_config(None, None) == E.ERNIE_EINVAL
     assert lib.ernie_run_job(None, None, None, None) == E.ERNIE_EINVAL
+
+
+def test_missing_library_and_missing_gpu_fail_loudly(tmp_path):
+    """There is no CPU fallback: a missing shared library raises on load, and without a GPU the engine refuses to start."""
+    import torch
+    from synth import make_workload
+    with pytest.raises(FileNotFoundError, match="no CPU fallback"):
+        E.load_library(str(tmp_path / "libernie_hip_absent.so"))
+    if not torch.cuda.is_available():
+        with pytest.raises(RuntimeError, match="needs a GPU"):
+            E.engine_from_workload(make_workload("tiny"))
