@@ -618,8 +618,8 @@ const half_t* apply_head(ErnieHandle* h, const half_t* x, int B, hipStream_t s) 
 }
 
 // Larger batches (B > 64): split-K MFMA GEMMs write fp32 partials; the attention prologue and two row
-// kernels add partials + bias (+ residual) and apply LayerNorm / GELU.  8 launches per layer; the step is
-// bound by the cache stream of the attention.
+// kernels add partials + bias (+ residual) and apply LayerNorm; FFN1 keeps its contraction whole with bias +
+// GELU in its epilogue.  7 launches per layer; the cache stream of the attention is the largest share of the step.
 int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipStream_t s) {
   const ErnieConfig& c = h->cfg;
   const int B = h->B, d = c.d_model, f = c.d_ffn;
