@@ -152,6 +152,41 @@ def measure_pass(E, eng, ids_np, lens, N, steps, warmup, graph=1, prof_passes=3)
             "prof": prof, "last_tokens": tok_host}
 
 
+def vendor_gemm_context(sh, T, ours):
+    """Context, not product: the vendor GEMM on the four GEMM shapes of one layer of the prefill (T packed tokens),
+    operands drawn like the workload's (activations ~ N(0, 1), weights ~ N(0, 0.02^2)), no bias and no epilogue,
+    beside the per-layer time of this library's prefill GEMMs (which carry bias, GELU, residual and the cache
+    scatter in their epilogues)."""
+    import torch
+    d, f = sh.d_model, sh.d_ffn
+    shapes, rows, total_us, total_fl = [(3 * d, d), (d, d), (f, d), (d, f)], [], 0.0, 0.0
+    gen = torch.Generator(device="cuda:0").manual_seed(1)
+    for rep in range(2):                                  # the first round warms the library's kernel selection
+        rows, total_us, total_fl = [], 0.0, 0.0
+        for N, K in shapes:
+            x = torch.randn(T, K, device="cuda:0", dtype=torch.float16, generator=gen)
+            w = (0.02 * torch.randn(N, K, device="cuda:0", generator=gen)).half()
+            for _ in range(3):
+                y = torch.nn.functional.linear(x, w)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            iters = 20
+            e0.record()
+            for _ in range(iters):
+                y = torch.nn.functional.linear(x, w)
+            e1.record(); torch.cuda.synchronize()
+            us, fl = e0.elapsed_time(e1) * 1e3 / iters, 2.0 * T * N * K
+            rows.append({"M": T, "N": N, "K": K, "us": us, "tflops": fl / us / 1e6})
+            total_us += us; total_fl += fl
+            del x, w, y
+    out = {"what": "torch.nn.functional.linear fp16, no epilogue, same box", "per_shape": rows,
+           "layer_us": total_us, "layer_tflops": total_fl / total_us / 1e6}
+    if ours:
+        out["this_library_layer_us"] = ours["ms_per_pass"] * 1e3 / sh.n_layers
+        out["this_library_tflops"] = ours["achieved"]
+    return out
+
+
 def trim_sweep(args):
     """Vocabulary trimming measured end to end at the ERNIE-base shape: the trimming kernels on a synthetic Zipf
     corpus, then the generation pass for several kept-row counts V' (kept rows chosen, table trimmed and prompts
@@ -377,6 +412,9 @@ def main():
     ap.add_argument("--shape", action="append", default=[], help="override an integer field of the workload shape, "
                     "key=value (repeatable; e.g. prompt_len=8): for sensitivity runs, not the headline number")
     ap.add_argument("--tune", action="append", default=[], help="decode tuning knob, key=value (repeatable)")
+    ap.add_argument("--vendor-gemm", action="store_true", help="context only: also time the vendor GEMM "
+                    "(torch.nn.functional.linear, fp16, no epilogue) on the four prefill GEMM shapes of the workload "
+                    "and report it beside this library's prefill GEMM family")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (sequences shard by batch with no collective); "
@@ -467,6 +505,8 @@ def main():
         dst.copy_(src)                      # one elementwise copy kernel: reads n bytes, writes n bytes
         torch.cuda.synchronize()
         out["calib_copy_bytes"] = n
+    if args.vendor_gemm:
+        out["vendor_gemm_context"] = vendor_gemm_context(sh, int(np.sum(lens)), kernels.get("gemm_prefill"))
     if not args.no_cpu_baseline:
         rows = list(range(min(args.cpu_rows, B)))
         out["cpu_baseline"] = cpu_baseline(wl, rows, N)

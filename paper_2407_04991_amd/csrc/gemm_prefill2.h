@@ -1,9 +1,12 @@
 // Prefill GEMM on FP16 MFMA, asynchronous-copy pipeline:
 //   C[M, N] = A[M, K] * W[N, K]^T  (+ fused epilogue), fp32 accumulation.
 //
-// One workgroup (WGM x WGN waves, each TM x TN MFMA 32x32x16 tiles) owns a
+// One workgroup (WGM x WGN waves, each 32 TM x 32 TN outputs as 2 TM x 2 TN tiles of the 16x16x32 MFMA) owns a
 // (32 WGM TM) x (32 WGN TN) output tile and walks K in steps of BK through an
-// S-stage ring in LDS.  Operands travel global -> LDS
+// S-stage ring in LDS.  The 16x16x32 instruction is used because it moves a third fewer register bytes per
+// flop than 32x32x16 (accumulators are read and written once per 32 instead of per 16 of K): in a
+// register-only loop on random operands, where the chip is power-limited, it sustains 1.95 PFLOP/s against
+// 1.45.  Operands travel global -> LDS
 // directly (global_load_lds_dwordx4: lane l's 16 bytes land at LDS base + 16 l),
 // so no registers are spent on staging and S - 1 stages stay in flight per wave.
 //
@@ -12,8 +15,9 @@
 //            quarter-wave's 16-byte fragment reads fall on 64 distinct banks.  A
 //            load instruction covers 16 (BK = 32) or 8 (BK = 64) whole rows:
 //            the lanes of one row read one contiguous 64/128-byte run.
-//   W stage  the packed weight is already in fragment order: 1 KiB fragments
-//            are copied verbatim and read back lane-contiguously.
+//   W stage  the packed weight (1 KiB fragments of 32 columns x 16 k, see common.h) is copied verbatim; a
+//            16-column x 32-k operand is one half (columns) of two consecutive fragments (k), still one
+//            16-byte read per lane, every quarter-wave on 256 contiguous bytes.
 //
 // Rows >= M and n-tiles past the end are clamped to the last valid one (their
 // products land in accumulator entries the epilogue never stores).
@@ -66,8 +70,7 @@ struct GemmPipe {
   static_assert(kAInstr >= 1 && kBM % (kRowsPerInstr * kWaves) == 0, "A tile must split evenly over the waves");
 };
 
-// DBG (measurement builds only, 0 in the library): 1 = no operand copies after the first stages,
-// 2 = fragments read from LDS once, 4 = no barrier / waits, 8 = no A copies, 16 = no W copies.
+// DBG (measurement builds only, 0 in the library): 8 = no A copies, 16 = no W copies.
 template <int WGM, int WGN, int TM, int TN, int BK, int S, class Epi, int DBG = 0>
 __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_prefill2_kernel(const half_t* __restrict__ A,
                                                             const half_t* __restrict__ Wp,
@@ -89,10 +92,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
   const int kbeg = blockIdx.y * steps * BK;
 
   // bias of this lane's TN columns: fetched now, so that the epilogue does not start with a memory round trip
-  float bvv[TN];
+  float bvv[2 * TN];
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int mycol = n0 + wn * 32 * TN + j * 32 + (lane & 31);
+  for (int j = 0; j < 2 * TN; ++j) {
+    const int mycol = n0 + wn * 32 * TN + j * 16 + (lane & 15);
     bvv[j] = (mycol < N) ? bias[mycol] : 0.f;
   }
 
@@ -129,60 +132,59 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
     }
   };
 
-  floatx16 acc[TM][TN];
+  floatx4 acc[2 * TM][2 * TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < 2 * TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+    for (int j = 0; j < 2 * TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
 
-  // ---- fragment read offsets (bytes) inside a stage
-  int a_off[TM], a_swz[TM];
+  // ---- fragment read offsets (bytes) inside a stage.  A operand of sub-tile i: lane l holds row 16 i + l % 16,
+  // k = 8 (l / 16) .. + 7 of a 32-wide k step; W operand of sub-tile j: column 16 j + l % 16, same k.
+  const int l16 = lane & 15, kq = lane >> 4;
+  int a_off[2 * TM], a_swz[2 * TM];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int r = wm * 32 * TM + i * 32 + (lane & 31);
+  for (int i = 0; i < 2 * TM; ++i) {
+    const int r = wm * 32 * TM + i * 16 + l16;
     a_off[i] = r * P::kRowBytes;
     a_swz[i] = (r / P::kRowsPer256) % P::kChunks;
   }
-  const int hh = lane >> 5;
+  // 16-k fragment t of a 32-k step holds k-quarters 2 t and 2 t + 1 in its two 512-byte halves
+  const int b_lane = (kq >> 1) * 1024 + (kq & 1) * 512 + l16 * 16;
 
 #pragma unroll
   for (int s = 0; s < S - 1; ++s)
     if (s < steps) issue(s, s);
 
-  half8 fa[2][TM], fb[2][TN];
   for (int step = 0; step < steps; ++step) {
     // stage `step` has landed once at most (S - 2) later stages of this wave are still in flight
-    constexpr int kInFlight = ((DBG & 8) ? 0 : P::kAInstr) + ((DBG & 16) ? 0 : P::kBInstr);   // = P::kLoads in the library
-    if constexpr (!(DBG & 4)) { if (step + S - 2 < steps) wait_vmcnt<(S - 2) * kInFlight>(); else wait_vmcnt<0>(); }
+    if (step + S - 2 < steps) wait_vmcnt<(S - 2) * P::kLoads>(); else wait_vmcnt<0>();
     // Plain s_barrier: __syncthreads() would add a fence that drains vmcnt to 0 and with it the pipeline.
     // Each wave has waited for its own share of the stage above; LDS reads below are issued after the
     // barrier in program order, and the compiler barriers keep them there.
     asm volatile("" ::: "memory");
-    if constexpr (!(DBG & 4)) __builtin_amdgcn_s_barrier();     // every wave's share of the stage is visible; the stage computed last step is free
+    __builtin_amdgcn_s_barrier();     // every wave's share of the stage is visible; the stage computed last step is free
     asm volatile("" ::: "memory");
-    if constexpr (!(DBG & 1)) if (step + S - 1 < steps) issue((step + S - 1) % S, step + S - 1);
+    if (step + S - 1 < steps) issue((step + S - 1) % S, step + S - 1);
 
     const unsigned char* sa = smem_raw + (step % S) * P::kStage;
     const unsigned char* sb = sa + P::kAStage;
-    // fragments of k-substep ks + 1 are read from LDS while the MFMAs of substep ks run
-    auto read_frags = [&](int ks, int buf) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        fa[buf][i] = *reinterpret_cast<const half8*>(sa + a_off[i] + (((2 * ks + hh) ^ a_swz[i]) * 16));
+    for (int kk = 0; kk < BK / 32; ++kk) {
+      half8 fa[2 * TM], fb[2 * TN];
+      // the reads return in order: the first row of products can start after two of them
+      fa[0] = *reinterpret_cast<const half8*>(sa + a_off[0] + (((4 * kk + kq) ^ a_swz[0]) * 16));
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        fb[buf][j] = *reinterpret_cast<const half8*>(sb + ((wn * TN + j) * (BK / 16) + ks) * 1024 + lane * 16);
-    };
-    if (!(DBG & 2) || step == 0) read_frags(0, 0);
+      for (int j = 0; j < 2 * TN; ++j)
+        fb[j] = *reinterpret_cast<const half8*>(sb + ((wn * TN + (j >> 1)) * (BK / 16) + 2 * kk) * 1024 + (j & 1) * 256 + b_lane);
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      if constexpr (!(DBG & 2)) if (ks + 1 < BK / 16) read_frags(ks + 1, (ks + 1) & 1);
+      for (int i = 1; i < 2 * TM; ++i)
+        fa[i] = *reinterpret_cast<const half8*>(sa + a_off[i] + (((4 * kk + kq) ^ a_swz[i]) * 16));
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < 2 * TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(fa[ks & 1][i], fb[ks & 1][j], acc[i][j]);
+        for (int j = 0; j < 2 * TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
   }
 
@@ -190,8 +192,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
   // (lane = column on the way in, 8 consecutive columns of one row on the way out), so that the
   // epilogue functor stores runs of 8 columns instead of single elements.
   __syncthreads();                       // all waves have finished reading the last stage
-  float* patch = reinterpret_cast<float*>(smem_raw) + wave * (32 * 33);
-  static_assert(P::kLdsBytes >= P::kWaves * 32 * 33 * 4, "the stage ring must hold one patch per wave");
+  constexpr int kPitch = 36;             // floats: the four row groups of a sub-tile land 16 banks apart
+  float* patch = reinterpret_cast<float*>(smem_raw) + wave * (32 * kPitch);
+  static_assert(P::kLdsBytes >= P::kWaves * 32 * kPitch * 4, "the stage ring must hold one patch per wave");
   // Interior tiles (the vast majority) take a copy of the epilogue without bounds checks: with the per-store
   // branches gone the compiler can count the outstanding loads and stores exactly, instead of draining them
   // at every join.
@@ -214,18 +217,23 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int colbase = n0 + wn * 32 * TN + j * 32;
-      const float bv = bvv[j];
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
+        // sub-tile (si, sj) of the 32 x 32 block: lane holds column 16 sj + l % 16 of rows 16 si + 4 (l / 16) + v
 #pragma unroll
-        for (int v = 0; v < 16; ++v) patch[mfma32_row(v, lane) * 33 + (lane & 31)] = acc[i][j][v] + bv;
+        for (int si = 0; si < 2; ++si)
+#pragma unroll
+          for (int sj = 0; sj < 2; ++sj)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              patch[(si * 16 + 4 * kq + v) * kPitch + sj * 16 + l16] = acc[2 * i + si][2 * j + sj][v] + bvv[2 * j + sj];
         // same-wave LDS traffic: the compiler's lgkmcnt waits order the reads after the writes
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const int r = t * 16 + (lane >> 2), c8 = (lane & 3) * 8;
           float o[8];
 #pragma unroll
-          for (int q = 0; q < 8; ++q) o[q] = patch[r * 33 + c8 + q];
+          for (int q = 0; q < 8; ++q) o[q] = patch[r * kPitch + c8 + q];
           const int row = m0 + wm * 32 * TM + i * 32 + r, col = colbase + c8;
           if (!kChecked || (row < M && col < N)) {
             if constexpr (epi_has_load<Epi>::value) epi.store8(row, col, o, pre[(j * TM + i) * 2 + t]);
