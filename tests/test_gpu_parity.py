@@ -364,6 +364,31 @@ def test_host_lengths_survive_unsynchronised_calls_and_graph_replays(E):
     eng.close(); ref.close()
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13, 14, 15, 16, 17, 18])
+def test_seeded_random_small_configurations(E, seed):
+    """Model width, FFN width, depth, batch, ragged lengths, kept-row count and generated length drawn from a seed:
+    shapes that no named configuration has (one head, widths that are not powers of two, a single layer, batches
+    on both decode paths), three sampled rows against the oracle."""
+    rng = np.random.default_rng(seed)
+    heads = int(rng.choice([1, 2, 3, 5]))
+    d_ffn = int(rng.choice([64, 192, 320, 512]))
+    layers = int(rng.integers(1, 4))
+    B = int(rng.choice([1, 2, 7, 33, 64, 65, 90]))
+    lengths = [int(x) for x in rng.integers(1, 45, size=B)]
+    n_gen = int(rng.integers(1, 5))
+    vocab_kept = int(rng.integers(65, 700))
+    wl = _ragged_workload(lengths, max_pos=64, n_gen=n_gen, vocab_kept=vocab_kept, n_layers=layers,
+                          d_model=64 * heads, n_heads=heads, d_ffn=d_ffn)
+    eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
+    ids, lens = wl.padded(0)
+    rows = sorted({0, B // 2, B - 1})
+    _say(f"[parity] seed {seed}: layers={layers} d={64 * heads} ffn={d_ffn} B={B} V'={vocab_kept} n_gen={n_gen}")
+    orc = oracle_generate(wl, 0, rows, n_gen)
+    toks, hid, lg = gpu_generate(eng, ids, lens, n_gen, {r: orc[r]["tokens"] for r in orc})
+    check_rows(orc, toks, hid, lg, f"seeded-{seed}")
+    eng.close()
+
+
 def test_prefill_gemm_tile_shapes_agree(E):
     """Every tile shape of the prefill GEMM (chosen by problem size, here forced: 256 x 256, 128 x 128, 64 x 64) meets
     the oracle on a ragged batch whose packed token count spans several tiles with a partial last one and whose
