@@ -152,6 +152,29 @@ def measure_pass(E, eng, ids_np, lens, N, steps, warmup, graph=1, prof_passes=3)
             "prof": prof, "last_tokens": tok_host}
 
 
+def graph_node_floor_us(n_nodes=256, reps=20):
+    """Context for the launch-bound decode kernels: time per node of a HIP graph of `n_nodes` dependent launches of a
+    one-element kernel (what a kernel of the decode chain costs before it moves a byte)."""
+    import torch
+    x = torch.zeros(1, device="cuda:0")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        x.add_(1.0)
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        for _ in range(n_nodes):
+            x.add_(1.0)
+    with torch.cuda.stream(side):
+        g.replay(); side.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(side)
+        for _ in range(reps):
+            g.replay()
+        e1.record(side); side.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (reps * n_nodes)
+
+
 def vendor_gemm_context(sh, T, ours):
     """Context, not product: the vendor GEMM on the four GEMM shapes of one layer of the prefill (T packed tokens),
     operands drawn like the workload's (activations ~ N(0, 1), weights ~ N(0, 0.02^2)), no bias and no epilogue,
@@ -495,6 +518,8 @@ def main():
         "prefill_frac_of_mfma_peak": pf / (pre * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS,
         "decode_step_ms": dec_ms_mean, "decode_tokens_per_s": B / (dec_ms_mean * 1e-3),
         "decode_step_algorithmic_gbs": dec_gbs, "decode_step_frac_of_hbm_peak": dec_gbs / HBM_PEAK_GBS,
+        "decode_launches_per_step": sum(k["launches_per_pass"] for n, k in kernels.items() if phase[n] == "decode") / (N - 1),
+        "graph_node_floor_us": graph_node_floor_us(),
         "kernels": kernels,
     }
     if args.calib_copy_mb > 0:
