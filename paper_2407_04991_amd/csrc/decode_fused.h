@@ -134,17 +134,21 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_kernel(DecGemmArgs p) {
   {
     const int chunks = kslice / 8;
     const int total = MT * 32 * chunks;
+    // piece id -> (row, chunk) by stepping: one division per batch instead of one per piece (the divisions were
+    // a fifth of this kernel's code)
+    const int step_r = (NW * 64) / chunks, step_c = (NW * 64) - step_r * chunks;
     auto copy_batch = [&](int id0, auto pieces_tag) {
       constexpr int kPieces = decltype(pieces_tag)::value;
       half8 v[kPieces];
       int dst[kPieces];
+      int r = id0 / chunks, ch = id0 - r * chunks;
 #pragma unroll
       for (int q = 0; q < kPieces; ++q) {
-        int id = id0 + q * NW * 64;
-        if (id >= total) id -= total;                      // < total: a batch never spans more than the tile twice
-        const int r = id / chunks, ch = id - r * chunks;
+        if (r >= MT * 32) r -= MT * 32;                    // past the end: wraps into the tile (a batch never spans it twice)
         dst[q] = r * pitch + ch * 8;
         v[q] = *reinterpret_cast<const half8*>(p.a16 + (size_t)min(r, B - 1) * K + k0 + ch * 8);
+        r += step_r; ch += step_c;
+        if (ch >= chunks) { ch -= chunks; r += 1; }
       }
 #pragma unroll
       for (int q = 0; q < kPieces; ++q)
