@@ -3,7 +3,7 @@
 The decode-step kernels evaluate erf by formula 7.1.26 of Abramowitz & Stegun instead of calling the library
 routine.  The coefficients are read out of the kernel source, the formula is evaluated in fp32 exactly as the
 device code does, and the result is compared with scipy's erf: the GELU built on it must stay three orders of
-magnitude below the fp16 rounding of its output, as the design doc states.
+magnitude below the fp16 rounding of its output (half an ulp of fp16 at |y| = 1 is 4.9e-4).
 """
 import os
 import re
