@@ -10,11 +10,13 @@
 // directly (global_load_lds_dwordx4: lane l's 16 bytes land at LDS base + 16 l),
 // so no registers are spent on staging and S - 1 stages stay in flight per wave.
 //
-//   A stage  32 WGM TM rows x BK halves, row-major, 16-byte chunks XOR-swizzled
-//            (slot = chunk ^ ((row / rows_per_256B) % chunks_per_row)) so that a
-//            quarter-wave's 16-byte fragment reads fall on 64 distinct banks.  A
-//            load instruction covers 16 (BK = 32) or 8 (BK = 64) whole rows:
-//            the lanes of one row read one contiguous 64/128-byte run.
+//   A stage  32 WGM TM rows x BK halves.  BK = 64: row-major rows of 128 bytes, 16-byte chunk c of row r in
+//            slot c ^ ((r / 2) % 8).  BK = 32: the 16 rows x 4 chunks that one load instruction covers are
+//            permuted inside their 1 KiB block so that every chunk sits on the banks it would have in rows of
+//            128 bytes (position ((r / 2) % 4) * 16 + (r % 2) * 8 + (c ^ ((r / 2) % 8)), in 16-byte units).
+//            Both are conflict-free for the 16 x 32 operand read (lane -> row lane % 16, chunk lane / 16),
+//            measured at 230 B/clk/CU; plain rows of 64 bytes with a 4-way XOR ran that read at half rate.
+//            The lanes that fetch one row are adjacent, so a row is still one contiguous 64/128-byte run.
 //   W stage  the packed weight (1 KiB fragments of 32 columns x 16 k, see common.h) is copied verbatim; a
 //            16-column x 32-k operand is one half (columns) of two consecutive fragments (k), still one
 //            16-byte read per lane, every quarter-wave on 256 contiguous bytes.
@@ -103,8 +105,18 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
   const half_t* a_src[P::kAInstr];
 #pragma unroll
   for (int i = 0; i < P::kAInstr; ++i) {
-    const int r = (wave * P::kAInstr + i) * P::kRowsPerInstr + lane / P::kChunks;     // row inside the tile
-    const int c = (lane % P::kChunks) ^ ((r / P::kRowsPer256) % P::kChunks);          // global chunk that lands in slot lane % kChunks
+    int r, c;      // row inside the tile and 16-byte chunk of it that this lane's copy lands on (LDS position = lane)
+    if constexpr (BK == 32) {
+      // 16 rows x 4 chunks per instruction: chunk c of row r sits at 16-byte position
+      //   ((r / 2) % 4) * 16 + (r % 2) * 8 + (c ^ ((r / 2) % 8))
+      // of its 1 KiB block, i.e. on the banks it would have in rows of 128 bytes (see the W / A stage notes above)
+      const int line = lane >> 4, u = lane & 15, x = u & 7;
+      r = (wave * P::kAInstr + i) * 16 + 2 * (line + 4 * (x >> 2)) + (u >> 3);
+      c = (x & 3) ^ line;
+    } else {
+      r = (wave * P::kAInstr + i) * P::kRowsPerInstr + lane / P::kChunks;
+      c = (lane % P::kChunks) ^ ((r / P::kRowsPer256) % P::kChunks);                  // global chunk that lands in slot lane % kChunks
+    }
     a_src[i] = A + (size_t)min(m0 + r, M - 1) * K + kbeg + c * 8;
   }
   // W fragment f of a stage = (n-tile f / (BK/16), k-tile f % (BK/16)); wave w copies fragments w*kBInstr + j
@@ -147,8 +159,14 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
 #pragma unroll
   for (int i = 0; i < 2 * TM; ++i) {
     const int r = wm * 32 * TM + i * 16 + l16;
-    a_off[i] = r * P::kRowBytes;
-    a_swz[i] = (r / P::kRowsPer256) % P::kChunks;
+    if constexpr (BK == 32) {
+      const int rl = r & 15;                                   // r is a multiple of 16 plus l16
+      a_off[i] = (r >> 4) * 1024 + (((rl >> 1) & 3) * 16 + (rl & 1) * 8) * 16;
+      a_swz[i] = (rl >> 1) & 7;
+    } else {
+      a_off[i] = r * P::kRowBytes;
+      a_swz[i] = (r / P::kRowsPer256) % P::kChunks;
+    }
   }
   // 16-k fragment t of a 32-k step holds k-quarters 2 t and 2 t + 1 in its two 512-byte halves
   const int b_lane = (kq >> 1) * 1024 + (kq & 1) * 512 + l16 * 16;
