@@ -272,7 +272,7 @@ void launch_gemm_prefill(ErnieHandle* h, const half_t* A, const half_t* Wp, cons
   // chip one and a half times; otherwise 64 x 64 with BK = 64 (measured 3-15 % faster than 128 x 64 there).
   const int forced = h->pf_tile;          // test hook: 1 / 2 / 3 force the 256 / 128 / 64 tile
   if (forced == 1 || (!forced && (tiles_256x256 >= 512 || (tiles_256x256 >= 128 && tiles_256x256 <= 256))))
-    launch_gemm_prefill_t<4, 4, 2, 2, 32, 3>(A, Wp, bias, M, N, K, epi, s);
+    launch_gemm_prefill_t<4, 4, 2, 2, 64, 2>(A, Wp, bias, M, N, K, epi, s);
   else if (forced == 2 || (!forced && tiles_128x128 >= 384)) launch_gemm_prefill_t<2, 2, 2, 2, 32, 3>(A, Wp, bias, M, N, K, epi, s);
   else launch_gemm_prefill_t<2, 2, 1, 1, 64, 3>(A, Wp, bias, M, N, K, epi, s);
 }
@@ -316,7 +316,7 @@ int configure_kernels() {
   rc |= allow_lds(gemm_prefill2_kernel<__VA_ARGS__, EpiResidual>, GemmPipe<__VA_ARGS__>::kLdsBytes);  \
   rc |= allow_lds(gemm_prefill2_kernel<__VA_ARGS__, EpiGelu>, GemmPipe<__VA_ARGS__>::kLdsBytes);      \
   rc |= allow_lds(gemm_prefill2_kernel<__VA_ARGS__, EpiRaw32>, GemmPipe<__VA_ARGS__>::kLdsBytes)
-  GEMM_LDS(4, 4, 2, 2, 32, 3); GEMM_LDS(2, 2, 2, 2, 32, 3); GEMM_LDS(2, 2, 1, 1, 64, 3);
+  GEMM_LDS(4, 4, 2, 2, 64, 2); GEMM_LDS(2, 2, 2, 2, 32, 3); GEMM_LDS(2, 2, 1, 1, 64, 3);
 #undef GEMM_LDS
   rc |= allow_lds(gemm_prefill2_kernel<2, 2, 1, 1, 64, 3, EpiGeluFast>, GemmPipe<2, 2, 1, 1, 64, 3>::kLdsBytes);
   const size_t big = (size_t)4 * 8 * 16 * 64 * 4;   // MT = 8, NW = 4
