@@ -284,6 +284,9 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
  *   "big_warm" 0..256   large-batch path: workgroups appended to the decode attention that pull the layer's bias and
  *                       LayerNorm vectors (read first by the row kernels and the FFN1 epilogue that follow) and the
  *                       next layer's QKV bias into every XCD's L2 (default 16; 0 = off).  Does not change any result.
+ *   "big_ln_rows" 1/2/4 large-batch path: rows per workgroup of the LayerNorm row kernels (default 1: a row's
+ *                       partial sums are 20 KB at d = 1024, and several rows behind one CU's memory pipeline
+ *                       lengthen these short kernels).  Does not change any result.
  *   "pf_tile" 0..3      prefill GEMM tile: 0 = chosen from the problem size (default), 1 = 256 x 256, 2 = 128 x 128,
  *                       3 = 64 x 64.  Does not change any result.
  *   "attn_nt" 0/1       decode attention reads the cache with the non-temporal (streaming) hint, so that the

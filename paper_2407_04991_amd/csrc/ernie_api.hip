@@ -141,7 +141,7 @@ struct ErnieHandle {
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
   half_t *type_emb = nullptr, *head_w = nullptr;                      // optional variants, null when off
   float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
-  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2, dec_prefetch = 64, kv_prefetch = 1, big_warm = 16, pf_tile = 0;
+  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2, dec_prefetch = 64, kv_prefetch = 1, big_warm = 16, pf_tile = 0, big_ln_rows = 1;
   int cand = 0;                  // argmax candidates per row left by the last projection   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   float* r_logits = nullptr;     // [2][max_batch][V'] fp32, large-batch projection only
@@ -541,7 +541,7 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
     rc |= launch_gemm_dec<EPI_RAW>(h, f2, h->sk_f2, s);
   }
   const LayerPtrs& P = h->layers[c.n_layers - 1];
-  { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_f2, h->sk_f2, P.b2, h->X1, B, d,
+  { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3(B), dim3(64), 0, s, h->r_f2, h->sk_f2, P.b2, h->X1, B, d,
                      P.ln2_g, P.ln2_b, c.ln_eps, h->X, hidden_out)); }
   DecGemmArgs z{};
   z.B = B; z.Wp = h->tok_p; z.N = c.vocab_kept; z.K = d; z.a16 = apply_head(h, h->X, B, s); z.logits_out = logits_out;
@@ -611,7 +611,7 @@ const half_t* apply_head(ErnieHandle* h, const half_t* x, int B, hipStream_t s) 
   const int sk = pick_gemm_split(B, d, d);
   launch_gemm_splitk(h, x, h->head_w, B, d, d, h->r_out, sk, s);
   ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
-  ROW_DISPATCH(d, hipLaunchKernelGGL((ln_partials_kernel<RC, true>), dim3((B + 3) / 4), dim3(256), 0, s, h->r_out, sk,
+  ROW_DISPATCH(d, hipLaunchKernelGGL((ln_partials_kernel<RC, true>), dim3(B), dim3(64), 0, s, h->r_out, sk,
                                      h->head_b, (const half_t*)nullptr, B, d, h->head_g, h->head_beta, h->cfg.ln_eps,
                                      h->hlast, (float*)nullptr));
   return h->hlast;
@@ -625,6 +625,7 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
   const int B = h->B, d = c.d_model, f = c.d_ffn;
   const int sk_q = pick_gemm_split(B, 3 * d, d), sk_o = pick_gemm_split(B, d, d), sk_1 = pick_gemm_split(B, f, d),
             sk_2 = pick_gemm_split(B, d, f);
+  const int rpw = h->big_ln_rows;        // rows per workgroup of the LayerNorm row kernels
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerPtrs& L = h->layers[l];
     launch_gemm_splitk(h, h->X, L.wqkv, B, 3 * d, d, h->r_qkv, sk_q, s);
@@ -643,7 +644,7 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
     }
     launch_gemm_splitk(h, h->O, L.wo, B, d, d, h->r_out, sk_o, s);
     { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
-      ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_out, sk_o,
+      ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + rpw - 1) / rpw), dim3(64 * rpw), 0, s, h->r_out, sk_o,
                                          L.bo, h->X, B, d, L.ln1_g, L.ln1_b, c.ln_eps, h->X1, (float*)nullptr)); }
     if (h->big_f1_fused) {
       // FFN1 keeps its contraction whole: bias + GELU in the GEMM epilogue, no partial buffers and one launch
@@ -660,7 +661,7 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
     launch_gemm_splitk(h, h->G, L.w2, B, d, f, h->r_f2, sk_2, s);
     { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
       float* hid = (l == c.n_layers - 1) ? hidden_out : nullptr;
-      ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, h->r_f2, sk_2,
+      ROW_DISPATCH(d, hipLaunchKernelGGL(ln_partials_kernel<RC>, dim3((B + rpw - 1) / rpw), dim3(64 * rpw), 0, s, h->r_f2, sk_2,
                                          L.b2, h->X1, B, d, L.ln2_g, L.ln2_b, c.ln_eps, h->X, hid)); }
   }
   const half_t* x = apply_head(h, h->X, B, s);
@@ -889,7 +890,7 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_o
   if (fused_decode_fits(h, B)) {
     rc = decode_layers_fused(h, tok, logits_out_dev, hidden_out_dev, s);
   } else {
-    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_decode_kernel<RC>, dim3((B + 3) / 4), dim3(256), 0, s, tok, h->lens, B, c.max_pos,
+    { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_decode_kernel<RC>, dim3(B), dim3(64), 0, s, tok, h->lens, B, c.max_pos,
                        h->tok_rm, h->pos, h->type_emb ? h->type_emb + d : nullptr, h->emb_g, h->emb_b, c.ln_eps, d, h->X,
                        h->eos, h->finished)); }
     rc = decode_layers_big(h, logits_out_dev, hidden_out_dev, s);
@@ -1048,6 +1049,7 @@ int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!h || !key) return ERNIE_EINVAL;
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "dec_nw16")) { h->dec_nw16 = value; return ERNIE_OK; }
+  if (!strcmp(key, "big_ln_rows")) { if (value != 1 && value != 2 && value != 4) return ERNIE_EINVAL; h->big_ln_rows = value; return ERNIE_OK; }
   if (!strcmp(key, "pf_tile")) { if (value < 0 || value > 3) return ERNIE_EINVAL; h->pf_tile = value; return ERNIE_OK; }
   if (!strcmp(key, "big_warm")) { if (value < 0 || value > 256) return ERNIE_EINVAL; h->big_warm = value; return ERNIE_OK; }
   if (!strcmp(key, "kv_prefetch")) { if (value < 0 || value > 2048) return ERNIE_EINVAL; h->kv_prefetch = value; return ERNIE_OK; }

@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256) void embed_ln_decode_kernel(
     const float* __restrict__ gamma, const float* __restrict__ beta, float eps, int d, half_t* __restrict__ X,
     int eos, int* __restrict__ finished) {
   const int lane = threadIdx.x & 63;
-  const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);     // blockDim.x / 64 rows per workgroup
   if (b >= B) return;
   // a sequence that is fed the end-of-sequence token is finished from this step on (sticky until the next
   // prefill): later kernels of the step skip its cache and its emitted token is the end token again
