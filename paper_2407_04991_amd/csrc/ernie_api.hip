@@ -141,7 +141,7 @@ struct ErnieHandle {
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
   half_t *type_emb = nullptr, *head_w = nullptr;                      // optional variants, null when off
   float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
-  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2, dec_prefetch = 64, kv_prefetch = 1, big_warm = 16, pf_tile = 0, big_ln_rows = 1;
+  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2, dec_prefetch = 64, kv_prefetch = 1, big_warm = 16, pf_tile = 0, big_ln_rows = 1, big_f1_tile = 0, big_narrow = 1;
   int cand = 0;                  // argmax candidates per row left by the last projection   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   float* r_logits = nullptr;     // [2][max_batch][V'] fp32, large-batch projection only
@@ -583,6 +583,15 @@ void launch_gemm_splitk(ErnieHandle* h, const half_t* A, const half_t* Wp, int M
   ProfScope prof(h, ERNIE_PROF_GEMM_DEC, s, 2.0 * N * K, 2.0 * M * N * K);
   using P = SplitPipe;
   const int tiles_m = (M + P::kBM - 1) / P::kBM, tiles_n = (N + P::kBN - 1) / P::kBN;
+  if (h->big_narrow && (long)tiles_m * tiles_n * sk * 2 <= 256) {
+    // too few 64 x 64 tiles for the CUs even after the split of the contraction: 64 x 32 tiles double them
+    using Q = GemmPipe<2, 1, 1, 1, 64, 3>;
+    const int tn = (N + Q::kBN - 1) / Q::kBN;
+    hipLaunchKernelGGL((gemm_prefill2_kernel<2, 1, 1, 1, 64, 3, EpiRaw32>), dim3(tiles_m * tn, sk), dim3(128),
+                       Q::kLdsBytes, s, A, Wp, h->zero_bias, M, N, K, (N + 31) / 32, tn,
+                       EpiRaw32{out, N, (size_t)M * N});
+    return;
+  }
   hipLaunchKernelGGL((gemm_prefill2_kernel<2, 2, 1, 1, 64, 3, EpiRaw32>), dim3(tiles_m * tiles_n, sk), dim3(256),
                      P::kLdsBytes, s, A, Wp, h->zero_bias, M, N, K, (N + 31) / 32, tiles_n,
                      EpiRaw32{out, N, (size_t)M * N});
@@ -650,7 +659,12 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
       // FFN1 keeps its contraction whole: bias + GELU in the GEMM epilogue, no partial buffers and one launch
       // less (the wide N gives enough 64 x 64 tiles; the unsplit GEMM costs 0.3-1.6 us more, a launch 5-6 us)
       ProfScope prof(h, ERNIE_PROF_GEMM_DEC, s, 2.0 * f * d, 2.0 * B * f * d);
-      launch_gemm_prefill_t<2, 2, 1, 1, 64, 3>(h->X1, L.w1, L.b1, B, f, d, EpiGeluFast{h->G, f}, s);
+      // 64 x 32 tiles when 64 x 64 ones would leave half the CUs without a workgroup (measured +0.5 % at
+      // B = 128, f = 4096; -0.6 % at B = 256, f = 3072, where 64 x 64 already gives 192 workgroups)
+      const long tiles64 = (long)((B + 63) / 64) * ((f + 63) / 64);
+      const bool narrow = h->big_f1_tile == 1 || (h->big_f1_tile == 0 && tiles64 * 2 <= 256);
+      if (narrow) launch_gemm_prefill_t<2, 1, 1, 1, 64, 3>(h->X1, L.w1, L.b1, B, f, d, EpiGeluFast{h->G, f}, s);
+      else launch_gemm_prefill_t<2, 2, 1, 1, 64, 3>(h->X1, L.w1, L.b1, B, f, d, EpiGeluFast{h->G, f}, s);
     } else {
       launch_gemm_splitk(h, h->X1, L.w1, B, f, d, h->r_f1, sk_1, s);
       ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
@@ -1050,6 +1064,8 @@ int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "dec_nw16")) { h->dec_nw16 = value; return ERNIE_OK; }
   if (!strcmp(key, "big_ln_rows")) { if (value != 1 && value != 2 && value != 4) return ERNIE_EINVAL; h->big_ln_rows = value; return ERNIE_OK; }
+  if (!strcmp(key, "big_narrow")) { h->big_narrow = value != 0; return ERNIE_OK; }
+  if (!strcmp(key, "big_f1_tile")) { if (value < 0 || value > 2) return ERNIE_EINVAL; h->big_f1_tile = value; return ERNIE_OK; }
   if (!strcmp(key, "pf_tile")) { if (value < 0 || value > 3) return ERNIE_EINVAL; h->pf_tile = value; return ERNIE_OK; }
   if (!strcmp(key, "big_warm")) { if (value < 0 || value > 256) return ERNIE_EINVAL; h->big_warm = value; return ERNIE_OK; }
   if (!strcmp(key, "kv_prefetch")) { if (value < 0 || value > 2048) return ERNIE_EINVAL; h->kv_prefetch = value; return ERNIE_OK; }
