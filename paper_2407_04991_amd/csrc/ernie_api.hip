@@ -563,8 +563,10 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
 
 // Decode projections at B > 64: the batch is a real M dimension, so they run on the MFMA GEMM pipeline
 // (64 x 64 tiles, BK = 64: measured 10-20 % faster than 128 x 64 at these shapes) with the contraction split
-// over gridDim.y until about 256 workgroups stream the weights, each keeping a slice of at least 192;
-// partial results are fp32 [split][B][N].
+// over gridDim.y until at least 144 workgroups stream the weights, each keeping a slice of at least 192;
+// partial results are fp32 [split][B][N].  Every further split adds a partial buffer that is written and read
+// back: measured, 144 unsplit workgroups beat 288 split ones (QKV at B = 256: step -1.2 %) and 192 beat 384,
+// while 128 lose to 256.
 using SplitPipe = GemmPipe<2, 2, 1, 1, 64, 3>;
 
 int pick_gemm_split(int B, int N, int K) {
@@ -573,7 +575,7 @@ int pick_gemm_split(int B, int N, int K) {
   for (int sk = 1; sk <= kBigMaxSplitK; sk *= 2) {
     if ((K / 64) % sk != 0 || (sk > 1 && K / sk < 192)) break;
     best = sk;
-    if (tiles * sk >= 256) break;
+    if (tiles * sk >= 144) break;
   }
   return best;
 }
