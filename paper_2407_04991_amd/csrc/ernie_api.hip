@@ -605,7 +605,7 @@ void launch_logits_big(ErnieHandle* h, const half_t* X, int B, float* logits_out
   using P = SplitPipe;
   const int N = h->cfg.vocab_kept, K = h->cfg.d_model;
   const int tiles_m = (B + P::kBM - 1) / P::kBM, tiles_n = (N + P::kBN - 1) / P::kBN;
-  const int sk = (tiles_m * tiles_n < 256 && (K / 64) % 2 == 0 && K / 2 >= 192) ? 2 : 1;
+  const int sk = (tiles_m * tiles_n < 144 && (K / 64) % 2 == 0 && K / 2 >= 192) ? 2 : 1;
   hipLaunchKernelGGL((gemm_prefill2_kernel<2, 2, 1, 1, 64, 3, EpiRaw32>), dim3(tiles_m * tiles_n, sk), dim3(256),
                      P::kLdsBytes, s, X, h->tok_p, h->zero_bias, B, N, K, (N + 31) / 32, tiles_n,
                      EpiRaw32{h->r_logits, N, (size_t)B * N});
