@@ -665,7 +665,9 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
       // B = 128, f = 4096; -0.6 % at B = 256, f = 3072, where 64 x 64 already gives 192 workgroups)
       const long tiles64 = (long)((B + 63) / 64) * ((f + 63) / 64);
       const bool narrow = h->big_f1_tile == 1 || (h->big_f1_tile == 0 && tiles64 * 2 <= 256);
-      if (narrow) launch_gemm_prefill_t<2, 1, 1, 1, 64, 3>(h->X1, L.w1, L.b1, B, f, d, EpiGeluFast{h->G, f}, s);
+      // the narrow tile's stages are 12 KB, so its ring is five deep (16 k-steps, unsplit: -1.1 % of the step at
+      // B = 128); five stages of the 64 x 64 tile, or of the split projections, measured slower
+      if (narrow) launch_gemm_prefill_t<2, 1, 1, 1, 64, 5>(h->X1, L.w1, L.b1, B, f, d, EpiGeluFast{h->G, f}, s);
       else launch_gemm_prefill_t<2, 2, 1, 1, 64, 3>(h->X1, L.w1, L.b1, B, f, d, EpiGeluFast{h->G, f}, s);
     } else {
       launch_gemm_splitk(h, h->X1, L.w1, B, f, d, h->r_f1, sk_1, s);
