@@ -391,6 +391,32 @@ def test_seeded_random_small_configurations(E, seed):
     eng.close()
 
 
+@pytest.mark.parametrize("seed", [1001, 1002, 1003, 1004])
+def test_seeded_random_wide_configurations(E, seed):
+    """As above at widths and lengths of the benchmark models: 8-16 heads, FFN width up to 4096, prompts up to 300
+    (several attention key blocks and GEMM tiles), batches up to 256, with or without the optional model variants."""
+    rng = np.random.default_rng(seed)
+    heads = int(rng.choice([8, 12, 16]))
+    d_ffn = int(rng.choice([1024, 3072, 4096]))
+    layers = int(rng.integers(1, 3))
+    B = int(rng.choice([8, 40, 70, 140, 256]))
+    lmax = int(rng.choice([130, 300]))
+    lengths = [int(x) for x in rng.integers(1, lmax + 1, size=B)]
+    n_gen = int(rng.integers(1, 4))
+    vocab_kept = int(rng.integers(1000, 9000))
+    name = str(rng.choice(["tiny_affine", "tiny_head"]))
+    wl = _ragged_workload(lengths, name=name, max_pos=lmax + 8, n_gen=n_gen, vocab_kept=vocab_kept, vocab_full=12000,
+                          n_layers=layers, d_model=64 * heads, n_heads=heads, d_ffn=d_ffn)
+    eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
+    ids, lens = wl.padded(0)
+    rows = sorted({0, B - 1})
+    _say(f"[parity] seed {seed}: {name} layers={layers} d={64 * heads} ffn={d_ffn} B={B} lmax={lmax} V'={vocab_kept} n_gen={n_gen}")
+    orc = oracle_generate(wl, 0, rows, n_gen)
+    toks, hid, lg = gpu_generate(eng, ids, lens, n_gen, {r: orc[r]["tokens"] for r in orc})
+    check_rows(orc, toks, hid, lg, f"seeded-wide-{seed}")
+    eng.close()
+
+
 def test_prefill_gemm_tile_shapes_agree(E):
     """Every tile shape of the prefill GEMM (chosen by problem size, here forced: 256 x 256, 128 x 128, 64 x 64) meets
     the oracle on a ragged batch whose packed token count spans several tiles with a partial last one and whose
