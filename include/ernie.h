@@ -286,6 +286,9 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
  *                       next layer's QKV bias into every XCD's L2 (default 16; 0 = off).  Does not change any result.
  *   "big_f1_tile" 0..2  large-batch path, first FFN GEMM (unsplit): 0 = 64 x 32 tiles when 64 x 64 ones would number
  *                       128 or fewer, else 64 x 64 (default), 1 = 64 x 32, 2 = 64 x 64.  Does not change any result.
+ *   "big_mfast" 0/1     large-batch path: with exactly two row tiles (64 < B <= 128) the tiles of the decode GEMMs are
+ *                       ordered rows-fastest, so that both row tiles of a weight column strip run in one XCD and the
+ *                       strip is fetched once (default 1).  Does not change any result.
  *   "big_narrow" 0/1    large-batch path: split-K projections whose 64 x 64 tiles times splits number 128 or fewer
  *                       run on 64 x 32 tiles instead (default 1).  Does not change any result.
  *   "big_ln_rows" 1/2/4 large-batch path: rows per workgroup of the LayerNorm row kernels (default 1: a row's

@@ -141,7 +141,7 @@ struct ErnieHandle {
   float *Yf, *strip_val, *r_qkv, *r_out, *r_f1, *r_f2, *zero_bias;
   half_t *type_emb = nullptr, *head_w = nullptr;                      // optional variants, null when off
   float *head_b = nullptr, *head_g = nullptr, *head_beta = nullptr, *out_bias = nullptr;
-  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2, dec_prefetch = 64, kv_prefetch = 1, big_warm = 16, pf_tile = 0, big_ln_rows = 1, big_f1_tile = 0, big_narrow = 1;
+  int sk_out, sk_f2, fused_decode, attn_dec, attn_nt = 1, ln_ns = 0, ln_rpw = 0, big_f1_fused = 1, big_logits_gemm = 1, dec_nw16 = 2, dec_prefetch = 64, kv_prefetch = 1, big_warm = 16, pf_tile = 0, big_ln_rows = 1, big_f1_tile = 0, big_narrow = 1, big_mfast = 1;
   int cand = 0;                  // argmax candidates per row left by the last projection   // decode tuning (see ernie_debug_tune)
   int *strip_idx, *cu, *lens, *tok_seq, *tok_pos, *tok_prev;
   float* r_logits = nullptr;     // [2][max_batch][V'] fp32, large-batch projection only
@@ -253,12 +253,12 @@ void launch_attn_decode(const ErnieHandle* h, const float* rqkv, int sk_in, int 
 // to fill 256 CUs twice over; small problems take smaller tiles so that every CU holds several workgroups.
 template <int WGM, int WGN, int TM, int TN, int BK, int S, class Epi>
 void launch_gemm_prefill_t(const half_t* A, const half_t* Wp, const float* bias, int M, int N, int K, Epi epi,
-                           hipStream_t s) {
+                           hipStream_t s, bool rows_fastest = false) {
   using P = GemmPipe<WGM, WGN, TM, TN, BK, S>;
   const int tiles_m = (M + P::kBM - 1) / P::kBM, tiles_n = (N + P::kBN - 1) / P::kBN;
   hipLaunchKernelGGL((gemm_prefill2_kernel<WGM, WGN, TM, TN, BK, S, Epi>), dim3(tiles_m * tiles_n), dim3(64 * WGM * WGN),
                      P::kLdsBytes, s,
-                     A, Wp, bias, M, N, K, (N + 31) / 32, tiles_n, epi);
+                     A, Wp, bias, M, N, K, (N + 31) / 32, rows_fastest ? -tiles_m : tiles_n, epi);
 }
 
 template <class Epi>
@@ -590,12 +590,12 @@ void launch_gemm_splitk(ErnieHandle* h, const half_t* A, const half_t* Wp, int M
     using Q = GemmPipe<2, 1, 1, 1, 64, 3>;
     const int tn = (N + Q::kBN - 1) / Q::kBN;
     hipLaunchKernelGGL((gemm_prefill2_kernel<2, 1, 1, 1, 64, 3, EpiRaw32>), dim3(tiles_m * tn, sk), dim3(128),
-                       Q::kLdsBytes, s, A, Wp, h->zero_bias, M, N, K, (N + 31) / 32, tn,
+                       Q::kLdsBytes, s, A, Wp, h->zero_bias, M, N, K, (N + 31) / 32, (h->big_mfast && tiles_m == 2) ? -tiles_m : tn,
                        EpiRaw32{out, N, (size_t)M * N});
     return;
   }
   hipLaunchKernelGGL((gemm_prefill2_kernel<2, 2, 1, 1, 64, 3, EpiRaw32>), dim3(tiles_m * tiles_n, sk), dim3(256),
-                     P::kLdsBytes, s, A, Wp, h->zero_bias, M, N, K, (N + 31) / 32, tiles_n,
+                     P::kLdsBytes, s, A, Wp, h->zero_bias, M, N, K, (N + 31) / 32, (h->big_mfast && tiles_m == 2) ? -tiles_m : tiles_n,
                      EpiRaw32{out, N, (size_t)M * N});
 }
 
@@ -667,8 +667,8 @@ int decode_layers_big(ErnieHandle* h, float* logits_out, float* hidden_out, hipS
       const bool narrow = h->big_f1_tile == 1 || (h->big_f1_tile == 0 && tiles64 * 2 <= 256);
       // the narrow tile's stages are 12 KB, so its ring is five deep (16 k-steps, unsplit: -1.1 % of the step at
       // B = 128); five stages of the 64 x 64 tile, or of the split projections, measured slower
-      if (narrow) launch_gemm_prefill_t<2, 1, 1, 1, 64, 5>(h->X1, L.w1, L.b1, B, f, d, EpiGeluFast{h->G, f}, s);
-      else launch_gemm_prefill_t<2, 2, 1, 1, 64, 3>(h->X1, L.w1, L.b1, B, f, d, EpiGeluFast{h->G, f}, s);
+      if (narrow) launch_gemm_prefill_t<2, 1, 1, 1, 64, 5>(h->X1, L.w1, L.b1, B, f, d, EpiGeluFast{h->G, f}, s, h->big_mfast && (B + 63) / 64 == 2);
+      else launch_gemm_prefill_t<2, 2, 1, 1, 64, 3>(h->X1, L.w1, L.b1, B, f, d, EpiGeluFast{h->G, f}, s, h->big_mfast && (B + 63) / 64 == 2);
     } else {
       launch_gemm_splitk(h, h->X1, L.w1, B, f, d, h->r_f1, sk_1, s);
       ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
@@ -1068,6 +1068,7 @@ int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "dec_nw16")) { h->dec_nw16 = value; return ERNIE_OK; }
   if (!strcmp(key, "big_ln_rows")) { if (value != 1 && value != 2 && value != 4) return ERNIE_EINVAL; h->big_ln_rows = value; return ERNIE_OK; }
+  if (!strcmp(key, "big_mfast")) { h->big_mfast = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "big_narrow")) { h->big_narrow = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "big_f1_tile")) { if (value < 0 || value > 2) return ERNIE_EINVAL; h->big_f1_tile = value; return ERNIE_OK; }
   if (!strcmp(key, "pf_tile")) { if (value < 0 || value > 3) return ERNIE_EINVAL; h->pf_tile = value; return ERNIE_OK; }

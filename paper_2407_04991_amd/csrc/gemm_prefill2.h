@@ -85,7 +85,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, (TM * TN <= 8 ? 2 : 1)) void gemm_p
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
   const int tile = xcd_contiguous_id(blockIdx.x, gridDim.x);
-  const int tile_m = tile / tiles_n, tile_n = tile - tile_m * tiles_n;
+  // tiles_n > 0: column tiles fastest (neighbouring workgroups of an XCD share A rows: prefill, M large);
+  // tiles_n < 0: -tiles_n row tiles, fastest (the few row tiles of a weight column strip run next to each other
+  // in one XCD and fetch the strip once: decode at large batch)
+  int tile_m, tile_n;
+  if (tiles_n > 0) { tile_m = tile / tiles_n; tile_n = tile - tile_m * tiles_n; }
+  else { tile_n = tile / (-tiles_n); tile_m = tile + tile_n * tiles_n; }
   const int m0 = tile_m * P::kBM, n0 = tile_n * P::kBN;
   const int k_tiles = K / 16;
   // gridDim.y > 1 splits the contraction: workgroup y accumulates k in [y, y + 1) * K / gridDim.y and the

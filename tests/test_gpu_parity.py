@@ -284,7 +284,7 @@ def test_partial_head_parameters_are_rejected(E):
 
 @pytest.mark.parametrize("vocab_kept,knobs", [(512, {"big_logits_gemm": 0, "big_ln_rows": 4}),
                                               (512, {"big_f1_fused": 0, "big_warm": 0, "big_ln_rows": 2}),
-                                              (300, {"big_warm": 200}), (512, {"big_f1_tile": 1}), (512, {"big_f1_tile": 2, "big_narrow": 0})])
+                                              (300, {"big_warm": 200}), (512, {"big_f1_tile": 1}), (512, {"big_f1_tile": 2, "big_narrow": 0, "big_mfast": 0})])
 def test_large_batch_path_alternatives(E, vocab_kept, knobs):
     """B > 64 with each alternative of the large-batch path switched: projection by the skinny kernel instead of
     the GEMM pipeline, first FFN GEMM split with a separate GELU kernel, and a kept-row count that is not a
