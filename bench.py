@@ -26,7 +26,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # 2.0, WRITE_SIZE 1.0); summary and commands in profiles/base_b32_hbm_traffic_pmc.txt.  Counters cannot be
 # read from inside the process, so the figures are carried here for the workload they were measured on.
 MEASURED_HBM_BYTES_PER_LAUNCH = {
-    "base": {"gemm_dec": 8.728e+06, "gemm_dec_ln": 1.446e+07, "attn_dec": 1.550e+07, "logits": 3.344e+07, "gemm_prefill": 6.419e+07, "attn_prefill": 2.525e+07},
+    "base": {"gemm_dec": 8.725e+06, "gemm_dec_ln": 1.447e+07, "attn_dec": 1.550e+07, "logits": 3.345e+07, "gemm_prefill": 6.420e+07, "attn_prefill": 2.525e+07},
 }
 
 # Some decode kernels carry extra workgroups that fetch the NEXT kernel's operands into L2 ahead of time; the
