@@ -181,6 +181,24 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev,
                       void* stream);
 
 /*
+ * ernie_decode_step_static -- ernie_decode_step for callers that must not touch an allocator and want the
+ * step's temporaries out of their arena: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and errors as ernie_decode_step.  The temporaries of the step
+ * (raw fp32 GEMM outputs, fp16 activations, argmax candidates) live in a 5.25 MiB array of static device
+ * memory inside the library instead of in the arena; weights, the key/value cache and the per-sequence state
+ * stay in the arena.  Each GPU the library runs on holds its own copy of that array until the process ends.
+ * Limits (ERNIE_ECAPACITY beyond them, decided on the host before anything is enqueued): batch in flight <= 64,
+ * d_model <= 1024, d_ffn <= 4096, vocab_kept <= 32768, and a shape the small-batch decode path accepts.
+ * Every call on one GPU uses the same array, whichever handle it is made through: calls that overlap on one GPU
+ * (two streams, two handles) race; calls on one stream are ordered and safe.  Nothing in the array has to be
+ * zero at entry (every element is written before it is read within a step), so a call after a larger or a
+ * smaller batch needs no clearing.  Calls no hipMalloc / hipFree and no allocating library routine.
+ */
+int ernie_decode_step_static(ErnieHandle* h, const int32_t* tok_in_dev,
+                             float* logits_out_dev, float* hidden_out_dev, int32_t* tok_out_dev,
+                             void* stream);
+
+/*
  * End of sequence, batch compaction and batching order.  The paper orders its inputs
  * before inference and lets the batch size follow the input sizes (Introduction; Related
  * work, "Dynamic Batch Size") without giving a procedure; these entry points are the

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_PKG, "libernie_hip.so")
 
 ERNIE_OK, ERNIE_EINVAL, ERNIE_ECAPACITY, ERNIE_EARENA, ERNIE_ESEQUENCE, ERNIE_EHIP = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ("ernie_init_weights", "ernie_init_weights_ex", "ernie_prefill", "ernie_decode_step", "ernie_free",
+EXPORTS = ("ernie_init_weights", "ernie_init_weights_ex", "ernie_prefill", "ernie_decode_step", "ernie_decode_step_static", "ernie_free",
            "ernie_debug_buffer", "ernie_debug_tune", "ernie_profile", "ernie_profile_read",
            "ernie_error_string", "ernie_get_config", "ernie_job_workspace_bytes", "ernie_run_job", "ernie_set_eos", "ernie_batch_state", "ernie_compact", "ernie_plan_batches",
            "ernie_vocab_count", "ernie_vocab_select", "ernie_vocab_gather_rows", "ernie_remap_ids")
@@ -95,6 +95,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.ernie_decode_step.restype = C.c_int
     lib.ernie_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.ernie_decode_step_static.restype = C.c_int
+    lib.ernie_decode_step_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.ernie_free.restype = None
     lib.ernie_free.argtypes = [C.c_void_p]
     lib.ernie_debug_buffer.restype = C.c_int
@@ -190,6 +192,12 @@ def ernie_decode_step(handle, tok_in: Optional[torch.Tensor], logits_out: Option
                       hidden_out: Optional[torch.Tensor], tok_out: torch.Tensor, stream=None) -> int:
     return load_library().ernie_decode_step(handle, _ptr(tok_in), _ptr(logits_out), _ptr(hidden_out),
                                             _ptr(tok_out), _stream_ptr(stream))
+
+
+def ernie_decode_step_static(handle, tok_in: Optional[torch.Tensor], logits_out: Optional[torch.Tensor],
+                             hidden_out: Optional[torch.Tensor], tok_out: torch.Tensor, stream=None) -> int:
+    return load_library().ernie_decode_step_static(handle, _ptr(tok_in), _ptr(logits_out), _ptr(hidden_out),
+                                                   _ptr(tok_out), _stream_ptr(stream))
 
 
 def ernie_free(handle) -> None:
@@ -414,7 +422,7 @@ class ErnieEngine:
         return tok, lo, ho
 
     def decode_step(self, tok_in: Optional[torch.Tensor] = None, *, logits=False, hidden=False, stream=None,
-                    out=None):
+                    out=None, static=False):
         B = self.B
         if tok_in is not None:
             tok_in = tok_in.to(device=self.device, dtype=torch.int32).contiguous()
@@ -424,9 +432,10 @@ class ErnieEngine:
             tok = torch.empty(B, dtype=torch.int32, device=self.device)
         else:
             tok, lo, ho = out
-        rc = ernie_decode_step(self.handle, tok_in, lo, ho, tok, stream)
+        fn = ernie_decode_step_static if static else ernie_decode_step
+        rc = fn(self.handle, tok_in, lo, ho, tok, stream)
         if rc != ERNIE_OK:
-            raise ErnieError(rc, "ernie_decode_step")
+            raise ErnieError(rc, fn.__name__)
         return tok, lo, ho
 
     def set_eos(self, eos_id: int):

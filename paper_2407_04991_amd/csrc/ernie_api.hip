@@ -10,6 +10,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -32,6 +33,24 @@ constexpr int kBigMaxSplitK = 8;       // partial buffers of the raw fp32 GEMM o
 constexpr size_t kMaxLds = 160 * 1024;
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// Per-step temporaries of the small-batch decode step for ernie_decode_step_static: the same buffers the arena
+// holds for ernie_decode_step, at the largest shape that entry point accepts.
+constexpr int kStaticMaxBatch = 64, kStaticMaxWidth = 1024, kStaticMaxFfn = 4096, kStaticMaxStrips = 1024;
+struct StaticLayout {
+  static constexpr size_t r_qkv = 0;                                                               // [1][64][3 * 1024] fp32
+  static constexpr size_t r_out = r_qkv + (size_t)kStaticMaxBatch * 3 * kStaticMaxWidth * 4;       // [8][64][1024] fp32
+  static constexpr size_t r_f2 = r_out + (size_t)kBigMaxSplitK * kStaticMaxBatch * kStaticMaxWidth * 4;   // [4][64][1024] fp32
+  static constexpr size_t strip_val = r_f2 + (size_t)4 * kStaticMaxBatch * kStaticMaxWidth * 4;    // [64][1024] fp32
+  static constexpr size_t strip_idx = strip_val + (size_t)kStaticMaxBatch * kStaticMaxStrips * 4;  // [64][1024] int32
+  static constexpr size_t X = strip_idx + (size_t)kStaticMaxBatch * kStaticMaxStrips * 4;          // [64][1024] fp16
+  static constexpr size_t X1 = X + (size_t)kStaticMaxBatch * kStaticMaxWidth * 2;
+  static constexpr size_t O = X1 + (size_t)kStaticMaxBatch * kStaticMaxWidth * 2;
+  static constexpr size_t hlast = O + (size_t)kStaticMaxBatch * kStaticMaxWidth * 2;
+  static constexpr size_t G = hlast + (size_t)kStaticMaxBatch * kStaticMaxWidth * 2;               // [64][4096] fp16
+  static constexpr size_t total = G + (size_t)kStaticMaxBatch * kStaticMaxFfn * 2;
+};
+static_assert(StaticLayout::total == 5 * 1024 * 1024 + 256 * 1024, "5.25 MiB of static device memory per GPU");
 
 struct LayerPtrs {
   half_t *wqkv, *wo, *w1, *w2;                       // fragment-major
@@ -117,6 +136,10 @@ int check_config(const ErnieConfig* c) {
 
 }  // namespace
 
+// File-scope device array behind ernie_decode_step_static.  In host code this name is only a stand-in for the
+// symbol: the device address is looked up once per device (static_scratch_for_current_device) and that
+// pointer is what kernels and copies receive.
+static __device__ __align__(256) unsigned char scratch[StaticLayout::total];
 
 // Optional per-kernel timing (ernie_profile): HIP events recorded on the caller's stream
 // around every launch of a category, plus the algorithmic bytes / flops of those launches.
@@ -160,7 +183,26 @@ struct ErnieHandle {
   // state of the batch in flight
   bool prefilled;
   int B, max_len, steps;
+  unsigned char* static_scratch = nullptr;   // device address of the file-scope scratch array on this handle's GPU
 };
+
+// Device address of the file-scope `scratch` array on the CURRENT device, looked up once per device and kept:
+// every GPU holds its own copy of the array at its own address.
+static int static_scratch_for_current_device(unsigned char** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static unsigned char* ptr_of_device[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ERNIE_EHIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of_device[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return ERNIE_EHIP; }
+    ptr_of_device[dev] = static_cast<unsigned char*>(p);
+  }
+  *out = ptr_of_device[dev];
+  return ERNIE_OK;
+}
 
 // A staging slot for one host -> device copy on stream `s`; *slot_out is the ring slot to pass to
 // stage_release after the copy has been enqueued, or -1 for a capture slot.  Returns null when the stream is
@@ -771,7 +813,7 @@ int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* w, const E
   for (int i = 0; i < kStagingSlots; ++i) { h->stage_ev[i] = nullptr; h->stage_busy[i] = false; }
 
   hipStream_t s = static_cast<hipStream_t>(stream);
-  bool host_ok = configure_kernels() == ERNIE_OK &&
+  bool host_ok = configure_kernels() == ERNIE_OK && static_scratch_for_current_device(&h->static_scratch) == ERNIE_OK &&
                  hipHostMalloc(reinterpret_cast<void**>(&h->staging),
                                sizeof(int) * 2 * kStagingSlots * (cfg->max_batch + 1), hipHostMallocDefault) == hipSuccess;
   for (int i = 0; host_ok && i < kStagingSlots; ++i)
@@ -893,14 +935,19 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
   return launch_status();
 }
 
-int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_out_dev, float* hidden_out_dev,
-                      int32_t* tok_out_dev, void* stream) {
+// Host-side checks shared by the two decode entry points.
+static int decode_step_checks(const ErnieHandle* h, const int32_t* tok_out_dev) {
   if (!h || !tok_out_dev) return ERNIE_EINVAL;
   if (!h->prefilled) return ERNIE_ESEQUENCE;
   const ErnieConfig& c = h->cfg;
   const int next_pos = h->max_len + h->steps;          // position / cache slot of the longest sequence's new token
   if (next_pos + 1 > c.max_seq || next_pos >= c.max_pos) return ERNIE_ECAPACITY;
+  return ERNIE_OK;
+}
 
+static int decode_step_enqueue(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_out_dev, float* hidden_out_dev,
+                               int32_t* tok_out_dev, void* stream) {
+  const ErnieConfig& c = h->cfg;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int B = h->B, d = c.d_model;
   const int* tok = tok_in_dev ? tok_in_dev : h->tok_prev;
@@ -921,6 +968,44 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_o
   }
   h->steps += 1;
   return launch_status();
+}
+
+int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_out_dev, float* hidden_out_dev,
+                      int32_t* tok_out_dev, void* stream) {
+  const int rc = decode_step_checks(h, tok_out_dev);
+  if (rc != ERNIE_OK) return rc;
+  return decode_step_enqueue(h, tok_in_dev, logits_out_dev, hidden_out_dev, tok_out_dev, stream);
+}
+
+int ernie_decode_step_static(ErnieHandle* h, const int32_t* tok_in_dev, float* logits_out_dev, float* hidden_out_dev,
+                             int32_t* tok_out_dev, void* stream) {
+  const int rc = decode_step_checks(h, tok_out_dev);
+  if (rc != ERNIE_OK) return rc;
+  const ErnieConfig& c = h->cfg;
+  // sizes beyond the static array's layout are refused before anything is enqueued
+  if (!h->static_scratch) return ERNIE_EHIP;
+  if (h->B > kStaticMaxBatch || c.d_model > kStaticMaxWidth || c.d_ffn > kStaticMaxFfn ||
+      h->plan.strips > kStaticMaxStrips || h->sk_f2 > 4 || !fused_decode_fits(h, h->B))
+    return ERNIE_ECAPACITY;
+  // the step's temporaries move from the arena to the static array for this call; weights, the key/value
+  // cache and the per-sequence state stay where they are
+  struct Saved { float *r_qkv, *r_out, *r_f2, *strip_val; int* strip_idx; half_t *X, *X1, *O, *G, *hlast; };
+  const Saved keep{h->r_qkv, h->r_out, h->r_f2, h->strip_val, h->strip_idx, h->X, h->X1, h->O, h->G, h->hlast};
+  unsigned char* base = h->static_scratch;
+  h->r_qkv = reinterpret_cast<float*>(base + StaticLayout::r_qkv);
+  h->r_out = reinterpret_cast<float*>(base + StaticLayout::r_out);
+  h->r_f2 = reinterpret_cast<float*>(base + StaticLayout::r_f2);
+  h->strip_val = reinterpret_cast<float*>(base + StaticLayout::strip_val);
+  h->strip_idx = reinterpret_cast<int*>(base + StaticLayout::strip_idx);
+  h->X = reinterpret_cast<half_t*>(base + StaticLayout::X);
+  h->X1 = reinterpret_cast<half_t*>(base + StaticLayout::X1);
+  h->O = reinterpret_cast<half_t*>(base + StaticLayout::O);
+  h->hlast = reinterpret_cast<half_t*>(base + StaticLayout::hlast);
+  h->G = reinterpret_cast<half_t*>(base + StaticLayout::G);
+  const int out = decode_step_enqueue(h, tok_in_dev, logits_out_dev, hidden_out_dev, tok_out_dev, stream);
+  h->r_qkv = keep.r_qkv; h->r_out = keep.r_out; h->r_f2 = keep.r_f2; h->strip_val = keep.strip_val;
+  h->strip_idx = keep.strip_idx; h->X = keep.X; h->X1 = keep.X1; h->O = keep.O; h->G = keep.G; h->hlast = keep.hlast;
+  return out;
 }
 
 int ernie_get_config(const ErnieHandle* h, ErnieConfig* out) {

@@ -63,6 +63,7 @@ def test_null_arguments_are_rejected_on_the_host():
     assert lib.ernie_init_weights(C.byref(cfg), None, None, 0, None, None, None) == E.ERNIE_EINVAL  # nowhere to write the size
     assert lib.ernie_prefill(None, 1, 1, None, None, None, None, None, None) == E.ERNIE_EINVAL
     assert lib.ernie_decode_step(None, None, None, None, None, None) == E.ERNIE_EINVAL
+    assert lib.ernie_decode_step_static(None, None, None, None, None, None) == E.ERNIE_EINVAL
     lib.ernie_free(None)     # no-op
     assert lib.ernie_profile(None, 1) == E.ERNIE_EINVAL
     assert lib.ernie_debug_tune(None, b"sk_out", 1) == E.ERNIE_EINVAL
