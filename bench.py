@@ -269,7 +269,7 @@ def trim_sweep(args):
         m = measure_pass(E, eng, ids_t.cpu().numpy(), lens, base.n_gen, args.steps, args.warmup, 1, 1)
         prof = m["prof"]
         dec_total = sum(ms for name, (ms, n, by, fl) in prof.items()
-                        if name in ("gemm_dec", "gemm_dec_ln", "attn_dec", "logits", "row_dec"))
+                        if name in ("gemm_dec", "gemm_dec_ln", "attn_dec", "logits", "row_dec", "dec_persist"))
         rows.append({"vocab_kept": k, "corpus_coverage": cover, "tokens_per_s": m["tokens_per_s"],
                      "prefill_ms": m["prefill_ms"], "decode_step_ms": m["decode_step_ms"],
                      "logits_share_of_decode_step": prof["logits"][0] / dec_total,
@@ -473,9 +473,10 @@ def main():
     dec_gbs = float(np.mean(step_bytes) / (dec_ms_mean * 1e-3) / 1e9)
     pf = prefill_flops(sh, lens)
     bound = {"gemm_dec": "hbm", "gemm_dec_ln": "hbm", "attn_dec": "hbm", "logits": "hbm", "row_dec": "hbm",
-             "gemm_prefill": "mfma", "attn_prefill": "mfma", "row_prefill": "hbm"}
+             "gemm_prefill": "mfma", "attn_prefill": "mfma", "row_prefill": "hbm", "dec_persist": "hbm"}
     phase = {"gemm_dec": "decode", "gemm_dec_ln": "decode", "attn_dec": "decode", "logits": "decode",
-             "row_dec": "decode", "gemm_prefill": "prefill", "attn_prefill": "prefill", "row_prefill": "prefill"}
+             "row_dec": "decode", "gemm_prefill": "prefill", "attn_prefill": "prefill", "row_prefill": "prefill",
+             "dec_persist": "decode"}
     # Event-bracketed eager launches carry the event and dispatch latency of every launch.  The timed region
     # replays graphs, so each family's time is scaled by (phase time in the timed configuration) / (sum of the
     # bracketed times of that phase): the families keep their measured shares of the measured phase time.

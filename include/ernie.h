@@ -269,7 +269,8 @@ int ernie_debug_buffer(ErnieHandle* h, const char* name, void** ptr_dev, size_t*
 #define ERNIE_PROF_LOGITS        5   /* output projection + first argmax stage (decode, small-batch path) */
 #define ERNIE_PROF_ROW_DEC       6   /* decode row kernels: embedding + LayerNorm, final LayerNorm, second argmax stage */
 #define ERNIE_PROF_ROW_PREFILL   7   /* prefill row kernels: token map, embedding + LayerNorm, LayerNorm, last-row gather, argmax */
-#define ERNIE_PROF_NCAT          8
+#define ERNIE_PROF_DEC_PERSIST   8   /* the one-launch decode kernel: every layer of a small-batch step (weights + cache bytes) */
+#define ERNIE_PROF_NCAT          9
 int ernie_profile(ErnieHandle* h, int enable);
 int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* launches,
                        double* alg_bytes, double* alg_flops);

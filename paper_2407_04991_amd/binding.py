@@ -25,7 +25,7 @@ EXPORTS = ("ernie_init_weights", "ernie_init_weights_ex", "ernie_prefill", "erni
            "ernie_vocab_count", "ernie_vocab_select", "ernie_vocab_gather_rows", "ernie_remap_ids")
 
 PROF_CATEGORIES = ("gemm_dec", "gemm_dec_ln", "attn_dec", "gemm_prefill", "attn_prefill", "logits",
-                   "row_dec", "row_prefill")
+                   "row_dec", "row_prefill", "dec_persist")
 
 
 class ErnieConfig(C.Structure):

@@ -17,6 +17,7 @@
 #include "attention.h"
 #include "common.h"
 #include "decode_fused.h"
+#include "decode_persist.h"
 #include "gemm_prefill.h"
 #include "gemm_prefill2.h"
 #include "gemm_skinny.h"
@@ -31,6 +32,7 @@ constexpr int kStagingSlots = 8;
 constexpr int kFusedMaxBatch = 64;     // the fused-prologue decode path keeps the whole batch in LDS
 constexpr int kBigMaxSplitK = 8;       // partial buffers of the raw fp32 GEMM outputs
 constexpr size_t kMaxLds = 160 * 1024;
+constexpr size_t kPersistMaxLds = kMaxLds - 8 * 1024;
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -68,6 +70,8 @@ struct ArenaPlan {
   bool has_type, has_head, has_bias;
   size_t kv, X, X1, Y, Q, O, G, Yf, hlast, strip_val, strip_idx, cu, lens, tok_seq, tok_pos, tok_prev;
   size_t finished, slot, keep, r_logits;
+  size_t xch, ptab, epoch;               // one-launch decode step: exchange buffers, layer table, step counter
+  PersistXch xo; int xch_batch;          // offsets inside a layer's exchange region and its row capacity (0 = none)
   size_t total;
   int vocab_tiles, strips;
   size_t t_max;
@@ -118,6 +122,17 @@ ArenaPlan make_plan(const ErnieConfig& c, const ErnieVariants* var) {
   p.cu = take((Bm + 1) * 4); p.lens = take(Bm * 4);
   p.tok_seq = take(p.t_max * 4); p.tok_pos = take(p.t_max * 4); p.tok_prev = take(Bm * 4);
   p.finished = take(Bm * 4); p.slot = take(Bm * 4); p.keep = take(Bm * 4);
+  // exchange buffers of the one-launch decode step (pairs of fp16 + tag: 4 bytes per element), one set per layer
+  p.xch_batch = (d <= 1024 && f <= 4096) ? (int)std::min<size_t>(Bm, kFusedMaxBatch) : 0;
+  {
+    const size_t xb = (size_t)p.xch_batch * 4;
+    p.xo.qkv = 0; p.xo.o = (unsigned)(xb * 3 * d); p.xo.y1 = p.xo.o + (unsigned)(xb * d);
+    p.xo.g = p.xo.y1 + (unsigned)(xb * d); p.xo.y2 = p.xo.g + (unsigned)(xb * f); p.xo.x = p.xo.y2 + (unsigned)(xb * d);
+    p.xo.x1 = p.xo.x + (unsigned)(xb * d); p.xo.layer_bytes = (unsigned)align_up(p.xo.x1 + xb * d);
+    p.xch = take((size_t)p.xo.layer_bytes * c.n_layers);
+    p.ptab = take(p.xch_batch ? sizeof(PersistLayer) * c.n_layers : 0);
+    p.epoch = take(256);
+  }
   p.total = off;
   return p;
 }
@@ -183,7 +198,13 @@ struct ErnieHandle {
   // state of the batch in flight
   bool prefilled;
   int B, max_len, steps;
-  unsigned char* static_scratch = nullptr;   // device address of the file-scope scratch array on this handle's GPU
+  unsigned char* static_scratch = nullptr;
+  // one-launch decode step (decode_persist.h)
+  int persist = 1, persist_stall = 0, cu_count = 0;
+  unsigned persist_spin = 1u << 17;
+  unsigned char* xch = nullptr; PersistLayer* ptab = nullptr; unsigned* epoch = nullptr;
+  std::vector<PersistLayer> ptab_host;   // source of the asynchronous copy into `ptab`: lives as long as the handle
+  int* err_host = nullptr;               // pinned, device-visible: a bounded wait that gave up leaves 1 here   // device address of the file-scope scratch array on this handle's GPU
 };
 
 // Device address of the file-scope `scratch` array on the CURRENT device, looked up once per device and kept:
@@ -371,6 +392,11 @@ int configure_kernels() {
 #undef LN_LDS
 #undef LN_LDS1
 #undef LN_LDS2
+  // (the one-launch kernel also holds a few KB of statically declared LDS)
+#define PERSIST_LDS(RPW) rc |= allow_lds(decode_persist_kernel<RPW, 8>, kPersistMaxLds); rc |= allow_lds(decode_persist_kernel<RPW, 16>, kPersistMaxLds); \
+  rc |= allow_lds(decode_persist_kernel<RPW, 24>, kPersistMaxLds); rc |= allow_lds(decode_persist_kernel<RPW, 32>, kPersistMaxLds)
+  PERSIST_LDS(1); PERSIST_LDS(2);
+#undef PERSIST_LDS
   rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_RAW>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<1, 16, EPI_RAW>, kMaxLds);
   rc |= allow_lds(gemm_dec_kernel<1, 16, EPI_ARGMAX>, kMaxLds);
@@ -603,6 +629,47 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
   return rc ? ERNIE_EHIP : ERNIE_OK;
 }
 
+// The whole layer stack of a small-batch decode step as ONE persistent kernel (decode_persist.h), followed by
+// the output projection.  Shapes it takes: whatever the small-batch path takes, FFN width up to 4096.
+bool persist_decode_fits(const ErnieHandle* h, int B) {
+  return h->persist && h->xch && B <= h->plan.xch_batch && fused_decode_fits(h, B) && h->cfg.d_ffn <= 4096 && h->cu_count > 0;
+}
+
+int decode_layers_persist(ErnieHandle* h, const int* tok, float* logits_out, float* hidden_out, hipStream_t s) {
+  const ErnieConfig& c = h->cfg;
+  const int B = h->B, d = c.d_model, f = c.d_ffn;
+  PersistArgs a{};
+  a.layers = h->ptab; a.n_layers = c.n_layers; a.B = B; a.d = d; a.f = f; a.H = c.n_heads; a.S = c.max_seq; a.eps = c.ln_eps;
+  a.tok = tok; a.cache_len = h->lens; a.tok_emb = h->tok_rm; a.pos_emb = h->pos;
+  a.seg_row = h->type_emb ? h->type_emb + d : nullptr; a.emb_g = h->emb_g; a.emb_b = h->emb_b;
+  a.max_pos = c.max_pos; a.vocab_kept = c.vocab_kept; a.eos = h->eos; a.finished = h->finished;
+  a.slot = h->compacted ? h->slot : nullptr;
+  a.xch = h->xch; a.xo = h->plan.xo; a.epoch = h->epoch; a.X = h->X; a.hidden_out = hidden_out;
+  a.err = h->err_host; a.spin_limit = h->persist_spin; a.stall = h->persist_stall; a.attn_nt = h->attn_nt;
+  const int rpw = B > 32 ? 2 : 1;
+  const size_t lds_a = (size_t)8 * rpw * (d + 8) * 2, lds_5 = (size_t)4 * rpw * (f + 8) * 2, lds_r = (size_t)8 * 2 * 8 * 256;
+  const size_t lds = std::max(std::max(lds_a, lds_5), lds_r);
+  if (lds > kPersistMaxLds) return ERNIE_EINVAL;
+  {
+    const double w_bytes = (double)c.n_layers * (4.0 * d * d + 2.0 * d * f) * 2.0;
+    const double kv_bytes = (double)c.n_layers * 2.0 * (h->sum_len + (double)B * (h->steps + 1)) * d * 2.0;
+    ProfScope prof(h, ERNIE_PROF_DEC_PERSIST, s, w_bytes + kv_bytes, 2.0 * B * (4.0 * d * d + 2.0 * d * f) * c.n_layers);
+    const dim3 grid(h->cu_count), block(kPersistThreads);
+#define PERSIST_LAUNCH(RPW, FR5) hipLaunchKernelGGL((decode_persist_kernel<RPW, FR5>), grid, block, lds, s, a)
+#define PERSIST_BY_F(RPW) do { if (f <= 1024) PERSIST_LAUNCH(RPW, 8); else if (f <= 2048) PERSIST_LAUNCH(RPW, 16); \
+                               else if (f <= 3072) PERSIST_LAUNCH(RPW, 24); else PERSIST_LAUNCH(RPW, 32); } while (0)
+    if (rpw == 1) PERSIST_BY_F(1); else PERSIST_BY_F(2);
+#undef PERSIST_BY_F
+#undef PERSIST_LAUNCH
+  }
+  DecGemmArgs z{};
+  z.B = B; z.Wp = h->tok_p; z.N = c.vocab_kept; z.K = d; z.a16 = apply_head(h, h->X, B, s); z.logits_out = logits_out;
+  z.bias_out = h->out_bias;
+  z.strip_val = h->strip_val; z.strip_idx = h->strip_idx; z.strips = h->plan.strips;
+  h->cand = h->plan.strips;
+  return launch_gemm_dec<EPI_ARGMAX>(h, z, 1, s);
+}
+
 // Decode projections at B > 64: the batch is a real M dimension, so they run on the MFMA GEMM pipeline
 // (64 x 64 tiles, BK = 64: measured 10-20 % faster than 128 x 64 at these shapes) with the contraction split
 // over gridDim.y until at least 144 workgroups stream the weights, each keeping a slice of at least 192;
@@ -808,6 +875,10 @@ int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* w, const E
   h->tok_seq = I32(plan.tok_seq); h->tok_pos = I32(plan.tok_pos); h->tok_prev = I32(plan.tok_prev);
   h->finished = I32(plan.finished); h->slot = I32(plan.slot); h->keep = I32(plan.keep);
   h->r_logits = F32(plan.r_logits);
+  if (plan.xch_batch > 0) {
+    h->xch = a + plan.xch; h->ptab = reinterpret_cast<PersistLayer*>(a + plan.ptab);
+    h->epoch = reinterpret_cast<unsigned*>(a + plan.epoch);
+  }
   h->prefilled = false; h->B = 0; h->max_len = 0; h->steps = 0; h->sum_len = h->sum_len2 = 0.0;
   h->staging = nullptr; h->staging_next = 0; h->staging_captured = 0;
   for (int i = 0; i < kStagingSlots; ++i) { h->stage_ev[i] = nullptr; h->stage_busy[i] = false; }
@@ -815,7 +886,14 @@ int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* w, const E
   hipStream_t s = static_cast<hipStream_t>(stream);
   bool host_ok = configure_kernels() == ERNIE_OK && static_scratch_for_current_device(&h->static_scratch) == ERNIE_OK &&
                  hipHostMalloc(reinterpret_cast<void**>(&h->staging),
-                               sizeof(int) * 2 * kStagingSlots * (cfg->max_batch + 1), hipHostMallocDefault) == hipSuccess;
+                               sizeof(int) * (2 * kStagingSlots * (cfg->max_batch + 1) + 16), hipHostMallocDefault) == hipSuccess;
+  if (host_ok) {
+    h->err_host = h->staging + (size_t)2 * kStagingSlots * (cfg->max_batch + 1);     // behind the staging slots
+    *h->err_host = 0;
+    int dev = 0;
+    host_ok = hipGetDevice(&dev) == hipSuccess &&
+              hipDeviceGetAttribute(&h->cu_count, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess;
+  }
   for (int i = 0; host_ok && i < kStagingSlots; ++i)
     host_ok = hipEventCreateWithFlags(&h->stage_ev[i], hipEventDisableTiming) == hipSuccess;
   if (!host_ok) {
@@ -847,6 +925,19 @@ int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* w, const E
     cvt_into(w->b1[l], L.b1, f, s); cvt_into(w->b2[l], L.b2, d, s);
     cvt_into(w->ln1_g[l], L.ln1_g, d, s); cvt_into(w->ln1_b[l], L.ln1_b, d, s);
     cvt_into(w->ln2_g[l], L.ln2_g, d, s); cvt_into(w->ln2_b[l], L.ln2_b, d, s);
+  }
+  if (h->xch) {
+    // tags start at zero everywhere, so that the first step's tag (1) is new to every pair
+    copies_ok &= hipMemsetAsync(h->xch, 0, (size_t)plan.xo.layer_bytes * cfg->n_layers, s) == hipSuccess;
+    copies_ok &= hipMemsetAsync(h->epoch, 0, 256, s) == hipSuccess;
+    h->ptab_host.resize(cfg->n_layers);
+    for (int l = 0; l < cfg->n_layers; ++l) {
+      const LayerPtrs& L = h->layers[l];
+      h->ptab_host[l] = PersistLayer{L.wqkv, L.wo, L.w1, L.w2, L.bqkv, L.bo, L.b1, L.b2, L.ln1_g, L.ln1_b, L.ln2_g,
+                                     L.ln2_b, kcache(h, l), vcache(h, l)};
+    }
+    copies_ok &= hipMemcpyAsync(h->ptab, h->ptab_host.data(), sizeof(PersistLayer) * cfg->n_layers,
+                                hipMemcpyHostToDevice, s) == hipSuccess;
   }
   if (plan.has_type) {
     h->type_emb = H16(plan.type_emb);
@@ -939,6 +1030,8 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
 static int decode_step_checks(const ErnieHandle* h, const int32_t* tok_out_dev) {
   if (!h || !tok_out_dev) return ERNIE_EINVAL;
   if (!h->prefilled) return ERNIE_ESEQUENCE;
+  // a bounded wait of the one-launch decode kernel gave up in an earlier step: reported once, here
+  if (h->err_host && *(volatile int*)h->err_host) { *(volatile int*)h->err_host = 0; return ERNIE_EHIP; }
   const ErnieConfig& c = h->cfg;
   const int next_pos = h->max_len + h->steps;          // position / cache slot of the longest sequence's new token
   if (next_pos + 1 > c.max_seq || next_pos >= c.max_pos) return ERNIE_ECAPACITY;
@@ -952,7 +1045,9 @@ static int decode_step_enqueue(ErnieHandle* h, const int32_t* tok_in_dev, float*
   const int B = h->B, d = c.d_model;
   const int* tok = tok_in_dev ? tok_in_dev : h->tok_prev;
   int rc;
-  if (fused_decode_fits(h, B)) {
+  if (persist_decode_fits(h, B)) {
+    rc = decode_layers_persist(h, tok, logits_out_dev, hidden_out_dev, s);
+  } else if (fused_decode_fits(h, B)) {
     rc = decode_layers_fused(h, tok, logits_out_dev, hidden_out_dev, s);
   } else {
     { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_decode_kernel<RC>, dim3(B), dim3(64), 0, s, tok, h->lens, B, c.max_pos,
@@ -964,7 +1059,7 @@ static int decode_step_enqueue(ErnieHandle* h, const int32_t* tok_in_dev, float*
   { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0);
   hipLaunchKernelGGL(argmax_final_kernel, dim3(B), dim3(256), 0, s, h->strip_val, h->strip_idx, h->cand,
                      tok_out_dev, h->tok_prev, h->lens, 1, c.max_seq, c.vocab_kept,
-                     h->eos >= 0 ? h->finished : (const int*)nullptr, h->eos);
+                     h->eos >= 0 ? h->finished : (const int*)nullptr, h->eos, h->epoch);
   }
   h->steps += 1;
   return launch_status();
@@ -1002,7 +1097,10 @@ int ernie_decode_step_static(ErnieHandle* h, const int32_t* tok_in_dev, float* l
   h->O = reinterpret_cast<half_t*>(base + StaticLayout::O);
   h->hlast = reinterpret_cast<half_t*>(base + StaticLayout::hlast);
   h->G = reinterpret_cast<half_t*>(base + StaticLayout::G);
+  const int persist_was = h->persist;
+  h->persist = 0;                    // the one-launch kernel's exchange buffers are arena memory: not used here
   const int out = decode_step_enqueue(h, tok_in_dev, logits_out_dev, hidden_out_dev, tok_out_dev, stream);
+  h->persist = persist_was;
   h->r_qkv = keep.r_qkv; h->r_out = keep.r_out; h->r_f2 = keep.r_f2; h->strip_val = keep.strip_val;
   h->strip_idx = keep.strip_idx; h->X = keep.X; h->X1 = keep.X1; h->O = keep.O; h->G = keep.G; h->hlast = keep.hlast;
   return out;
@@ -1151,6 +1249,9 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
 int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!h || !key) return ERNIE_EINVAL;
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
+  if (!strcmp(key, "persist")) { h->persist = value != 0; return ERNIE_OK; }
+  if (!strcmp(key, "persist_spin")) { if (value < 1) return ERNIE_EINVAL; h->persist_spin = (unsigned)value; return ERNIE_OK; }
+  if (!strcmp(key, "persist_stall")) { if (value < 0 || value > 5) return ERNIE_EINVAL; h->persist_stall = value; return ERNIE_OK; }
   if (!strcmp(key, "dec_nw16")) { h->dec_nw16 = value; return ERNIE_OK; }
   if (!strcmp(key, "big_ln_rows")) { if (value != 1 && value != 2 && value != 4) return ERNIE_EINVAL; h->big_ln_rows = value; return ERNIE_OK; }
   if (!strcmp(key, "big_mfast")) { h->big_mfast = value != 0; return ERNIE_OK; }

@@ -206,15 +206,18 @@ __global__ void gather_last_rows_kernel(const half_t* __restrict__ X, const int*
 // Second argmax stage: one block per sequence reduces the per-strip candidates
 // (value, index); the lowest index wins exact ties.  Also advances the cached
 // length of the sequence after a decode step (advance = 1).  A finished sequence
-// (`finished` non-null and set) emits `eos` and does not advance.
+// (`finished` non-null and set) emits `eos` and does not advance.  `step_counter` (may be null) is advanced by
+// one: the number of the decode step that tags the hand-overs of the one-launch decode kernel.
 __global__ __launch_bounds__(256) void argmax_final_kernel(const float* __restrict__ strip_val,
                                                            const int* __restrict__ strip_idx, int strips,
                                                            int* __restrict__ tok_out, int* __restrict__ tok_keep,
                                                            int* __restrict__ cache_len, int advance, int max_seq, int vocab,
-                                                           const int* __restrict__ finished, int eos) {
+                                                           const int* __restrict__ finished, int eos,
+                                                           unsigned* __restrict__ step_counter = nullptr) {
   __shared__ float sv[4];
   __shared__ int si[4];
   const int b = blockIdx.x;
+  if (step_counter && b == 0 && threadIdx.x == 0) *step_counter += 1u;
   // everything this workgroup reads is requested up front: the row's state for the last step of thread 0 and
   // the first four candidates of every thread (a loop of load + compare costs a memory round trip per trip)
   int done_flag = 0, len_now = 0;

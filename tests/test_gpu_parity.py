@@ -504,31 +504,43 @@ def test_decode_attention_shapes_and_poisoned_cache_tail(E):
 
 
 def test_profile_hooks_count_launches(E):
-    """ernie_profile brackets every launch of a kernel family; counts and algorithmic bytes match the step structure."""
+    """ernie_profile brackets every launch of a kernel family; counts and algorithmic bytes match the step structure,
+    with the layers of a step as one kernel (default) and as five kernels per layer."""
     import torch
     wl = make_workload("tiny_affine")
     sh = wl.shape
     eng = E.engine_from_workload(wl)
     ids, lens = wl.padded(0)
-    eng.profile(True)
-    tok, _, _ = eng.prefill(torch.as_tensor(ids), lens)
-    for _ in range(3):
-        eng.decode_step(None)
-    torch.cuda.synchronize()
-    p = eng.profile_read()
     Nl, d, f = sh.n_layers, sh.d_model, sh.d_ffn
-    assert p["gemm_prefill"][1] == 4 * Nl and p["attn_prefill"][1] == Nl
-    assert p["attn_dec"][1] == 3 * Nl and p["logits"][1] == 3
-    assert p["gemm_dec"][1] + p["gemm_dec_ln"][1] == 3 * 4 * Nl          # four projections per layer per step
-    assert p["gemm_dec_ln"][1] == 3 * 2 * Nl                             # every QKV (layer 0: embedding prologue) and FFN1
-    assert p["row_dec"][1] == 3 * 2                                      # final LayerNorm and second argmax stage per step
     w_layer = (4 * d * d + 2 * d * f) * 2
-    assert abs(p["gemm_dec"][2] + p["gemm_dec_ln"][2] - 3 * Nl * w_layer) < 1
     kv = sum(2 * (int(lens.sum()) + sh.batch * (t + 1)) * d * 2 for t in range(3)) * Nl
-    assert abs(p["attn_dec"][2] - kv) < 1
-    assert abs(p["gemm_prefill"][3] - 2 * int(lens.sum()) * Nl * (4 * d * d + 2 * d * f)) < 1
-    for name in ("gemm_prefill", "attn_prefill", "attn_dec", "gemm_dec", "gemm_dec_ln", "logits"):
-        assert p[name][0] > 0.0
+    for persist in (1, 0):
+        eng.tune("persist", persist)
+        eng.profile(True)
+        tok, _, _ = eng.prefill(torch.as_tensor(ids), lens)
+        for _ in range(3):
+            eng.decode_step(None)
+        torch.cuda.synchronize()
+        p = eng.profile_read()
+        assert p["gemm_prefill"][1] == 4 * Nl and p["attn_prefill"][1] == Nl
+        assert p["logits"][1] == 3
+        if persist:
+            assert p["dec_persist"][1] == 3 and p["attn_dec"][1] == 0 and p["gemm_dec"][1] == 0 and p["gemm_dec_ln"][1] == 0
+            assert p["row_dec"][1] == 3                                          # second argmax stage
+            assert abs(p["dec_persist"][2] - (3 * Nl * w_layer + kv)) < 1
+            assert p["dec_persist"][0] > 0.0
+        else:
+            assert p["dec_persist"][1] == 0 and p["attn_dec"][1] == 3 * Nl
+            assert p["gemm_dec"][1] + p["gemm_dec_ln"][1] == 3 * 4 * Nl          # four projections per layer per step
+            assert p["gemm_dec_ln"][1] == 3 * 2 * Nl                             # every QKV (layer 0: embedding prologue) and FFN1
+            assert p["row_dec"][1] == 3 * 2                                      # final LayerNorm and second argmax stage per step
+            assert abs(p["gemm_dec"][2] + p["gemm_dec_ln"][2] - 3 * Nl * w_layer) < 1
+            assert abs(p["attn_dec"][2] - kv) < 1
+            for name in ("attn_dec", "gemm_dec", "gemm_dec_ln"):
+                assert p[name][0] > 0.0
+        assert abs(p["gemm_prefill"][3] - 2 * int(lens.sum()) * Nl * (4 * d * d + 2 * d * f)) < 1
+        for name in ("gemm_prefill", "attn_prefill", "logits"):
+            assert p[name][0] > 0.0
     eng.profile(False)
     eng.decode_step(None)
     torch.cuda.synchronize()

@@ -46,6 +46,7 @@ def test_static_scratch_decode_step_matches_the_arena_one():
         ids, lens = wl.padded(0)
         feeds = [rng.integers(0, V, size=B).astype(np.int32) for _ in range(3)]
         ref_eng = E.engine_from_workload(wl, max_seq=wl.shape.prompt_len + 8)
+        ref_eng.tune("persist", 0)      # the five-kernels-per-layer decode step, which is what the static variant runs
         ref = _steps(ref_eng, ids, lens, feeds, static=False)
         ref_eng.close()
         eng = E.engine_from_workload(wl, max_seq=wl.shape.prompt_len + 8)
