@@ -18,8 +18,10 @@
 // Work split.  All five GEMM-shaped phases of a layer use the same decomposition: a workgroup owns R batch
 // rows of NS adjacent 32-column strips over the WHOLE contraction (no partial sums cross workgroups); its
 // eight waves split the contraction and are added through LDS in a fixed order.  The weight fragments of a
-// phase are requested before the workgroup starts polling for the phase's input, so the HBM stream runs
-// under the hand-over latency.  Row-wise work sits where the full row is: LayerNorm in the prologue of the
+// phase are requested before the workgroup starts polling for the phase's input, so the HBM stream runs under
+// the hand-over latency (measured: with the weight loads removed altogether the step is only 13 % shorter;
+// warming the L2 for later phases with strided touch loads made it LONGER, because loads return in order and
+// every later load of the wave queues behind the touches).  Row-wise work sits where the full row is: LayerNorm in the prologue of the
 // consuming GEMM (QKV, FFN1), bias / residual / GELU in the epilogue of the producing one.
 #pragma once
 
@@ -41,6 +43,66 @@ struct PersistLayer {                   // one per layer, in device memory
   const float *bqkv, *bo, *b1, *b2, *ln1_g, *ln1_b, *ln2_g, *ln2_b;
   half_t *kc, *vc;                      // this layer's key / value cache
 };
+
+// A pointer read from device memory (or from a struct passed by value) carries no address space, and loads
+// through it are flat instructions (which also count against the LDS counter).  These say "global memory".
+template <class T>
+__device__ __forceinline__ T* as_global(T* p) {
+  typedef __attribute__((address_space(1))) T gT;
+  return (T*)(gT*)p;
+}
+template <class T>
+__device__ __forceinline__ T ld_global(const T* p) {
+  typedef __attribute__((address_space(1))) const T gT;
+  return *(gT*)p;
+}
+template <class T>
+__device__ __forceinline__ void st_global(T* p, T v) {
+  typedef __attribute__((address_space(1))) T gT;
+  *(gT*)p = v;
+}
+template <class T>
+__device__ __forceinline__ T ld_global_nt(const T* p) {
+  typedef __attribute__((address_space(1))) const T gT;
+  return __builtin_nontemporal_load((gT*)p);
+}
+template <bool NT>
+__device__ __forceinline__ half8 ld_kv(const half_t* p) {
+  if constexpr (NT) return ld_global_nt(reinterpret_cast<const half8*>(p));
+  else return ld_global(reinterpret_cast<const half8*>(p));
+}
+
+// The thread's index, opaque to the optimiser.  Everything in a phase that derives from the thread or workgroup
+// index (offsets, unit numbers) is the same in every layer; hoisted out of the layer loop it would occupy
+// registers for the whole kernel, and the spills that follow are reloaded through the same in-order counter
+// as the hand-over loads (a reload then waits for every outstanding touch).  Recomputing costs a few ALU
+// instructions per phase.
+__device__ __forceinline__ int fresh_tid() {
+  int t = threadIdx.x;
+  asm volatile("" : "+v"(t));
+  return t;
+}
+__device__ __forceinline__ int fresh_wg() {
+  int b = blockIdx.x;
+  asm volatile("" : "+s"(b));
+  return b;
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains the vector-memory counter, i.e.
+// waits for every outstanding global load and store of the wave: the L2 touches (HBM latency) and the pairs
+// just published among them.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// Barrier + "did any thread of the workgroup give up a wait?" (sticky: once set, the workgroup leaves).
+__device__ __forceinline__ bool persist_sync_fail(bool fail, int* s_fail) {
+  if (__any(fail) && (fresh_tid() & 63) == 0) *s_fail = 1;
+  lds_barrier();
+  return *s_fail != 0;
+}
 
 // Per-layer exchange region: [B][cols] fp16 matrices stored as pairs (4 bytes per element), in this order.
 struct PersistXch {
@@ -66,7 +128,17 @@ struct PersistArgs {
   unsigned spin_limit;
   int stall;                            // test hook: phase number (1..5, layer 0) whose output is withheld; 0 = none
   int attn_nt;
+  int dbg;                              // measurement hook, bit mask: 1 = helper workgroups idle, 2 = no weight loads (results are wrong)
+  int helpers_from;                     // workgroups from this id on (a multiple of 8) own no unit and warm the L2; = grid if none
+  int kv_rows;                          // upper bound of the cache rows of any stream after this step (L2 warm-up only)
+  unsigned red_off;                     // byte offset of the cross-wave reduction buffer in dynamic LDS (behind the largest A tile)
+  unsigned long long* trace;            // test hook: [workgroup][layer][32] 100 MHz time stamps (entry, input ready, done per phase), or null
 };
+
+// Time stamp `slot` of the workgroup's current layer (tracing only).
+__device__ __forceinline__ void persist_stamp(unsigned long long* row, int slot) {
+  if (row && threadIdx.x == 0) row[slot] = wall_clock64();
+}
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t xch_rsrc(const void* p, unsigned bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
@@ -105,62 +177,97 @@ struct PersistGemm {
   bool withhold;                       // test hook: compute, but do not publish
 };
 
-// One GEMM-shaped phase.  R rows per workgroup (PRO_LN / PRO_EMBED: one or two rows per wave, R = 8 or 16),
-// NS strips per workgroup, FR weight fragments in flight per wave and strip.  Returns false (uniformly for the
-// workgroup) when a wait gave up.
-template <int R, int NS, int FR, int PRO, int EPI, int RC = 2>
-__device__ __forceinline__ bool persist_gemm_phase(const PersistGemm& g, const PersistArgs& p, unsigned tag,
-                                                   unsigned char* smem_raw) {
+// The weight fragments a wave holds for its unit of a GEMM phase: NS strips x FR k-tiles, requested one
+// phase ahead (right after the current phase's input has arrived), so that they have landed by the time the
+// next phase's input does.  Loads return in order: a poll issued behind a late weight request would wait for it.
+template <int NS, int FR>
+struct PersistW {
+  half8 w[NS][FR];
+};
+
+// A workgroup's unit of a GEMM phase.  Every phase has at most as many units as unit-owning workgroups (the host checks), so a
+// workgroup owns one unit or sits the phase out.  Units are (strip group, row group) in XCD-contiguous order
+// with the row group fastest: the row groups of a strip group run on one XCD and share its weight fragments
+// in that L2.
+template <int R, int NS>
+struct PersistUnit {
+  static constexpr int NV = R <= 8 ? 4 : R / 2;      // accumulator registers that hold rows < R (row = 8 (v / 4) + 4 (lane / 32) + v % 4)
+  static constexpr int kMyNv = (NS * NV + kPersistWaves - 1) / kPersistWaves;
+  int sg, row0;
+  bool has;
+  float bias_r[kMyNv];        // bias of this lane's output columns, fetched ahead of the epilogue
+};
+
+template <int R, int NS>
+__device__ __forceinline__ PersistUnit<R, NS> persist_unit(int N, int B, const float* bias) {
+  PersistUnit<R, NS> u;
+  const int tid = fresh_tid(), lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n_tiles = N / 32, zg = (B + R - 1) / R, n_units = ((n_tiles + NS - 1) / NS) * zg;
+  const int wg = fresh_wg();
+  u.has = wg < n_units;
+  const int logical = u.has ? xcd_contiguous_id(wg, n_units) : 0;      // (n_units <= the unit-owning workgroups, host-checked)
+  u.sg = logical / zg;
+  u.row0 = (logical - u.sg * zg) * R;
+#pragma unroll
+  for (int i = 0; i < PersistUnit<R, NS>::kMyNv; ++i) {
+    const int nt = u.sg * NS + (wave + i * kPersistWaves) / PersistUnit<R, NS>::NV;
+    u.bias_r[i] = ld_global(bias + min(nt * 32 + (lane & 31), N - 1));
+  }
+  return u;
+}
+
+// Requests the workgroup's weight fragments of a phase (all of them when the wave's share of the contraction
+// is at most FR k-tiles, which the host guarantees).  Straight-line: a workgroup that sits the phase out loads
+// its clamped unit's fragments too (a few KB from L2) rather than branching, so that the registers have one
+// definition.
+template <int R, int NS, int FR>
+__device__ __forceinline__ void persist_w_issue(PersistW<NS, FR>& W, const half_t* Wp, int N, int K, int B, bool off = false) {
+  if (off) {
+    const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int n = 0; n < NS; ++n)
+#pragma unroll
+      for (int u = 0; u < FR; ++u) W.w[n][u] = z;
+    return;
+  }
+  const int tid = fresh_tid(), lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int k_tiles = K / 16, n_tiles = N / 32;
+  const int zg = (B + R - 1) / R, n_units = ((n_tiles + NS - 1) / NS) * zg;
+  const int wg = fresh_wg();
+  const int logical = wg < n_units ? xcd_contiguous_id(wg, n_units) : 0;
+  const int sg = logical / zg;
+  const int kb = k_tiles * wave / kPersistWaves;
+#pragma unroll
+  for (int n = 0; n < NS; ++n) {
+    const half_t* wp = Wp + packed_frag_offset(min(sg * NS + n, n_tiles - 1), 0, k_tiles) + lane * 8;
+#pragma unroll
+    for (int u = 0; u < FR; ++u) W.w[n][u] = ld_global(reinterpret_cast<const half8*>(wp + (size_t)min(kb + u, k_tiles - 1) * 512));
+  }
+}
+
+// First half of a GEMM phase: waits for the unit's input and leaves the A tile [R][K] as fp16 in LDS (PRO_LN /
+// PRO_EMBED: normalised, and published as residual rows by strip group 0; PRO_COPY: copied, plus the
+// residual tile of the epilogue).  Returns false (uniformly for the workgroup) when a wait gave up.
+template <int R, int NS, int PRO, int EPI, int RC = 2>
+__device__ __forceinline__ bool persist_gemm_in(const PersistGemm& g, const PersistArgs& p, unsigned tag,
+                                                unsigned char* smem_raw, half_t* sRes, int* s_fail,
+                                                const PersistUnit<R, NS>& un) {
   constexpr int NW = kPersistWaves;
-  constexpr int NV = R <= 8 ? 4 : R / 2;      // accumulator registers that hold rows < R (row = 8 (v / 4) + 4 (lane / 32) + v % 4)
   constexpr int RPW = R / NW;                 // LayerNorm prologues: rows per wave
   static_assert(PRO == PRO_COPY || R == 8 || R == 16, "LayerNorm prologue: one or two rows per wave");
   static_assert(EPI != PEPI_RES || NS == 1, "the residual tile is one strip wide");
-  __shared__ __align__(16) half_t sRes[16 * 32];
   half_t* sA = reinterpret_cast<half_t*>(smem_raw);            // [R][K + 8]
-  float* red = reinterpret_cast<float*>(smem_raw);             // [NW][NS * NV][64], reused after the MFMA loop
-
-  const int tid = threadIdx.x, lane = tid & 63;
+  const int tid = fresh_tid(), lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int K = g.K, B = g.B, N = g.N;
-  const int k_tiles = K / 16, n_tiles = N / 32, pitch = K + 8;
-  const int kb = k_tiles * wave / NW, ke = k_tiles * (wave + 1) / NW;
-  const int zg = (B + R - 1) / R, sgs = (n_tiles + NS - 1) / NS, n_units = sgs * zg;
+  const int K = g.K, B = g.B, N = g.N, pitch = K + 8;
+  const int sg = un.sg, row0 = un.row0;
   const __amdgpu_buffer_rsrc_t r_in = xch_rsrc(g.in, (unsigned)B * K * 4);
-  const __amdgpu_buffer_rsrc_t r_out = xch_rsrc(g.out, (unsigned)B * N * 4);
   const __amdgpu_buffer_rsrc_t r_xout = xch_rsrc(g.xout, (unsigned)B * K * 4);
   const __amdgpu_buffer_rsrc_t r_res = xch_rsrc(g.res, (unsigned)B * N * 4);
-
-  for (int u0 = blockIdx.x; u0 < n_units; u0 += gridDim.x) {
-    // XCD-contiguous order, row group fastest: the row groups of a strip group run on one XCD and share its
-    // weight fragments in that L2
-    const int logical = n_units <= (int)gridDim.x ? xcd_contiguous_id(u0, n_units) : u0;
-    const int sg = logical / zg, zi = logical - sg * zg;
-    const int row0 = zi * R;
-
-    // 1. weight stream first: it runs under the wait for this phase's input
-    const half_t* wp[NS];
-    half8 wf[NS][FR];
-#pragma unroll
-    for (int n = 0; n < NS; ++n) {
-      wp[n] = g.Wp + packed_frag_offset(min(sg * NS + n, n_tiles - 1), 0, k_tiles) + lane * 8;
-#pragma unroll
-      for (int u = 0; u < FR; ++u)
-        wf[n][u] = *reinterpret_cast<const half8*>(wp[n] + (size_t)min(kb + u, k_tiles - 1) * 512);
-    }
-
-    // the bias of this lane's output columns travels with the weights (the epilogue would otherwise start with a
-    // memory round trip of its own)
-    constexpr int kMyNv = (NS * NV + NW - 1) / NW;
-    float bias_r[kMyNv];
-#pragma unroll
-    for (int i = 0; i < kMyNv; ++i) {
-      const int nt = sg * NS + (wave + i * NW) / NV;
-      bias_r[i] = g.bias[min(nt * 32 + (lane & 31), N - 1)];
-    }
-
-    bool fail = false;
-    // 2. prologue: the A tile [R][K] as fp16 in LDS
+  bool fail = false;
+  if (un.has) {
     if constexpr (PRO == PRO_COPY) {
       const int upr = K / 4;                         // 16-byte units (4 values) per row
       const int total = R * upr;
@@ -214,10 +321,10 @@ __device__ __forceinline__ bool persist_gemm_phase(const PersistGemm& g, const P
 #pragma unroll
       for (int c = 0; c < RC; ++c) {
         const int cc = min(c * 64 + lane, chunks - 1);
-        const float4 g0 = *reinterpret_cast<const float4*>(g.gamma + cc * 8), g1 = *reinterpret_cast<const float4*>(g.gamma + cc * 8 + 4);
-        const float4 t0 = *reinterpret_cast<const float4*>(g.beta + cc * 8), t1 = *reinterpret_cast<const float4*>(g.beta + cc * 8 + 4);
-        gm[c][0] = g0.x; gm[c][1] = g0.y; gm[c][2] = g0.z; gm[c][3] = g0.w; gm[c][4] = g1.x; gm[c][5] = g1.y; gm[c][6] = g1.z; gm[c][7] = g1.w;
-        bt[c][0] = t0.x; bt[c][1] = t0.y; bt[c][2] = t0.z; bt[c][3] = t0.w; bt[c][4] = t1.x; bt[c][5] = t1.y; bt[c][6] = t1.z; bt[c][7] = t1.w;
+        const floatx4 g0 = ld_global(reinterpret_cast<const floatx4*>(g.gamma + cc * 8)), g1 = ld_global(reinterpret_cast<const floatx4*>(g.gamma + cc * 8 + 4));
+        const floatx4 t0 = ld_global(reinterpret_cast<const floatx4*>(g.beta + cc * 8)), t1 = ld_global(reinterpret_cast<const floatx4*>(g.beta + cc * 8 + 4));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { gm[c][j] = g0[j]; gm[c][4 + j] = g1[j]; bt[c][j] = t0[j]; bt[c][4 + j] = t1[j]; }
       }
       if constexpr (PRO == PRO_EMBED) {
 #pragma unroll
@@ -229,10 +336,10 @@ __device__ __forceinline__ bool persist_gemm_phase(const PersistGemm& g, const P
 #pragma unroll
           for (int c = 0; c < RC; ++c) {
             const int cc = min(c * 64 + lane, chunks - 1);
-            const half8 e = *reinterpret_cast<const half8*>(p.tok_emb + (size_t)id * K + cc * 8);
-            const half8 q = *reinterpret_cast<const half8*>(p.pos_emb + (size_t)pos * K + cc * 8);
+            const half8 e = ld_global(reinterpret_cast<const half8*>(p.tok_emb + (size_t)id * K + cc * 8));
+            const half8 q = ld_global(reinterpret_cast<const half8*>(p.pos_emb + (size_t)pos * K + cc * 8));
             half8 s8 = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (p.seg_row) s8 = *reinterpret_cast<const half8*>(p.seg_row + cc * 8);
+            if (p.seg_row) s8 = ld_global(reinterpret_cast<const half8*>(p.seg_row + cc * 8));
             const float live = (c * 64 + lane < chunks) ? 1.f : 0.f;
 #pragma unroll
             for (int j = 0; j < 8; ++j) v[i][c][j] = ((float)e[j] + (float)q[j] + (float)s8[j]) * live;
@@ -328,225 +435,299 @@ __device__ __forceinline__ bool persist_gemm_phase(const PersistGemm& g, const P
         }
       }
     }
-    if (__syncthreads_or(fail)) return false;
+  }
+  return !persist_sync_fail(fail, s_fail);
+}
 
-    // 3. MFMA over this wave's k-tiles
-    floatx16 acc[NS];
+// Second half of a GEMM phase: MFMA over each wave's share of the contraction, cross-wave reduction through
+// LDS in a fixed order, bias / residual / GELU, and publication of the unit's outputs as tagged pairs.
+// The MFMA loop is branch-free: FR k-steps are always issued, a step past the wave's share with a zero A
+// fragment, so that all LDS fragment reads are in flight before the first product and nothing but the
+// matrix pipe paces the loop.  With one strip per workgroup the steps alternate between two accumulators
+// (a chain of dependent MFMAs issues one per result latency, not one per pass through the pipe).
+template <int R, int NS, int FR, int EPI>
+__device__ __forceinline__ void persist_gemm_out(const PersistGemm& g, unsigned tag, unsigned char* smem_raw, float* red,
+                                                 const half_t* sRes, const PersistUnit<R, NS>& un, PersistW<NS, FR>& W,
+                                                 unsigned long long* tr = nullptr, int slot0 = 0) {
+  constexpr int NW = kPersistWaves;
+  constexpr int NV = PersistUnit<R, NS>::NV, kMyNv = PersistUnit<R, NS>::kMyNv;
+  constexpr int NA = NS == 1 ? 2 : NS;        // independent accumulator chains
+  const half_t* sA = reinterpret_cast<const half_t*>(smem_raw);
+  const int tid = fresh_tid(), lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int K = g.K, B = g.B, N = g.N;
+  const int k_tiles = K / 16, n_tiles = N / 32, pitch = K + 8;
+  const int kb = k_tiles * wave / NW, ke = k_tiles * (wave + 1) / NW;      // ke - kb <= FR (host-checked)
+  const __amdgpu_buffer_rsrc_t r_out = xch_rsrc(g.out, (unsigned)B * N * 4);
+  if (un.has) {
+    floatx16 acc[NA];
 #pragma unroll
-    for (int n = 0; n < NS; ++n)
+    for (int n = 0; n < NA; ++n)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
     const half_t* ap = sA + (lane & (R - 1)) * pitch + 8 * (lane >> 5);    // tile rows R..31 repeat rows 0..R-1
-    for (int base = kb; base < ke; base += FR) {
+    // A fragments are read eight k-steps ahead of their products (all of them would cost four registers per step)
+    constexpr int kAhead = FR < 8 ? FR : 8;
+    half8 af[kAhead];
 #pragma unroll
-      for (int u = 0; u < FR; ++u)
-        if (base + u < ke) {
-          const half8 a = *reinterpret_cast<const half8*>(ap + (base + u) * 16);
+    for (int u = 0; u < kAhead; ++u) af[u] = *reinterpret_cast<const half8*>(ap + min(kb + u, k_tiles - 1) * 16);
 #pragma unroll
-          for (int n = 0; n < NS; ++n) acc[n] = mfma32(a, wf[n][u], acc[n]);
-        }
-      if (base + FR < ke) {
+    for (int u = 0; u < FR; ++u) {
+      const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+      const half8 a = (kb + u < ke) ? af[u % kAhead] : z;
+      if (u + kAhead < FR) af[u % kAhead] = *reinterpret_cast<const half8*>(ap + min(kb + u + kAhead, k_tiles - 1) * 16);
+      if constexpr (NS == 1) acc[u & 1] = mfma32(a, W.w[0][u], acc[u & 1]);
+      else {
 #pragma unroll
-        for (int n = 0; n < NS; ++n)
-#pragma unroll
-          for (int u = 0; u < FR; ++u)
-            wf[n][u] = *reinterpret_cast<const half8*>(wp[n] + (size_t)min(base + FR + u, k_tiles - 1) * 512);
+        for (int n = 0; n < NS; ++n) acc[n] = mfma32(a, W.w[n][u], acc[n]);
       }
     }
-    __syncthreads();          // all waves are done reading sA before it is reused
-
-    // 4. cross-wave reduction in a fixed order, then the epilogue
+    if constexpr (NS == 1) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[0][v] += acc[1][v];
+    }
+    persist_stamp(tr, slot0);
+    // `red` does not overlap the A tile: no barrier between the last fragment read and the first partial
 #pragma unroll
     for (int n = 0; n < NS; ++n)
 #pragma unroll
       for (int v = 0; v < NV; ++v) red[(wave * NS * NV + n * NV + v) * 64 + lane] = acc[n][v];
-    __syncthreads();
+    lds_barrier();
+    persist_stamp(tr, slot0 + 2);
 #pragma unroll
     for (int i = 0; i < kMyNv; ++i) {
       const int nv = wave + i * NW;
       if (nv >= NS * NV) break;
       const int n = nv / NV, v = nv - n * NV;
-      const int nt = sg * NS + n;
+      const int nt = un.sg * NS + n;
       float s = 0.f;
 #pragma unroll
       for (int w = 0; w < NW; ++w) s += red[(w * NS * NV + nv) * 64 + lane];
-      const int tr = mfma32_row(v, lane);                 // row inside the tile
-      const int row = row0 + tr, col = nt * 32 + (lane & 31);
-      const bool live = nt < n_tiles && tr < R && row < B;
-      float val = s + bias_r[i];
-      if constexpr (EPI == PEPI_RES) val += (float)sRes[min(tr, R - 1) * 32 + (lane & 31)];
+      const int tr_ = mfma32_row(v, lane);                // row inside the tile
+      const int row = un.row0 + tr_, col = nt * 32 + (lane & 31);
+      const bool live = nt < n_tiles && tr_ < R && row < B;
+      float val = s + un.bias_r[i];
+      if constexpr (EPI == PEPI_RES) val += (float)sRes[min(tr_, R - 1) * 32 + (lane & 31)];
       if constexpr (EPI == PEPI_GELU) val = gelu_erf_fast(val);
       const float nb = __shfl_xor(val, 1, 64);            // the odd neighbour column
       if (live && (lane & 1) == 0 && !g.withhold)
         xch_store8(r_out, ((unsigned)row * N + col) * 4, pack_h2(val, nb), tag);
     }
-    __syncthreads();          // `red` / `sRes` are free for the next unit or phase
+    persist_stamp(tr, slot0 + 3);
   }
-  return true;
+  lds_barrier();          // the A tile, `red` and the residual tile are free for the next phase
 }
 
-// Decode attention of one layer: a group of four waves per (sequence, head) stream, two streams per
-// workgroup at a time.  q, k, v of the new token come from the exchange buffer (QKV output + bias, already
-// fp16); the new key and value are appended to the cache and used from registers.  The first batch of cache
-// rows is requested before the wait for q, k, v.
+// The first batch of cache rows of a workgroup's first pair of streams, and the streams' cached length,
+// requested a phase ahead like the weight fragments.
+template <int U>
+struct PersistKV {
+  half8 k[U], v[U];
+  int len;
+};
+
 template <int U, bool NT>
-__device__ __forceinline__ bool persist_attn_phase(const PersistArgs& p, const PersistLayer& L, unsigned char* xl,
-                                                   unsigned tag, bool withhold) {
-  constexpr int NW = 4;
-  __shared__ float sm[2][NW][8][10];
-  const int tid = threadIdx.x, lane = tid & 63;
+__device__ __forceinline__ void persist_kv_issue(PersistKV<U>& F, const PersistArgs& p, const PersistLayer& L, int u0) {
+  const int tid = fresh_tid(), lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int grp = wave >> 2, w4 = wave & 3;
-  const int ec = lane & 7, team = lane >> 3;
-  const int B = p.B, H = p.H, S = p.S, d = p.d;
-  const int n_streams = B * H;
-  const __amdgpu_buffer_rsrc_t r_qkv = xch_rsrc(xl + p.xo.qkv, (unsigned)B * 3 * d * 4);
-  const __amdgpu_buffer_rsrc_t r_o = xch_rsrc(xl + p.xo.o, (unsigned)B * d * 4);
-
-  for (int u0 = blockIdx.x; u0 * 2 < n_streams; u0 += gridDim.x) {
-    const int s = u0 * 2 + grp;
-    const bool active = s < n_streams;
-    const int b = active ? s / H : 0, h = active ? s - b * H : 0;
-    // a sequence that is fed the end token (now or at an earlier step) is finished: no cache stream, no append
-    const bool done = active && p.eos >= 0 && (p.finished[b] != 0 || p.tok[b] == p.eos);
-    bool fail = false;
-    SoftmaxPart st;
-    st.m = -INFINITY; st.l = 0.f;
+  const int grp = wave >> 2, w4 = wave & 3, ec = lane & 7, team = lane >> 3;
+  const int H = p.H, S = p.S;
+  const int s = min(u0 * 2 + grp, p.B * H - 1);        // clamped: a group without a stream loads a valid one and ignores it
+  const int b = s / H, h = s - b * H;
+  const int cb = p.slot ? p.slot[b] : b;
+  const half_t* Kb = L.kc + ((size_t)cb * H + h) * S * 64 + ec * 8;
+  const half_t* Vb = L.vc + ((size_t)cb * H + h) * S * 64 + ec * 8;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) st.acc[j] = 0.f;
+  for (int u = 0; u < U; ++u) {
+    const size_t row = (size_t)min((w4 * U + u) * 8 + team, S - 1) * 64;     // clamped to the capacity, masked later
+    F.k[u] = ld_kv<NT>(Kb + row);
+    F.v[u] = ld_kv<NT>(Vb + row);
+  }
+  F.len = p.cache_len[b];
+}
 
-    if (active && !done) {
-      const int cb = p.slot ? p.slot[b] : b;
-      half_t* Kb = L.kc + ((size_t)cb * H + h) * S * 64 + ec * 8;
-      half_t* Vb = L.vc + ((size_t)cb * H + h) * S * 64 + ec * 8;
-      half8 kf[U], vf[U];
-      int key[U];
-      int g0 = w4 * U;
+// q (scaled), k, v of the new token of one stream, as the attention uses them.
+struct PersistQKV {
+  float q[8];
+  half8 knew, vnew;
+};
+
+// Waits for q, k, v of stream (b, h) in the exchange buffer; false when the wait gave up.
+__device__ __forceinline__ bool persist_qkv_wait(PersistQKV& o, const PersistArgs& p, __amdgpu_buffer_rsrc_t r_qkv, int b,
+                                                 int h, unsigned tag) {
+  const int ec = fresh_tid() & 7, d = p.d;
+  const unsigned off = ((unsigned)b * 3 * d + h * 64 + ec * 8) * 4;
+  u32x4 a[3][2];
+  unsigned spins = 0;
+  bool good = true;
+  while (true) {
+    asm volatile("" ::: "memory");
+    bool ok = true;
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+      a[t][0] = xch_load16(r_qkv, off + (unsigned)t * d * 4);
+      a[t][1] = xch_load16(r_qkv, off + (unsigned)t * d * 4 + 16);
+    }
+#pragma unroll
+    for (int t = 0; t < 3; ++t) ok &= xch_ready(a[t][0], tag) && xch_ready(a[t][1], tag);
+    if (__all(ok)) break;
+    if (++spins > p.spin_limit) { good = false; break; }
+  }
+  float qq[8];
+  unpack_h2(a[0][0][0], qq[0], qq[1]); unpack_h2(a[0][0][2], qq[2], qq[3]);
+  unpack_h2(a[0][1][0], qq[4], qq[5]); unpack_h2(a[0][1][2], qq[6], qq[7]);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o.q[j] = qq[j] * 0.125f;
+  const u32x4 kw = {a[1][0][0], a[1][0][2], a[1][1][0], a[1][1][2]};
+  const u32x4 vw = {a[2][0][0], a[2][0][2], a[2][1][0], a[2][1][2]};
+  o.knew = __builtin_bit_cast(half8, kw);
+  o.vnew = __builtin_bit_cast(half8, vw);
+  return good;
+}
+
+// One (sequence, head) stream by a group of four waves: online softmax over the cache rows in F (first batch)
+// and the batches after it, the new key / value appended and used from registers; the group's wave 0 ends up
+// with the merged state after the workgroup barrier, which the caller provides.
+template <int U, bool NT>
+__device__ __forceinline__ void persist_attn_stream(SoftmaxPart& st, const PersistKV<U>& F, const PersistQKV& x,
+                                                    half_t* Kb, half_t* Vb, int S, float (*sm)[8][10]) {
+  constexpr int NW = 4;
+  const int tid = fresh_tid(), lane = tid & 63;
+  const int w4 = __builtin_amdgcn_readfirstlane(tid >> 6) & 3;
+  const int ec = lane & 7, team = lane >> 3;
+  half8 kf[U], vf[U];
+  int key[U];
+  int g0 = w4 * U;
+#pragma unroll
+  for (int u = 0; u < U; ++u) { key[u] = (g0 + u) * 8 + team; kf[u] = F.k[u]; vf[u] = F.v[u]; }
+  const int len = F.len;
+  const bool has_new = len < S;                 // a replayed step past capacity appends nothing
+  const int c = has_new ? len + 1 : S;
+  const int newest = has_new ? len : -1;        // this key comes from registers, not from the cache
+  if (has_new && w4 == 0 && team == 0) {
+    st_global(reinterpret_cast<half8*>(Kb + (size_t)len * 64), x.knew);
+    st_global(reinterpret_cast<half8*>(Vb + (size_t)len * 64), x.vnew);
+  }
+  while (g0 * 8 < c) {
+    float sc[U];
+    float mx = st.m;
+    half8 vcur[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool valid = key[u] < c;
+      const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (key[u] == newest) { kf[u] = x.knew; vf[u] = x.vnew; }
+      float pr = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) pr += x.q[j] * (float)kf[u][j];
+      pr += __shfl_xor(pr, 1, 64);
+      pr += __shfl_xor(pr, 2, 64);
+      pr += __shfl_xor(pr, 4, 64);
+      sc[u] = valid ? pr : -INFINITY;
+      vcur[u] = valid ? vf[u] : z;               // rows past the valid length hold arbitrary bits: weight 0 must meet value 0
+      mx = fmaxf(mx, sc[u]);
+    }
+    g0 += NW * U;
+    if (g0 * 8 < c) {                            // next batch in flight during the softmax update
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         key[u] = (g0 + u) * 8 + team;
         const size_t row = (size_t)min(key[u], S - 1) * 64;
-        kf[u] = load_kv<NT>(Kb + row);
-        vf[u] = load_kv<NT>(Vb + row);
-      }
-      const int len = p.cache_len[b];
-
-      float q[8];
-      half8 knew, vnew;
-      {
-        const unsigned off = ((unsigned)b * 3 * d + h * 64 + ec * 8) * 4;
-        u32x4 a[3][2];
-        unsigned spins = 0;
-        while (true) {
-          asm volatile("" ::: "memory");
-          bool ok = true;
-#pragma unroll
-          for (int t = 0; t < 3; ++t) {
-            a[t][0] = xch_load16(r_qkv, off + (unsigned)t * d * 4);
-            a[t][1] = xch_load16(r_qkv, off + (unsigned)t * d * 4 + 16);
-          }
-#pragma unroll
-          for (int t = 0; t < 3; ++t) ok &= xch_ready(a[t][0], tag) && xch_ready(a[t][1], tag);
-          if (__all(ok)) break;
-          if (++spins > p.spin_limit) { fail = true; break; }
-        }
-        float qq[8];
-        unpack_h2(a[0][0][0], qq[0], qq[1]); unpack_h2(a[0][0][2], qq[2], qq[3]);
-        unpack_h2(a[0][1][0], qq[4], qq[5]); unpack_h2(a[0][1][2], qq[6], qq[7]);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) q[j] = qq[j] * 0.125f;
-        const u32x4 kw = {a[1][0][0], a[1][0][2], a[1][1][0], a[1][1][2]};
-        const u32x4 vw = {a[2][0][0], a[2][0][2], a[2][1][0], a[2][1][2]};
-        knew = __builtin_bit_cast(half8, kw);
-        vnew = __builtin_bit_cast(half8, vw);
-      }
-      const bool has_new = len < S;                 // a replayed step past capacity appends nothing
-      const int c = fail ? 0 : (has_new ? len + 1 : S);
-      const int newest = has_new ? len : -1;        // this key comes from registers, not from the cache
-      if (!fail && has_new && w4 == 0 && team == 0) {
-        *reinterpret_cast<half8*>(Kb + (size_t)len * 64) = knew;
-        *reinterpret_cast<half8*>(Vb + (size_t)len * 64) = vnew;
-      }
-      while (g0 * 8 < c) {
-        float sc[U];
-        float mx = st.m;
-        half8 vcur[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const bool valid = key[u] < c;
-          const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-          if (key[u] == newest) { kf[u] = knew; vf[u] = vnew; }
-          float pr = 0.f;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) pr += q[j] * (float)kf[u][j];
-          pr += __shfl_xor(pr, 1, 64);
-          pr += __shfl_xor(pr, 2, 64);
-          pr += __shfl_xor(pr, 4, 64);
-          sc[u] = valid ? pr : -INFINITY;
-          vcur[u] = valid ? vf[u] : z;
-          mx = fmaxf(mx, sc[u]);
-        }
-        g0 += NW * U;
-        if (g0 * 8 < c) {
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            key[u] = (g0 + u) * 8 + team;
-            const size_t row = (size_t)min(key[u], S - 1) * 64;
-            kf[u] = load_kv<NT>(Kb + row);
-            vf[u] = load_kv<NT>(Vb + row);
-          }
-        }
-        if (mx != -INFINITY) {
-          const float alpha = (st.m == -INFINITY) ? 0.f : __expf(st.m - mx);
-          st.l *= alpha;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            const float pr = __expf(sc[u] - mx);
-            st.l += pr;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) st.acc[j] += pr * (float)vcur[u][j];
-          }
-          st.m = mx;
-        }
-      }
-#pragma unroll
-      for (int off = 8; off < 64; off <<= 1) {
-        const float om = __shfl_xor(st.m, off, 64);
-        const float ol = __shfl_xor(st.l, off, 64);
-        float oa[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) oa[j] = __shfl_xor(st.acc[j], off, 64);
-        softmax_merge(st, om, ol, oa);
-      }
-      if (team == 0) {
-        sm[grp][w4][ec][0] = st.m; sm[grp][w4][ec][1] = st.l;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) sm[grp][w4][ec][2 + j] = st.acc[j];
+        kf[u] = ld_kv<NT>(Kb + row);
+        vf[u] = ld_kv<NT>(Vb + row);
       }
     }
-    if (__syncthreads_or(fail)) return false;
-    if (active && w4 == 0 && team == 0) {
-      float o8[8];
-      if (done) {
+    if (mx != -INFINITY) {
+      const float alpha = (st.m == -INFINITY) ? 0.f : __expf(st.m - mx);
+      st.l *= alpha;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) o8[j] = 0.f;          // the row is not used; its consumers still need the tag
-      } else {
+      for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
 #pragma unroll
-        for (int w = 1; w < NW; ++w) softmax_merge(st, sm[grp][w][ec][0], sm[grp][w][ec][1], &sm[grp][w][ec][2]);
-        const float inv = 1.0f / st.l;
+      for (int u = 0; u < U; ++u) {
+        const float pr = __expf(sc[u] - mx);
+        st.l += pr;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) o8[j] = st.acc[j] * inv;
+        for (int j = 0; j < 8; ++j) st.acc[j] += pr * (float)vcur[u][j];
       }
-      if (!withhold) {
-        const unsigned off = ((unsigned)b * d + h * 64 + ec * 8) * 4;
-        xch_store16(r_o, off, pack_h2(o8[0], o8[1]), pack_h2(o8[2], o8[3]), tag);
-        xch_store16(r_o, off + 16, pack_h2(o8[4], o8[5]), pack_h2(o8[6], o8[7]), tag);
-      }
+      st.m = mx;
     }
-    __syncthreads();          // `sm` is free for the next pair of streams
   }
+#pragma unroll
+  for (int off = 8; off < 64; off <<= 1) {
+    const float om = __shfl_xor(st.m, off, 64);
+    const float ol = __shfl_xor(st.l, off, 64);
+    float oa[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) oa[j] = __shfl_xor(st.acc[j], off, 64);
+    softmax_merge(st, om, ol, oa);
+  }
+  if (team == 0) {
+    sm[w4][ec][0] = st.m; sm[w4][ec][1] = st.l;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sm[w4][ec][2 + j] = st.acc[j];
+  }
+}
+
+// Publishes one stream's attention output (merged over the group's waves) as tagged pairs; a finished
+// sequence's row is zeros (unused, but its consumers still wait for the tag).
+__device__ __forceinline__ void persist_attn_publish(SoftmaxPart& st, float (*sm)[8][10], bool done, bool withhold,
+                                                     __amdgpu_buffer_rsrc_t r_o, int b, int h, int d, unsigned tag) {
+  const int ec = fresh_tid() & 7;
+  float o8[8];
+  if (done) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o8[j] = 0.f;
+  } else {
+#pragma unroll
+    for (int w = 1; w < 4; ++w) softmax_merge(st, sm[w][ec][0], sm[w][ec][1], &sm[w][ec][2]);
+    const float inv = 1.0f / st.l;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o8[j] = st.acc[j] * inv;
+  }
+  if (!withhold) {
+    const unsigned off = ((unsigned)b * d + h * 64 + ec * 8) * 4;
+    xch_store16(r_o, off, pack_h2(o8[0], o8[1]), pack_h2(o8[2], o8[3]), tag);
+    xch_store16(r_o, off + 16, pack_h2(o8[4], o8[5]), pack_h2(o8[6], o8[7]), tag);
+  }
+}
+
+// Attention of pair `u0` of streams (two groups of four waves).  With `F_ready` the first batch of cache rows is
+// already in F (requested a phase ago); otherwise it is requested here.  `x` holds q, k, v when `x_ready`.
+template <int U, bool NT>
+__device__ __forceinline__ bool persist_attn_pair(const PersistArgs& p, const PersistLayer& L, unsigned char* xl, unsigned tag,
+                                                  bool withhold, int u0, PersistKV<U>& F, bool F_ready, PersistQKV& x,
+                                                  bool x_ready, bool x_good, float (*sm_all)[4][8][10], int* s_fail,
+                                                  unsigned long long* tr = nullptr) {
+  const int tid = fresh_tid(), lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2, w4 = wave & 3, ec = lane & 7, team = lane >> 3;
+  const int B = p.B, H = p.H, S = p.S, d = p.d, n_streams = B * H;
+  const __amdgpu_buffer_rsrc_t r_qkv = xch_rsrc(xl + p.xo.qkv, (unsigned)B * 3 * d * 4);
+  const __amdgpu_buffer_rsrc_t r_o = xch_rsrc(xl + p.xo.o, (unsigned)B * d * 4);
+  const int s = u0 * 2 + grp;
+  const bool active = s < n_streams;
+  const int sc = min(s, n_streams - 1), b = sc / H, h = sc - b * H;
+  // a sequence that is fed the end token (now or at an earlier step) is finished: no cache stream, no append
+  const bool done = active && p.eos >= 0 && (p.finished[b] != 0 || p.tok[b] == p.eos);
+  persist_stamp(tr, 28);
+  if (!F_ready) persist_kv_issue<U, NT>(F, p, L, u0);
+  bool good = x_good;
+  if (!x_ready && active && !done) good = persist_qkv_wait(x, p, r_qkv, b, h, tag);
+  SoftmaxPart st;
+  st.m = -INFINITY; st.l = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) st.acc[j] = 0.f;
+  if (active && !done && good) {
+    const int cb = p.slot ? p.slot[b] : b;
+    half_t* Kb = L.kc + ((size_t)cb * H + h) * S * 64 + ec * 8;
+    half_t* Vb = L.vc + ((size_t)cb * H + h) * S * 64 + ec * 8;
+    persist_attn_stream<U, NT>(st, F, x, Kb, Vb, S, sm_all[grp]);
+  }
+  persist_stamp(tr, 29);
+  if (persist_sync_fail(!good, s_fail)) return false;
+  persist_stamp(tr, 30);
+  if (active && w4 == 0 && team == 0) persist_attn_publish(st, sm_all[grp], done, withhold, r_o, b, h, d, tag);
+  lds_barrier();          // `sm` is free for the next pair of streams
   return true;
 }
 
@@ -554,13 +735,13 @@ __device__ __forceinline__ bool persist_attn_phase(const PersistArgs& p, const P
 // buffer and writes the plain fp16 rows the projection kernel reads (and the caller's fp32 copy).
 template <int RC>
 __device__ __forceinline__ bool persist_final_ln(const PersistArgs& p, const PersistLayer& L, const unsigned char* y2,
-                                                 unsigned tag) {
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+                                                 unsigned tag, int* s_fail) {
+  const int tid = fresh_tid(), lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int d = p.d, B = p.B, chunks = d / 8;
   const __amdgpu_buffer_rsrc_t r_in = xch_rsrc(y2, (unsigned)B * d * 4);
   bool fail = false;
-  for (int r = blockIdx.x * kPersistWaves + wave; r < B; r += gridDim.x * kPersistWaves) {
+  for (int r = blockIdx.x * kPersistWaves + wave; r < B; r += p.helpers_from * kPersistWaves) {
     u32x4 a[RC][2];
     unsigned spins = 0;
     while (true) {
@@ -597,65 +778,241 @@ __device__ __forceinline__ bool persist_final_ln(const PersistArgs& p, const Per
       }
     }
   }
-  return !__syncthreads_or(fail);
+  return !persist_sync_fail(fail, s_fail);
 }
 
-// RPW: rows per wave of the LayerNorm prologues (1 for B <= 32, 2 above); FR5: weight fragments in flight per
-// wave in the second FFN GEMM, whose contraction is the FFN width (8 per 1024 of it).
-template <int RPW, int FR5>
-__global__ __launch_bounds__(kPersistThreads) void decode_persist_kernel(PersistArgs p) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
+// ---------------------------------------------------------------- helper workgroups
+// Workgroups past the largest phase never own a unit.  They run ahead of the others and pull what the coming
+// phases will read out of HBM into the L2 of the XCD that will read it (workgroup ids congruent mod 8 share an
+// XCD, and a unit's workgroup is known in advance): one 4-byte load per 64 bytes, values discarded.  Their own
+// loads queue behind their touches, which delays nobody.  The others then request their weight fragments and
+// cache rows at the usual place and find them in L2.
+//
+// Touches up to 16 x 32 KB of [base, base + bytes) (the rest is left to the consumer).
+__device__ __forceinline__ void persist_helper_touch(const unsigned char* base, size_t bytes) {
+  if (bytes == 0) return;
+  const size_t lines = (bytes + 63) / 64;
+  const int tid = threadIdx.x;
+  constexpr int kFlight = 16;
+  for (size_t l0 = 0; l0 < lines; l0 += (size_t)kFlight * kPersistThreads) {
+    unsigned t[kFlight];
+#pragma unroll
+    for (int q = 0; q < kFlight; ++q) {
+      const size_t line = min(l0 + (size_t)q * kPersistThreads + tid, lines - 1);     // clamped: all loads issue together
+      t[q] = ld_global(reinterpret_cast<const unsigned*>(base + line * 64));
+    }
+#pragma unroll
+    for (int q = 0; q < kFlight; ++q) asm volatile("" ::"v"(t[q]));
+  }
+}
+
+// The packed weight strips that XCD `x` will read in a GEMM phase with `n_tiles` strips in groups of NS and zg row
+// groups (units in XCD-contiguous order), share `rank` of `count`.
+__device__ __forceinline__ void persist_helper_weights(const half_t* Wp, int n_tiles, int K, int NS, int zg, int grid, int x,
+                                                       int rank, int count) {
+  const int n_units = ((n_tiles + NS - 1) / NS) * zg;
+  if (n_units > grid) return;
+  const int q = n_units >> 3, r = n_units & 7;
+  const int lo = x * q + min(x, r), cnt = q + (x < r ? 1 : 0);
+  if (cnt <= 0) return;
+  const int s_lo = (lo / zg) * NS, s_hi = min(((lo + cnt - 1) / zg + 1) * NS, n_tiles);
+  if (s_hi <= s_lo) return;
+  const size_t strip = (size_t)K * 64, all = (size_t)(s_hi - s_lo) * strip;
+  const size_t part = (all / count + 63) / 64 * 64, off = min(part * rank, all);
+  persist_helper_touch(reinterpret_cast<const unsigned char*>(Wp) + (size_t)s_lo * strip + off, min(part, all - off));
+}
+
+// Waits (bounded) until the first pair of an exchange matrix carries this step's tag; false on give-up.
+__device__ __forceinline__ bool persist_helper_wait(const unsigned char* buf, unsigned tag, unsigned limit) {
+  const __amdgpu_buffer_rsrc_t r = xch_rsrc(buf, 16);
+  unsigned spins = 0;
+  while (true) {
+    asm volatile("" ::: "memory");
+    const u32x4 v = xch_load16(r, 0);
+    if (v[1] == tag) return true;
+    if (++spins > limit) return false;
+    __builtin_amdgcn_s_sleep(8);
+  }
+}
+
+template <int RPW>
+__device__ __forceinline__ void persist_helper(const PersistArgs& p, unsigned tag) {
+  constexpr int R = 8 * RPW, R5 = 4 * RPW;
+  const int grid = p.helpers_from;                 // workgroups that own units
+  const int wg = blockIdx.x, x = wg & 7, rank = (wg - p.helpers_from) >> 3, count = ((int)gridDim.x - p.helpers_from) >> 3;
+  const int d = p.d, f = p.f, B = p.B, H = p.H, S = p.S;
+  const int zg = (B + R - 1) / R, zg5 = (B + R5 - 1) / R5;
+  const int n_streams = B * H, rows = min(S, p.kv_rows);
+  const int lookahead = 3;                         // phases between a touch and its use
+  for (int t = 0; t < 5 * p.n_layers; ++t) {
+    const int l = t / 5, ph = t - 5 * l;
+    if (t >= lookahead) {                          // stay `lookahead` phases ahead of the publishing front
+      const int tw = t - lookahead, lw = tw / 5, pw = tw - 5 * lw;
+      const unsigned char* xw = p.xch + (size_t)lw * p.xo.layer_bytes;
+      const unsigned off = pw == 0 ? p.xo.qkv : pw == 1 ? p.xo.o : pw == 2 ? p.xo.y1 : pw == 3 ? p.xo.g : p.xo.y2;
+      if (!persist_helper_wait(xw + off, tag, p.spin_limit)) return;
+    }
+    const PersistLayer L = p.layers[l];
+    if (ph == 0) persist_helper_weights(as_global(L.wqkv), 3 * d / 32, d, 2, zg, grid, x, rank, count);
+    else if (ph == 2) persist_helper_weights(as_global(L.wo), d / 32, d, 1, zg, grid, x, rank, count);
+    else if (ph == 3) persist_helper_weights(as_global(L.w1), f / 32, d, 2, zg, grid, x, rank, count);
+    else if (ph == 4) persist_helper_weights(as_global(L.w2), d / 32, f, 1, zg5, grid, x, rank, count);
+    else {
+      // attention: unit u (streams 2u, 2u + 1) runs on workgroup u % grid; this XCD's units are those congruent
+      // to x mod 8 (grid is a multiple of 8).  Items = (unit, stream, K | V), dealt round-robin to the helpers.
+      const int n_units = (n_streams + 1) / 2;
+      const int mine = (n_units - x + 7) / 8;      // units of this XCD
+      for (int i = rank; i < mine * 4; i += count) {
+        const int u = x + 8 * (i >> 2), s = 2 * u + ((i >> 1) & 1);
+        if (s >= n_streams) continue;
+        const int b = s / H, h = s - b * H;
+        const int cb = p.slot ? p.slot[b] : b;
+        const half_t* base = ((i & 1) ? as_global(L.vc) : as_global(L.kc)) + ((size_t)cb * H + h) * S * 64;
+        persist_helper_touch(reinterpret_cast<const unsigned char*>(base), (size_t)rows * 128);
+      }
+    }
+  }
+}
+
+// RPW: rows per wave of the LayerNorm prologues (1 for B <= 32, 2 above); FRD / FR5: weight fragments per wave
+// and strip in the GEMMs whose contraction is the model width / the FFN width (one per 128 of it); U: cache-row
+// groups in flight per wave of the attention (a batch covers 32 U keys).
+// Order inside a phase: request this phase's weight fragments, wait for the phase's input, compute, publish.
+template <int RPW, int FRD, int FR5, int U>
+__global__ __launch_bounds__(kPersistThreads) void decode_persist_kernel(PersistArgs p_in) {
+  PersistArgs p = p_in;             // (pointers inside a by-value struct argument are not known to be global)
+  p.layers = as_global(p.layers); p.tok = as_global(p.tok); p.cache_len = as_global(p.cache_len);
+  p.tok_emb = as_global(p.tok_emb); p.pos_emb = as_global(p.pos_emb); p.seg_row = as_global(p.seg_row);
+  p.emb_g = as_global(p.emb_g); p.emb_b = as_global(p.emb_b); p.finished = as_global(p.finished);
+  p.slot = as_global(p.slot); p.xch = as_global(p.xch); p.epoch = as_global(p.epoch); p.X = as_global(p.X);
+  p.hidden_out = as_global(p.hidden_out); p.err = as_global(p.err); p.trace = as_global(p.trace);
+  extern __shared__ __align__(16) unsigned char smem_raw[];      // the A tile, then `red` behind it (p.red_off)
+  __shared__ __align__(16) half_t sRes[16 * 32];
+  __shared__ float sm[2][4][8][10];
+  __shared__ int s_fail;
+  if (threadIdx.x == 0) s_fail = 0;
+  lds_barrier();
+  float* red = reinterpret_cast<float*>(smem_raw + p.red_off);
   constexpr int R = 8 * RPW;        // rows per workgroup of the GEMM phases whose contraction is d
   constexpr int R5 = 4 * RPW;       // ... of the second FFN GEMM: its input row is four times as long
   const unsigned tag = *p.epoch + 1u;
   const int d = p.d, f = p.f, B = p.B;
+  const int me = blockIdx.x;
+  const int n_streams = B * p.H;
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const bool no_w = (p.dbg & 2) != 0;
+  if ((int)blockIdx.x >= p.helpers_from) {       // uniform for the workgroup
+    if (!(p.dbg & 1)) persist_helper<RPW>(p, tag);
+    return;
+  }
   bool ok = true;
-  for (int l = 0; l < p.n_layers && ok; ++l) {
-    const PersistLayer L = p.layers[l];
+  // Weight fragments are requested at the start of their phase, before the wait for its input.  (Requesting them a
+  // phase earlier, across the hand-over wait, needs two sets of fragments alive at once: up to 160 registers, which
+  // the allocator answered with hundreds of spills -- and a spill reload waits for every outstanding load.)  The
+  // helper workgroups have pulled them into this XCD's L2 by then.
+  for (int l = 0; l < p.n_layers; ++l) {
+    PersistLayer L = p.layers[l];
+    L.wqkv = as_global(L.wqkv); L.wo = as_global(L.wo); L.w1 = as_global(L.w1); L.w2 = as_global(L.w2);
+    L.bqkv = as_global(L.bqkv); L.bo = as_global(L.bo); L.b1 = as_global(L.b1); L.b2 = as_global(L.b2);
+    L.ln1_g = as_global(L.ln1_g); L.ln1_b = as_global(L.ln1_b); L.ln2_g = as_global(L.ln2_g); L.ln2_b = as_global(L.ln2_b);
+    L.kc = as_global(L.kc); L.vc = as_global(L.vc);
     unsigned char* xl = p.xch + (size_t)l * p.xo.layer_bytes;
     const bool hook = l == 0;
+    unsigned long long* tr = p.trace ? p.trace + ((size_t)blockIdx.x * p.n_layers + l) * 32 : nullptr;
+    persist_stamp(tr, 0);
+    if (tr && l == 0 && threadIdx.x == 0) tr[15] = clock64();      // shader clock at the start (slot 15 of layer 0)
     {  // phase 1: QKV = LayerNorm(previous layer's sum, or the embedding) x Wqkv^T + bqkv
       PersistGemm g{};
       g.Wp = L.wqkv; g.N = 3 * d; g.K = d; g.B = B; g.eps = p.eps;
       g.xout = xl + p.xo.x; g.bias = L.bqkv; g.out = xl + p.xo.qkv; g.withhold = hook && p.stall == 1;
+      PersistW<2, FRD> w_qkv;
+      persist_w_issue<R, 2, FRD>(w_qkv, L.wqkv, 3 * d, d, B, no_w);
+      const PersistUnit<R, 2> un = persist_unit<R, 2>(3 * d, B, L.bqkv);
       if (l == 0) {
         g.gamma = p.emb_g; g.beta = p.emb_b;
-        ok = persist_gemm_phase<R, 2, 8, PRO_EMBED, PEPI_BIAS>(g, p, tag, smem_raw);
+        ok = persist_gemm_in<R, 2, PRO_EMBED, PEPI_BIAS>(g, p, tag, smem_raw, sRes, &s_fail, un);
       } else {
         const PersistLayer P = p.layers[l - 1];
-        g.in = xl - p.xo.layer_bytes + p.xo.y2; g.gamma = P.ln2_g; g.beta = P.ln2_b;
-        ok = persist_gemm_phase<R, 2, 8, PRO_LN, PEPI_BIAS>(g, p, tag, smem_raw);
+        g.in = xl - p.xo.layer_bytes + p.xo.y2; g.gamma = as_global(P.ln2_g); g.beta = as_global(P.ln2_b);
+        ok = persist_gemm_in<R, 2, PRO_LN, PEPI_BIAS>(g, p, tag, smem_raw, sRes, &s_fail, un);
       }
+      if (!ok) break;
+      persist_stamp(tr, 1);
+      persist_gemm_out<R, 2, FRD, PEPI_BIAS>(g, tag, smem_raw, red, sRes, un, w_qkv, tr, 16);
     }
-    if (!ok) break;
-    // phase 2: attention over the cache
-    ok = p.attn_nt ? persist_attn_phase<4, true>(p, L, xl, tag, hook && p.stall == 2)
-                   : persist_attn_phase<4, false>(p, L, xl, tag, hook && p.stall == 2);
-    if (!ok) break;
+    persist_stamp(tr, 2); persist_stamp(tr, 3);
+    {  // phase 2: attention over the cache
+      const __amdgpu_buffer_rsrc_t r_qkv = xch_rsrc(xl + p.xo.qkv, (unsigned)B * 3 * d * 4);
+      PersistKV<U> kv;
+      if (p.attn_nt) persist_kv_issue<U, true>(kv, p, L, me); else persist_kv_issue<U, false>(kv, p, L, me);
+      PersistQKV x;
+      bool good = true;
+      {
+        const int s = me * 2 + (wave >> 2);
+        const int sc = min(s, n_streams - 1), b = sc / p.H, h = sc - b * p.H;
+        const bool done = p.eos >= 0 && (p.finished[b] != 0 || p.tok[b] == p.eos);
+        if (s < n_streams && !done) good = persist_qkv_wait(x, p, r_qkv, b, h, tag);
+      }
+      persist_stamp(tr, 4);
+      const bool wh = hook && p.stall == 2;
+      if (me * 2 < n_streams)
+        ok = p.attn_nt ? persist_attn_pair<U, true>(p, L, xl, tag, wh, me, kv, true, x, true, good, sm, &s_fail, tr)
+                       : persist_attn_pair<U, false>(p, L, xl, tag, wh, me, kv, true, x, true, good, sm, &s_fail, tr);
+      for (int u0 = me + p.helpers_from; ok && u0 * 2 < n_streams; u0 += p.helpers_from)
+        ok = p.attn_nt ? persist_attn_pair<U, true>(p, L, xl, tag, wh, u0, kv, false, x, false, true, sm, &s_fail)
+                       : persist_attn_pair<U, false>(p, L, xl, tag, wh, u0, kv, false, x, false, true, sm, &s_fail);
+      if (!ok) break;
+    }
+    persist_stamp(tr, 5); persist_stamp(tr, 6);
     {  // phase 3: y1 = O x Wo^T + bo + x
       PersistGemm g{};
       g.Wp = L.wo; g.N = d; g.K = d; g.B = B; g.in = xl + p.xo.o; g.bias = L.bo; g.res = xl + p.xo.x;
       g.out = xl + p.xo.y1; g.withhold = hook && p.stall == 3;
-      ok = persist_gemm_phase<R, 1, 8, PRO_COPY, PEPI_RES>(g, p, tag, smem_raw);
+      PersistW<1, FRD> w_o;
+      persist_w_issue<R, 1, FRD>(w_o, L.wo, d, d, B, no_w);
+      const PersistUnit<R, 1> un = persist_unit<R, 1>(d, B, L.bo);
+      ok = persist_gemm_in<R, 1, PRO_COPY, PEPI_RES>(g, p, tag, smem_raw, sRes, &s_fail, un);
+      if (!ok) break;
+      persist_stamp(tr, 7);
+      persist_gemm_out<R, 1, FRD, PEPI_RES>(g, tag, smem_raw, red, sRes, un, w_o);
     }
-    if (!ok) break;
+    persist_stamp(tr, 8); persist_stamp(tr, 9);
     {  // phase 4: G = gelu(LayerNorm(y1) x W1^T + b1)
       PersistGemm g{};
       g.Wp = L.w1; g.N = f; g.K = d; g.B = B; g.eps = p.eps; g.in = xl + p.xo.y1; g.gamma = L.ln1_g; g.beta = L.ln1_b;
       g.xout = xl + p.xo.x1; g.bias = L.b1; g.out = xl + p.xo.g; g.withhold = hook && p.stall == 4;
-      ok = persist_gemm_phase<R, 2, 8, PRO_LN, PEPI_GELU>(g, p, tag, smem_raw);
+      PersistW<2, FRD> w_1;
+      persist_w_issue<R, 2, FRD>(w_1, L.w1, f, d, B, no_w);
+      const PersistUnit<R, 2> un = persist_unit<R, 2>(f, B, L.b1);
+      ok = persist_gemm_in<R, 2, PRO_LN, PEPI_GELU>(g, p, tag, smem_raw, sRes, &s_fail, un);
+      if (!ok) break;
+      persist_stamp(tr, 10);
+      persist_gemm_out<R, 2, FRD, PEPI_GELU>(g, tag, smem_raw, red, sRes, un, w_1, tr, 20);
     }
-    if (!ok) break;
+    persist_stamp(tr, 11); persist_stamp(tr, 12);
     {  // phase 5: y2 = G x W2^T + b2 + x1
       PersistGemm g{};
       g.Wp = L.w2; g.N = d; g.K = f; g.B = B; g.in = xl + p.xo.g; g.bias = L.b2; g.res = xl + p.xo.x1;
       g.out = xl + p.xo.y2; g.withhold = hook && p.stall == 5;
-      ok = persist_gemm_phase<R5, 1, FR5, PRO_COPY, PEPI_RES>(g, p, tag, smem_raw);
+      PersistW<1, FR5> w_2;
+      persist_w_issue<R5, 1, FR5>(w_2, L.w2, d, f, B, no_w);
+      const PersistUnit<R5, 1> un = persist_unit<R5, 1>(d, B, L.b2);
+      ok = persist_gemm_in<R5, 1, PRO_COPY, PEPI_RES>(g, p, tag, smem_raw, sRes, &s_fail, un);
+      if (!ok) break;
+      persist_stamp(tr, 13);
+      persist_gemm_out<R5, 1, FR5, PEPI_RES>(g, tag, smem_raw, red, sRes, un, w_2, tr, 24);
     }
+    persist_stamp(tr, 14);
   }
   if (ok) {
     const int last = p.n_layers - 1;
-    ok = persist_final_ln<2>(p, p.layers[last], p.xch + (size_t)last * p.xo.layer_bytes + p.xo.y2, tag);
+    PersistLayer L = p.layers[last];
+    L.ln2_g = as_global(L.ln2_g); L.ln2_b = as_global(L.ln2_b);
+    ok = persist_final_ln<2>(p, L, p.xch + (size_t)last * p.xo.layer_bytes + p.xo.y2, tag, &s_fail);
+  }
+  if (p.trace && threadIdx.x == 0) {       // shader-clock reading next to the last 100 MHz stamp: slot 15 of the last layer
+    unsigned long long* row = p.trace + ((size_t)blockIdx.x * p.n_layers + (p.n_layers - 1)) * 32;
+    row[15] = clock64();
   }
   if (!ok && threadIdx.x == 0) *p.err = 1;
 }

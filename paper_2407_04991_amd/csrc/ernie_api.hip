@@ -33,6 +33,7 @@ constexpr int kFusedMaxBatch = 64;     // the fused-prologue decode path keeps t
 constexpr int kBigMaxSplitK = 8;       // partial buffers of the raw fp32 GEMM outputs
 constexpr size_t kMaxLds = 160 * 1024;
 constexpr size_t kPersistMaxLds = kMaxLds - 8 * 1024;
+constexpr int kPersistTraceGroups = 512;   // workgroups the time-stamp trace of the one-launch decode kernel has room for
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -70,7 +71,7 @@ struct ArenaPlan {
   bool has_type, has_head, has_bias;
   size_t kv, X, X1, Y, Q, O, G, Yf, hlast, strip_val, strip_idx, cu, lens, tok_seq, tok_pos, tok_prev;
   size_t finished, slot, keep, r_logits;
-  size_t xch, ptab, epoch;               // one-launch decode step: exchange buffers, layer table, step counter
+  size_t xch, ptab, epoch, trace;        // one-launch decode step: exchange buffers, layer table, step counter
   PersistXch xo; int xch_batch;          // offsets inside a layer's exchange region and its row capacity (0 = none)
   size_t total;
   int vocab_tiles, strips;
@@ -132,6 +133,7 @@ ArenaPlan make_plan(const ErnieConfig& c, const ErnieVariants* var) {
     p.xch = take((size_t)p.xo.layer_bytes * c.n_layers);
     p.ptab = take(p.xch_batch ? sizeof(PersistLayer) * c.n_layers : 0);
     p.epoch = take(256);
+    p.trace = take(p.xch_batch ? (size_t)kPersistTraceGroups * c.n_layers * 32 * 8 : 0);
   }
   p.total = off;
   return p;
@@ -200,7 +202,7 @@ struct ErnieHandle {
   int B, max_len, steps;
   unsigned char* static_scratch = nullptr;
   // one-launch decode step (decode_persist.h)
-  int persist = 1, persist_stall = 0, cu_count = 0;
+  int persist = 1, persist_stall = 0, persist_trace = 0, persist_dbg = 0, persist_helpers = 1, cu_count = 0;
   unsigned persist_spin = 1u << 17;
   unsigned char* xch = nullptr; PersistLayer* ptab = nullptr; unsigned* epoch = nullptr;
   std::vector<PersistLayer> ptab_host;   // source of the asynchronous copy into `ptab`: lives as long as the handle
@@ -393,8 +395,9 @@ int configure_kernels() {
 #undef LN_LDS1
 #undef LN_LDS2
   // (the one-launch kernel also holds a few KB of statically declared LDS)
-#define PERSIST_LDS(RPW) rc |= allow_lds(decode_persist_kernel<RPW, 8>, kPersistMaxLds); rc |= allow_lds(decode_persist_kernel<RPW, 16>, kPersistMaxLds); \
-  rc |= allow_lds(decode_persist_kernel<RPW, 24>, kPersistMaxLds); rc |= allow_lds(decode_persist_kernel<RPW, 32>, kPersistMaxLds)
+#define PERSIST_LDS(RPW) rc |= allow_lds(decode_persist_kernel<RPW, 6, 24, 6>, kPersistMaxLds); rc |= allow_lds(decode_persist_kernel<RPW, 8, 8, 6>, kPersistMaxLds); \
+  rc |= allow_lds(decode_persist_kernel<RPW, 8, 16, 6>, kPersistMaxLds); rc |= allow_lds(decode_persist_kernel<RPW, 8, 24, 6>, kPersistMaxLds); \
+  rc |= allow_lds(decode_persist_kernel<RPW, 8, 32, 6>, kPersistMaxLds)
   PERSIST_LDS(1); PERSIST_LDS(2);
 #undef PERSIST_LDS
   rc |= allow_lds(gemm_dec_kernel<1, 8, EPI_RAW>, kMaxLds);
@@ -632,7 +635,13 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
 // The whole layer stack of a small-batch decode step as ONE persistent kernel (decode_persist.h), followed by
 // the output projection.  Shapes it takes: whatever the small-batch path takes, FFN width up to 4096.
 bool persist_decode_fits(const ErnieHandle* h, int B) {
-  return h->persist && h->xch && B <= h->plan.xch_batch && fused_decode_fits(h, B) && h->cfg.d_ffn <= 4096 && h->cu_count > 0;
+  if (!(h->persist && h->xch && B <= h->plan.xch_batch && fused_decode_fits(h, B) && h->cfg.d_ffn <= 4096 && h->cu_count > 0))
+    return false;
+  // every GEMM phase is one unit per workgroup: (strips / strips per unit) x row groups <= workgroups
+  const int d = h->cfg.d_model, f = h->cfg.d_ffn, rpw = B > 32 ? 2 : 1;
+  const int zg = (B + 8 * rpw - 1) / (8 * rpw), zg5 = (B + 4 * rpw - 1) / (4 * rpw);
+  const int units = std::max(std::max(((3 * d / 32 + 1) / 2) * zg, ((f / 32 + 1) / 2) * zg), (d / 32) * zg5);
+  return units <= h->cu_count;
 }
 
 int decode_layers_persist(ErnieHandle* h, const int* tok, float* logits_out, float* hidden_out, hipStream_t s) {
@@ -645,19 +654,41 @@ int decode_layers_persist(ErnieHandle* h, const int* tok, float* logits_out, flo
   a.max_pos = c.max_pos; a.vocab_kept = c.vocab_kept; a.eos = h->eos; a.finished = h->finished;
   a.slot = h->compacted ? h->slot : nullptr;
   a.xch = h->xch; a.xo = h->plan.xo; a.epoch = h->epoch; a.X = h->X; a.hidden_out = hidden_out;
+  a.dbg = h->persist_dbg;
+  a.trace = (h->persist_trace && h->cu_count <= kPersistTraceGroups)
+                ? reinterpret_cast<unsigned long long*>(h->arena + h->plan.trace) : nullptr;
   a.err = h->err_host; a.spin_limit = h->persist_spin; a.stall = h->persist_stall; a.attn_nt = h->attn_nt;
   const int rpw = B > 32 ? 2 : 1;
-  const size_t lds_a = (size_t)8 * rpw * (d + 8) * 2, lds_5 = (size_t)4 * rpw * (f + 8) * 2, lds_r = (size_t)8 * 2 * 8 * 256;
-  const size_t lds = std::max(std::max(lds_a, lds_5), lds_r);
+  // dynamic LDS: the largest A tile ([8 or 16 rows][d + 8], [4 or 8 rows][f + 8] fp16), then the cross-wave
+  // reduction buffer [8 waves][2 strips x 4 or 8 registers][64 lanes] fp32
+  const size_t lds_a = (size_t)8 * rpw * (d + 8) * 2, lds_5 = (size_t)4 * rpw * (f + 8) * 2, lds_r = (size_t)8 * 2 * 4 * rpw * 256;
+  const size_t red_off = (std::max(lds_a, lds_5) + 255) / 256 * 256;
+  const size_t lds = red_off + lds_r;
+  a.red_off = (unsigned)red_off;
+  {
+    // workgroups past the largest phase (rounded up to a multiple of 8, so that ids congruent mod 8 keep their
+    // XCD) own no unit: they warm the L2 for the others.  The attention may take several rounds of the grid.
+    const int zg = (B + 8 * rpw - 1) / (8 * rpw), zg5 = (B + 4 * rpw - 1) / (4 * rpw);
+    int busy = std::max(std::max(((3 * d / 32 + 1) / 2) * zg, ((f / 32 + 1) / 2) * zg), (d / 32) * zg5);
+    busy = std::max(busy, std::min((B * c.n_heads + 1) / 2, h->cu_count * 3 / 4));
+    busy = (busy + 7) / 8 * 8;
+    a.helpers_from = (h->persist_helpers && h->cu_count % 8 == 0 && h->cu_count - busy >= 8) ? busy : h->cu_count;
+    a.kv_rows = std::min(c.max_seq, h->max_len + h->steps + 1);
+  }
   if (lds > kPersistMaxLds) return ERNIE_EINVAL;
   {
     const double w_bytes = (double)c.n_layers * (4.0 * d * d + 2.0 * d * f) * 2.0;
     const double kv_bytes = (double)c.n_layers * 2.0 * (h->sum_len + (double)B * (h->steps + 1)) * d * 2.0;
     ProfScope prof(h, ERNIE_PROF_DEC_PERSIST, s, w_bytes + kv_bytes, 2.0 * B * (4.0 * d * d + 2.0 * d * f) * c.n_layers);
     const dim3 grid(h->cu_count), block(kPersistThreads);
-#define PERSIST_LAUNCH(RPW, FR5) hipLaunchKernelGGL((decode_persist_kernel<RPW, FR5>), grid, block, lds, s, a)
-#define PERSIST_BY_F(RPW) do { if (f <= 1024) PERSIST_LAUNCH(RPW, 8); else if (f <= 2048) PERSIST_LAUNCH(RPW, 16); \
-                               else if (f <= 3072) PERSIST_LAUNCH(RPW, 24); else PERSIST_LAUNCH(RPW, 32); } while (0)
+    // attention: the first batch of cache rows, requested before q, k, v arrive, covers 192 keys (six groups per
+    // wave); a longer cache is streamed in further batches
+    // fragment registers per wave: one per 128 of the contraction (6 for the 768-wide model, else 8; the FFN
+    // width in steps of 1024)
+#define PERSIST_LAUNCH(RPW, FRD, FR5) hipLaunchKernelGGL((decode_persist_kernel<RPW, FRD, FR5, 6>), grid, block, lds, s, a)
+#define PERSIST_BY_F(RPW) do { if (d <= 768 && f > 2048 && f <= 3072) PERSIST_LAUNCH(RPW, 6, 24); else if (f <= 1024) PERSIST_LAUNCH(RPW, 8, 8); \
+                               else if (f <= 2048) PERSIST_LAUNCH(RPW, 8, 16); else if (f <= 3072) PERSIST_LAUNCH(RPW, 8, 24); \
+                               else PERSIST_LAUNCH(RPW, 8, 32); } while (0)
     if (rpw == 1) PERSIST_BY_F(1); else PERSIST_BY_F(2);
 #undef PERSIST_BY_F
 #undef PERSIST_LAUNCH
@@ -930,6 +961,7 @@ int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* w, const E
     // tags start at zero everywhere, so that the first step's tag (1) is new to every pair
     copies_ok &= hipMemsetAsync(h->xch, 0, (size_t)plan.xo.layer_bytes * cfg->n_layers, s) == hipSuccess;
     copies_ok &= hipMemsetAsync(h->epoch, 0, 256, s) == hipSuccess;
+    copies_ok &= hipMemsetAsync(a + plan.trace, 0, (size_t)kPersistTraceGroups * cfg->n_layers * 32 * 8, s) == hipSuccess;
     h->ptab_host.resize(cfg->n_layers);
     for (int l = 0; l < cfg->n_layers; ++l) {
       const LayerPtrs& L = h->layers[l];
@@ -1208,6 +1240,8 @@ int ernie_debug_buffer(ErnieHandle* h, const char* name, void** ptr_dev, size_t*
     *ptr_dev = h->kv; *bytes = (size_t)c.n_layers * 2 * c.max_batch * c.max_seq * c.d_model * 2;
   } else if (!strcmp(name, "lens")) {
     *ptr_dev = h->lens; *bytes = (size_t)c.max_batch * 4;
+  } else if (!strcmp(name, "persist_trace") && h->xch) {
+    *ptr_dev = h->arena + h->plan.trace; *bytes = (size_t)h->cu_count * c.n_layers * 32 * 8;
   } else {
     return ERNIE_EINVAL;
   }
@@ -1250,6 +1284,9 @@ int ernie_debug_tune(ErnieHandle* h, const char* key, int value) {
   if (!h || !key) return ERNIE_EINVAL;
   if (!strcmp(key, "fused_decode")) { h->fused_decode = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "persist")) { h->persist = value != 0; return ERNIE_OK; }
+  if (!strcmp(key, "persist_helpers")) { h->persist_helpers = value != 0; return ERNIE_OK; }
+  if (!strcmp(key, "persist_dbg")) { h->persist_dbg = value; return ERNIE_OK; }
+  if (!strcmp(key, "persist_trace")) { h->persist_trace = value != 0; return ERNIE_OK; }
   if (!strcmp(key, "persist_spin")) { if (value < 1) return ERNIE_EINVAL; h->persist_spin = (unsigned)value; return ERNIE_OK; }
   if (!strcmp(key, "persist_stall")) { if (value < 0 || value > 5) return ERNIE_EINVAL; h->persist_stall = value; return ERNIE_OK; }
   if (!strcmp(key, "dec_nw16")) { h->dec_nw16 = value; return ERNIE_OK; }
