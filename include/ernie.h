@@ -16,7 +16,8 @@
  *    and LayerNorm statistics are fp32; logits and hidden outputs are fp32;
  *    token ids are int32 in TRIMMED index space [0, vocab_kept).  The caller
  *    converts to full-vocabulary ids with kept_ids[] (host post-processing).
- *    Ids are not range-checked on the device.
+ *    Ids outside [0, vocab_kept) are not diagnosed on the device: they are clamped into the table (a valid row is
+ *    read, never memory past it).
  *  - The caller owns every buffer: parameters, the arena, inputs, outputs, and
  *    the stream.  The library calls no hipMalloc / hipFree in prefill or decode
  *    and enqueues all work on `stream` (a hipStream_t passed as void*; NULL =
@@ -174,11 +175,24 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax,
  * past max_seq or max_pos makes the kernels skip the step for that sequence
  * instead of writing out of bounds.
  * Errors: ERNIE_ESEQUENCE (no prefill yet), ERNIE_ECAPACITY (some sequence
- * would exceed max_seq or max_pos), ERNIE_EINVAL, ERNIE_EHIP.
+ * would exceed max_seq or max_pos), ERNIE_EINVAL, ERNIE_EHIP (enqueueing failed, or
+ * an EARLIER step's kernel gave up a bounded wait: see ernie_last_error).
  */
 int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev,
                       float* logits_out_dev, float* hidden_out_dev, int32_t* tok_out_dev,
                       void* stream);
+
+/*
+ * ernie_last_error -- device-side failures that cannot be reported by the call that enqueued the work.
+ * At batch <= 64 the layers of a decode step run as one persistent kernel whose workgroups hand activations to
+ * each other through device memory; every wait of that kernel is bounded, and a wait that gives up (which needs
+ * a workgroup that is never scheduled, e.g. a GPU shared with another long-running kernel) writes an error
+ * word and ends the kernel; the step's outputs are then undefined.  This call returns ERNIE_EHIP once if that
+ * has happened since the last report, ERNIE_OK otherwise; the caller synchronises the stream first to be sure
+ * the step in question has run.  The next ernie_decode_step reports (and clears) the same condition itself.
+ * Error: ERNIE_EINVAL (NULL handle).
+ */
+int ernie_last_error(ErnieHandle* h);
 
 /*
  * ernie_decode_step_static -- ernie_decode_step for callers that must not touch an allocator and want the

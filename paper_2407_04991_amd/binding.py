@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_PKG, "libernie_hip.so")
 
 ERNIE_OK, ERNIE_EINVAL, ERNIE_ECAPACITY, ERNIE_EARENA, ERNIE_ESEQUENCE, ERNIE_EHIP = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ("ernie_init_weights", "ernie_init_weights_ex", "ernie_prefill", "ernie_decode_step", "ernie_decode_step_static", "ernie_free",
+EXPORTS = ("ernie_init_weights", "ernie_init_weights_ex", "ernie_prefill", "ernie_decode_step", "ernie_decode_step_static", "ernie_last_error", "ernie_free",
            "ernie_debug_buffer", "ernie_debug_tune", "ernie_profile", "ernie_profile_read",
            "ernie_error_string", "ernie_get_config", "ernie_job_workspace_bytes", "ernie_run_job", "ernie_set_eos", "ernie_batch_state", "ernie_compact", "ernie_plan_batches",
            "ernie_vocab_count", "ernie_vocab_select", "ernie_vocab_gather_rows", "ernie_remap_ids")
@@ -97,6 +97,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ernie_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.ernie_decode_step_static.restype = C.c_int
     lib.ernie_decode_step_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.ernie_last_error.restype = C.c_int
+    lib.ernie_last_error.argtypes = [C.c_void_p]
     lib.ernie_free.restype = None
     lib.ernie_free.argtypes = [C.c_void_p]
     lib.ernie_debug_buffer.restype = C.c_int
@@ -198,6 +200,10 @@ def ernie_decode_step_static(handle, tok_in: Optional[torch.Tensor], logits_out:
                              hidden_out: Optional[torch.Tensor], tok_out: torch.Tensor, stream=None) -> int:
     return load_library().ernie_decode_step_static(handle, _ptr(tok_in), _ptr(logits_out), _ptr(hidden_out),
                                                    _ptr(tok_out), _stream_ptr(stream))
+
+
+def ernie_last_error(handle) -> int:
+    return load_library().ernie_last_error(handle)
 
 
 def ernie_free(handle) -> None:

@@ -48,6 +48,7 @@ struct DecGemmArgs {
   const half_t* pos_emb;  // [P, K]
   const half_t* seg_row;  // [K] or null
   int max_pos;
+  int vocab_kept;         // rows of tok_emb: fed ids are clamped into the table
   int eos;                // >= 0: a row fed this id is marked finished (by the strip-0 workgroups)
   int* finished;
   // outputs
@@ -294,9 +295,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_dec_ln_kernel(DecGemmArgs p) {
       const int rr = min(row0 + wave * RPW + i, B - 1);
       if constexpr (SKIN == 0) {
         // embedding prologue: token row + position row (+ segment row); the sum is not biased
-        const int id = p.tok[rr];
+        const int fed = p.tok[rr];
+        const int id = min(max(fed, 0), p.vocab_kept - 1);
         const int pos = min(p.cache_len[rr], p.max_pos - 1);
-        if (p.eos >= 0 && sg == 0 && lane == 0 && row0 + wave * RPW + i < B && id == p.eos) p.finished[rr] = 1;
+        if (p.eos >= 0 && sg == 0 && lane == 0 && row0 + wave * RPW + i < B && fed == p.eos) p.finished[rr] = 1;
 #pragma unroll
         for (int c = 0; c < RC; ++c) {
           const int cc = min(c * 64 + lane, chunks - 1);

@@ -571,7 +571,7 @@ int decode_layers_fused(ErnieHandle* h, const int* tok, float* logits_out, float
     if (l == 0) {
       // the embedding LayerNorm of the fed tokens is this GEMM's prologue (no separate embedding launch)
       a.sk_in = 0; a.tok = tok; a.cache_len = h->lens; a.tok_emb = h->tok_rm; a.pos_emb = h->pos;
-      a.seg_row = h->type_emb ? h->type_emb + d : nullptr; a.max_pos = c.max_pos; a.eos = h->eos; a.finished = h->finished;
+      a.seg_row = h->type_emb ? h->type_emb + d : nullptr; a.max_pos = c.max_pos; a.vocab_kept = c.vocab_kept; a.eos = h->eos; a.finished = h->finished;
       a.gamma = h->emb_g; a.beta = h->emb_b; a.xout = h->X;
       a.kv = kv_prefetch_for(h, l, B);
       rc |= launch_gemm_dec_ln<EPI_RAW>(h, a, s);
@@ -1023,7 +1023,7 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax, const int32_t* ids_de
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); hipLaunchKernelGGL(token_map_kernel, dim3((T + 255) / 256), dim3(256), 0, s, h->cu, B, T, h->tok_seq, h->tok_pos,
                      h->lens, h->finished, h->slot); }
   { ProfScope prof(h, ERNIE_PROF_ROW_PREFILL, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_prefill_kernel<RC>, dim3((T + 3) / 4), dim3(256), 0, s, ids_dev, Lmax, h->tok_seq,
-                     h->tok_pos, T, h->tok_rm, h->pos, h->type_emb, h->emb_g, h->emb_b, c.ln_eps, d, h->X)); }
+                     h->tok_pos, T, h->tok_rm, h->pos, h->type_emb, h->emb_g, h->emb_b, c.ln_eps, d, h->X, c.vocab_kept)); }
   const int q_tiles = (max_len + kAttnQTile - 1) / kAttnQTile;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerPtrs& L = h->layers[l];
@@ -1084,7 +1084,7 @@ static int decode_step_enqueue(ErnieHandle* h, const int32_t* tok_in_dev, float*
   } else {
     { ProfScope prof(h, ERNIE_PROF_ROW_DEC, s, 0.0, 0.0); ROW_DISPATCH(d, hipLaunchKernelGGL(embed_ln_decode_kernel<RC>, dim3(B), dim3(64), 0, s, tok, h->lens, B, c.max_pos,
                        h->tok_rm, h->pos, h->type_emb ? h->type_emb + d : nullptr, h->emb_g, h->emb_b, c.ln_eps, d, h->X,
-                       h->eos, h->finished)); }
+                       h->eos, h->finished, c.vocab_kept)); }
     rc = decode_layers_big(h, logits_out_dev, hidden_out_dev, s);
   }
   if (rc != ERNIE_OK) return rc;
@@ -1136,6 +1136,12 @@ int ernie_decode_step_static(ErnieHandle* h, const int32_t* tok_in_dev, float* l
   h->r_qkv = keep.r_qkv; h->r_out = keep.r_out; h->r_f2 = keep.r_f2; h->strip_val = keep.strip_val;
   h->strip_idx = keep.strip_idx; h->X = keep.X; h->X1 = keep.X1; h->O = keep.O; h->G = keep.G; h->hlast = keep.hlast;
   return out;
+}
+
+int ernie_last_error(ErnieHandle* h) {
+  if (!h) return ERNIE_EINVAL;
+  if (h->err_host && *(volatile int*)h->err_host) { *(volatile int*)h->err_host = 0; return ERNIE_EHIP; }
+  return ERNIE_OK;
 }
 
 int ernie_get_config(const ErnieHandle* h, ErnieConfig* out) {
@@ -1252,9 +1258,17 @@ int ernie_profile(ErnieHandle* h, int enable) {
   if (!h) return ERNIE_EINVAL;
   Profiler& p = h->prof;
   if (enable && p.slots.empty()) {
-    p.slots.resize(32768);
-    for (auto& sl : p.slots)
-      if (hipEventCreate(&sl.a) != hipSuccess || hipEventCreate(&sl.b) != hipSuccess) return ERNIE_EHIP;
+    std::vector<ProfSlot> fresh(32768, ProfSlot{nullptr, nullptr, 0});
+    bool ok = true;
+    for (auto& sl : fresh)
+      if (hipEventCreate(&sl.a) != hipSuccess || hipEventCreate(&sl.b) != hipSuccess) { ok = false; break; }
+    if (!ok) {                      // nothing half-built is kept: the next enable starts over
+      for (auto& sl : fresh) { if (sl.a) (void)hipEventDestroy(sl.a); if (sl.b) (void)hipEventDestroy(sl.b); }
+      (void)hipGetLastError();
+      p.on = false;
+      return ERNIE_EHIP;
+    }
+    p.slots.swap(fresh);
   }
   p.on = enable != 0;
   p.used = 0;

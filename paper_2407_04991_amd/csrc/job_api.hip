@@ -60,8 +60,12 @@ struct Run {
     cv.notify_all();
   }
   void fail(int code) {
-    int expected = ERNIE_OK;
-    error.compare_exchange_strong(expected, code);
+    {
+      // under the mutex: a waiter that has just evaluated its predicate must not miss this wake-up
+      std::lock_guard<std::mutex> lk(mu);
+      int expected = ERNIE_OK;
+      error.compare_exchange_strong(expected, code);
+    }
     cv.notify_all();
   }
 
@@ -110,6 +114,8 @@ struct Run {
 
   bool stage_post(Slot& s) {
     if (hipEventSynchronize(s.done) != hipSuccess) { fail(ERNIE_EHIP); return false; }
+    // the batch has run: a decode kernel whose bounded wait gave up has left its mark by now
+    if (const int rc = ernie_last_error(h); rc != ERNIE_OK) { fail(rc); return false; }
     const auto t0 = Clock::now();
     const int a = starts[s.batch], B = s.B, N = job->n_gen;
     for (int r = 0; r < B; ++r) {

@@ -102,12 +102,13 @@ template <int RC>
 __global__ __launch_bounds__(256) void embed_ln_prefill_kernel(
     const int* __restrict__ ids, int Lmax, const int* __restrict__ tok_seq, const int* __restrict__ tok_pos, int T,
     const half_t* __restrict__ tok_emb, const half_t* __restrict__ pos_emb, const half_t* __restrict__ seg_row,
-    const float* __restrict__ gamma, const float* __restrict__ beta, float eps, int d, half_t* __restrict__ X) {
+    const float* __restrict__ gamma, const float* __restrict__ beta, float eps, int d, half_t* __restrict__ X,
+    int vocab_kept) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
   const int b = tok_seq[t], pos = tok_pos[t];
-  const int id = ids[(size_t)b * Lmax + pos];
+  const int id = min(max(ids[(size_t)b * Lmax + pos], 0), vocab_kept - 1);    // an id outside the table reads a valid row, never past it
   const half_t* e = tok_emb + (size_t)id * d;
   const half_t* p = pos_emb + (size_t)pos * d;
   RowRegs<RC> r;
@@ -137,7 +138,7 @@ __global__ __launch_bounds__(256) void embed_ln_decode_kernel(
     const int* __restrict__ tok, const int* __restrict__ cache_len, int B, int max_pos,
     const half_t* __restrict__ tok_emb, const half_t* __restrict__ pos_emb, const half_t* __restrict__ seg_row,
     const float* __restrict__ gamma, const float* __restrict__ beta, float eps, int d, half_t* __restrict__ X,
-    int eos, int* __restrict__ finished) {
+    int eos, int* __restrict__ finished, int vocab_kept) {
   const int lane = threadIdx.x & 63;
   const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);     // blockDim.x / 64 rows per workgroup
   if (b >= B) return;
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(256) void embed_ln_decode_kernel(
   // prefill): later kernels of the step skip its cache and its emitted token is the end token again
   if (eos >= 0 && lane == 0 && tok[b] == eos) finished[b] = 1;
   const int pos = min(cache_len[b], max_pos - 1);
-  const half_t* e = tok_emb + (size_t)tok[b] * d;
+  const half_t* e = tok_emb + (size_t)min(max(tok[b], 0), vocab_kept - 1) * d;
   const half_t* p = pos_emb + (size_t)pos * d;
   RowRegs<RC> r;
   const int chunks = d / 8;
