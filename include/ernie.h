@@ -24,6 +24,7 @@
  *    the default stream) without synchronising the host, so outputs are valid
  *    once the caller has synchronised the stream.
  *  - A handle is not thread-safe and carries one in-flight batch.
+ *  - Test and measurement hooks (ernie_debug_*, ernie_profile*) are declared in ernie_debug.h.
  *  - Return value: 0 on success, a negative ERNIE_E* code otherwise.  Codes
  *    -1..-4 are decided on the host before anything is enqueued and leave the
  *    handle's state unchanged.
@@ -37,6 +38,9 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+/* The library is built with hidden visibility: only what carries ERNIE_API is exported. */
+#define ERNIE_API __attribute__((visibility("default")))
 
 #define ERNIE_OK          0
 #define ERNIE_EINVAL     (-1)  /* NULL / misaligned pointer, unsupported shape, length out of range */
@@ -96,7 +100,7 @@ typedef struct {
  * Errors: ERNIE_EINVAL (NULL cfg/out/weight pointer, head_dim != 64,
  * non-positive sizes, misaligned arena), ERNIE_EARENA, ERNIE_EHIP.
  */
-int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* weights,
+ERNIE_API int ernie_init_weights(const ErnieConfig* cfg, const ErnieWeights* weights,
                        void* arena_dev, size_t arena_bytes, size_t* arena_needed,
                        void* stream, ErnieHandle** out);
 
@@ -125,7 +129,7 @@ typedef struct {
  * the repacked variant parameters.  Additional error: ERNIE_EINVAL if only some of the
  * four head parameters are given.
  */
-int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* weights, const ErnieVariants* variants,
+ERNIE_API int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* weights, const ErnieVariants* variants,
                           void* arena_dev, size_t arena_bytes, size_t* arena_needed,
                           void* stream, ErnieHandle** out);
 
@@ -152,7 +156,7 @@ int ernie_init_weights_ex(const ErnieConfig* cfg, const ErnieWeights* weights, c
  * Errors: ERNIE_EINVAL, ERNIE_ECAPACITY (B > max_batch, Lmax > max_seq,
  * Lmax > max_pos, capture slots used up), ERNIE_EHIP.
  */
-int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax,
+ERNIE_API int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax,
                   const int32_t* ids_dev, const int32_t* prompt_lens_host,
                   float* logits_out_dev, float* hidden_out_dev, int32_t* tok_out_dev,
                   void* stream);
@@ -178,7 +182,7 @@ int ernie_prefill(ErnieHandle* h, int32_t B, int32_t Lmax,
  * would exceed max_seq or max_pos), ERNIE_EINVAL, ERNIE_EHIP (enqueueing failed, or
  * an EARLIER step's kernel gave up a bounded wait: see ernie_last_error).
  */
-int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev,
+ERNIE_API int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev,
                       float* logits_out_dev, float* hidden_out_dev, int32_t* tok_out_dev,
                       void* stream);
 
@@ -192,7 +196,7 @@ int ernie_decode_step(ErnieHandle* h, const int32_t* tok_in_dev,
  * the step in question has run.  The next ernie_decode_step reports (and clears) the same condition itself.
  * Error: ERNIE_EINVAL (NULL handle).
  */
-int ernie_last_error(ErnieHandle* h);
+ERNIE_API int ernie_last_error(ErnieHandle* h);
 
 /*
  * ernie_decode_step_static -- ernie_decode_step for callers that must not touch an allocator and want the
@@ -208,7 +212,7 @@ int ernie_last_error(ErnieHandle* h);
  * zero at entry (every element is written before it is read within a step), so a call after a larger or a
  * smaller batch needs no clearing.  Calls no hipMalloc / hipFree and no allocating library routine.
  */
-int ernie_decode_step_static(ErnieHandle* h, const int32_t* tok_in_dev,
+ERNIE_API int ernie_decode_step_static(ErnieHandle* h, const int32_t* tok_in_dev,
                              float* logits_out_dev, float* hidden_out_dev, int32_t* tok_out_dev,
                              void* stream);
 
@@ -243,101 +247,17 @@ int ernie_decode_step_static(ErnieHandle* h, const int32_t* tok_in_dev,
  *   the cut points into order_out_host).  Error: ERNIE_EINVAL (NULL pointer, n < 0,
  *   limits < 1, a length < 1 or a prompt that alone exceeds max_tokens).
  */
-int ernie_set_eos(ErnieHandle* h, int32_t eos_id);
-int ernie_batch_state(ErnieHandle* h, int32_t* lens_out_dev, int32_t* finished_out_dev, void* stream);
-int ernie_compact(ErnieHandle* h, int32_t n_keep, const int32_t* keep_rows_host, void* stream);
-int ernie_plan_batches(const int32_t* lens_host, int32_t n, int32_t max_batch, int64_t max_tokens,
+ERNIE_API int ernie_set_eos(ErnieHandle* h, int32_t eos_id);
+ERNIE_API int ernie_batch_state(ErnieHandle* h, int32_t* lens_out_dev, int32_t* finished_out_dev, void* stream);
+ERNIE_API int ernie_compact(ErnieHandle* h, int32_t n_keep, const int32_t* keep_rows_host, void* stream);
+ERNIE_API int ernie_plan_batches(const int32_t* lens_host, int32_t n, int32_t max_batch, int64_t max_tokens,
                        int32_t* order_out_host, int32_t* starts_out_host, int32_t* n_batches_out);
 
 /* ernie_free -- releases the host-side handle (the arena stays the caller's). NULL is a no-op. */
-void ernie_free(ErnieHandle* h);
-
-/*
- * ernie_debug_buffer -- test hook: device address and size in bytes of an
- * internal buffer, for layer-by-layer comparison with a reference.  `name`
- * is one of "x" (layer input/output activations [T, d] fp16), "kv" (the
- * key/value cache [n_layers][2][max_batch][n_heads][max_seq][64] fp16),
- * "lens" ([max_batch] int32 cached lengths).  Returns ERNIE_EINVAL for an
- * unknown name.  Not part of the hot path.
- */
-int ernie_debug_buffer(ErnieHandle* h, const char* name, void** ptr_dev, size_t* bytes);
-
-/*
- * ernie_profile / ernie_profile_read -- measurement hooks (not part of the hot path).
- *
- * ernie_profile(h, 1) switches per-kernel timing on and clears the counters: from then on every
- * launch of the categories below is bracketed by HIP events recorded on the stream it is launched
- * on (events are created on the first enable; up to 32768 launches are recorded, later ones are not
- * timed).  Do not capture profiled calls into a graph.  ernie_profile(h, 0) switches it off.
- * ernie_profile_read waits for the recorded events of one category and returns the summed device
- * time between each pair, the number of launches, and the algorithmic bytes and flops of those
- * launches: weight bytes N*K*2 for the decode GEMMs and the output projection, K and V bytes of all
- * visible positions for decode attention, 2*M*N*K flops for GEMMs and 4*sum(L_b^2)*d for prefill
- * attention.
- */
-#define ERNIE_PROF_GEMM_DEC      0   /* decode GEMM on fp16 activations (attention output, FFN2) */
-#define ERNIE_PROF_GEMM_DEC_LN   1   /* decode GEMM with a LayerNorm prologue (QKV incl. the embedding LayerNorm of layer 0, FFN1) */
-#define ERNIE_PROF_ATTN_DEC      2   /* decode attention over the key/value cache */
-#define ERNIE_PROF_GEMM_PREFILL  3   /* prefill MFMA GEMMs */
-#define ERNIE_PROF_ATTN_PREFILL  4   /* prefill attention */
-#define ERNIE_PROF_LOGITS        5   /* output projection + first argmax stage (decode, small-batch path) */
-#define ERNIE_PROF_ROW_DEC       6   /* decode row kernels: embedding + LayerNorm, final LayerNorm, second argmax stage */
-#define ERNIE_PROF_ROW_PREFILL   7   /* prefill row kernels: token map, embedding + LayerNorm, LayerNorm, last-row gather, argmax */
-#define ERNIE_PROF_DEC_PERSIST   8   /* the one-launch decode kernel: every layer of a small-batch step (weights + cache bytes) */
-#define ERNIE_PROF_NCAT          9
-int ernie_profile(ErnieHandle* h, int enable);
-int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* launches,
-                       double* alg_bytes, double* alg_flops);
-
-/*
- * ernie_debug_tune -- test hook: override a decode-path tuning knob of this handle.
- *   "fused_decode" 0/1  use the small-batch path (row-wise work fused into GEMM prologues) when it fits,
- *                       else the large-batch path (split-K partials summed by row kernels)
- *   "sk_out", "sk_f2"   split of the contraction of the attention-output / second FFN GEMM over workgroups
- *   "attn_dec" 0..5     decode attention shape: 0 = chosen from the batch and capacity, 1 = 4 waves x 4 key groups
- *                       in flight, 2 = 8 waves x 3, 3 = 8 waves x 4, 4 = 4 waves x 2, 5 = 2 waves x 2 (a batch of
- *                       waves x groups x 8 keys per memory round trip)
- *   "ln_ns" 0/1/2/4     32-column strips per workgroup of the decode GEMMs with the LayerNorm prologue (0 = chosen
- *                       automatically); "ln_rpw" 0/1/2 rows normalised per wave in that prologue (0 = chosen from the batch size)
- *   "big_logits_gemm" 0/1  large-batch path: output projection on the MFMA GEMM pipeline followed by a row argmax
- *                       (default 1; needs vocab_kept % 8 == 0), or the table-streaming kernel with per-strip argmax
- *   "big_f1_fused" 0/1  large-batch path: first FFN GEMM unsplit with bias + GELU in its epilogue (default 1), or
- *                       split over the contraction with a separate GELU row kernel
- *   "dec_nw16" 0..3     decode GEMMs on fp16 activations with 16 instead of 8 waves per workgroup: 0 = never,
- *                       1 = second FFN GEMM, 2 = also the attention-output GEMM (default), 3 = also the projection
- *   "dec_prefetch" 0..1024  small-batch path: workgroups appended to the attention-output and second FFN GEMMs that
- *                       pull what the next kernel reads first (the weights of the following LayerNorm-prologue GEMM,
- *                       into the L2 of the XCD that will read them, and its bias / scale / shift vectors) out of
- *                       HBM ahead of time (default 64; 0 = off; rounded up to a multiple of 8 per split).  Does
- *                       not change any result.
- *   "kv_prefetch" 0..2048  small-batch path: workgroups appended to the QKV GEMM that stream the cache rows of the
- *                       attention that follows into the L2 of the XCD that will read them (0 = off, 1 = one
- *                       workgroup per two (sequence, head) streams (default), larger = that many workgroups,
- *                       rounded up to a multiple of 8).  Does not change any result.
- *   "big_warm" 0..256   large-batch path: workgroups appended to the decode attention that pull the layer's bias and
- *                       LayerNorm vectors (read first by the row kernels and the FFN1 epilogue that follow) and the
- *                       next layer's QKV bias into every XCD's L2 (default 16; 0 = off).  Does not change any result.
- *   "big_f1_tile" 0..2  large-batch path, first FFN GEMM (unsplit): 0 = 64 x 32 tiles when 64 x 64 ones would number
- *                       128 or fewer, else 64 x 64 (default), 1 = 64 x 32, 2 = 64 x 64.  Does not change any result.
- *   "big_mfast" 0/1     large-batch path: with exactly two row tiles (64 < B <= 128) the tiles of the decode GEMMs are
- *                       ordered rows-fastest, so that both row tiles of a weight column strip run in one XCD and the
- *                       strip is fetched once (default 1).  Does not change any result.
- *   "big_narrow" 0/1    large-batch path: split-K projections whose 64 x 64 tiles times splits number 128 or fewer
- *                       run on 64 x 32 tiles instead (default 1).  Does not change any result.
- *   "big_ln_rows" 1/2/4 large-batch path: rows per workgroup of the LayerNorm row kernels (default 1: a row's
- *                       partial sums are 20 KB at d = 1024, and several rows behind one CU's memory pipeline
- *                       lengthen these short kernels).  Does not change any result.
- *   "pf_tile" 0..3      prefill GEMM tile: 0 = chosen from the problem size (default), 1 = 256 x 256, 2 = 128 x 128,
- *                       3 = 64 x 64.  Does not change any result.
- *   "attn_nt" 0/1       decode attention reads the cache with the non-temporal (streaming) hint, so that the
- *                       once-per-step cache stream does not displace the weights from the caches (default 1)
- * Splits are 1, 2 or 4.  Results are deterministic for any fixed setting.  Returns ERNIE_EINVAL for an
- * unknown key or a split that is not supported or does not divide the k-tile count.
- */
-int ernie_debug_tune(ErnieHandle* h, const char* key, int value);
+ERNIE_API void ernie_free(ErnieHandle* h);
 
 /* ernie_error_string -- static description of an ERNIE_E* code. */
-const char* ernie_error_string(int code);
+ERNIE_API const char* ernie_error_string(int code);
 
 #ifdef __cplusplus
 }

@@ -55,10 +55,10 @@ typedef struct {
 } ErnieJobStats;
 
 /* ernie_get_config -- copies the configuration the handle was created with. */
-int ernie_get_config(const ErnieHandle* h, ErnieConfig* out);
+ERNIE_API int ernie_get_config(const ErnieHandle* h, ErnieConfig* out);
 
 /* Device workspace of a job: two batch slots of padded prompt ids and generated tokens. 0 if h is NULL or n_gen < 1. */
-size_t ernie_job_workspace_bytes(const ErnieHandle* h, int32_t n_gen);
+ERNIE_API size_t ernie_job_workspace_bytes(const ErnieHandle* h, int32_t n_gen);
 
 /*
  * ernie_run_job -- see the top of this file.  `stats_out` may be NULL.
@@ -68,7 +68,7 @@ size_t ernie_job_workspace_bytes(const ErnieHandle* h, int32_t n_gen);
  * prompt whose length + n_gen - 1 exceeds max_seq or max_pos).  ERNIE_EHIP if a HIP call fails
  * while running (remaining batches are abandoned; tokens_out_host is then incomplete).
  */
-int ernie_run_job(ErnieHandle* h, const ErnieJob* job, ErnieJobStats* stats_out, void* stream);
+ERNIE_API int ernie_run_job(ErnieHandle* h, const ErnieJob* job, ErnieJobStats* stats_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -23,6 +23,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "ernie.h"
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -38,7 +40,7 @@ extern "C" {
  * n == 0 is a no-op.  Errors: ERNIE_EINVAL (NULL pointer with n > 0, misalignment,
  * vocab_full outside [1, ERNIE_VOCAB_MAX], n < 0 or n > 2^39).
  */
-int ernie_vocab_count(const int32_t* ids_dev, int64_t n, int32_t vocab_full,
+ERNIE_API int ernie_vocab_count(const int32_t* ids_dev, int64_t n, int32_t vocab_full,
                       uint64_t* counts_dev, void* stream);
 
 /*
@@ -53,7 +55,7 @@ int ernie_vocab_count(const int32_t* ids_dev, int64_t n, int32_t vocab_full,
  * Errors: ERNIE_EINVAL (NULL pointer, k outside [1, vocab_full], bad or duplicate
  * reserved ids, unk_full_id not reserved, vocab_full outside [1, ERNIE_VOCAB_MAX]).
  */
-int ernie_vocab_select(const uint64_t* counts_dev, int32_t vocab_full, int32_t k,
+ERNIE_API int ernie_vocab_select(const uint64_t* counts_dev, int32_t vocab_full, int32_t k,
                        const int32_t* reserved_host, int32_t n_reserved, int32_t unk_full_id,
                        int32_t* kept_ids_dev, int32_t* full_to_trimmed_dev, void* stream);
 
@@ -64,7 +66,7 @@ int ernie_vocab_select(const uint64_t* counts_dev, int32_t vocab_full, int32_t k
  *   being clamped into [0, vocab_full).
  * Errors: ERNIE_EINVAL (NULL pointer, misalignment, d % 8 != 0, non-positive sizes).
  */
-int ernie_vocab_gather_rows(const void* table_full_dev, int32_t vocab_full, int32_t d,
+ERNIE_API int ernie_vocab_gather_rows(const void* table_full_dev, int32_t vocab_full, int32_t d,
                             const int32_t* kept_ids_dev, int32_t k, void* table_kept_dev, void* stream);
 
 /*
@@ -72,7 +74,7 @@ int ernie_vocab_gather_rows(const void* table_full_dev, int32_t vocab_full, int3
  *   in_dev, out_dev [n] int32 (may be the same buffer); map_dev [map_len] int32.
  * Errors: ERNIE_EINVAL (NULL pointer with n > 0, misalignment, map_len < 1, n < 0).
  */
-int ernie_remap_ids(const int32_t* in_dev, int64_t n, const int32_t* map_dev, int32_t map_len,
+ERNIE_API int ernie_remap_ids(const int32_t* in_dev, int64_t n, const int32_t* map_dev, int32_t map_len,
                     int32_t fallback, int32_t* out_dev, void* stream);
 
 #ifdef __cplusplus

@@ -3,6 +3,7 @@
 // enqueued on the caller's stream; nothing here allocates device memory.
 
 #include "../../include/ernie.h"
+#include "../../include/ernie_debug.h"
 #include "../../include/ernie_job.h"
 
 #include <hip/hip_runtime.h>
@@ -230,7 +231,7 @@ static int static_scratch_for_current_device(unsigned char** out) {
 // A staging slot for one host -> device copy on stream `s`; *slot_out is the ring slot to pass to
 // stage_release after the copy has been enqueued, or -1 for a capture slot.  Returns null when the stream is
 // capturing and the capture slots are used up.
-int* stage_acquire(ErnieHandle* h, hipStream_t s, int* slot_out) {
+static int* stage_acquire(ErnieHandle* h, hipStream_t s, int* slot_out) {
   const size_t pitch = (size_t)h->cfg.max_batch + 1;
   hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
   if (hipStreamIsCapturing(s, &st) != hipSuccess) { (void)hipGetLastError(); st = hipStreamCaptureStatusNone; }
@@ -246,7 +247,7 @@ int* stage_acquire(ErnieHandle* h, hipStream_t s, int* slot_out) {
   return h->staging + (size_t)slot * pitch;
 }
 
-void stage_release(ErnieHandle* h, hipStream_t s, int slot) {
+static void stage_release(ErnieHandle* h, hipStream_t s, int slot) {
   if (slot < 0) return;
   if (hipEventRecord(h->stage_ev[slot], s) == hipSuccess) h->stage_busy[slot] = true;
   else { (void)hipGetLastError(); (void)hipStreamSynchronize(s); }      // no event: wait for the copy instead

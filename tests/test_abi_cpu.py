@@ -26,6 +26,16 @@ def test_library_exports_every_declared_symbol():
         assert getattr(lib, n) is not None
 
 
+def test_library_exports_nothing_else():
+    """Hidden visibility: the dynamic symbol table defines the declared entry points and no other function or object
+    (no kernel stubs, no helpers)."""
+    import subprocess
+    from paper_2407_04991_amd import binding
+    out = subprocess.run(["nm", "-D", "--defined-only", binding.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    defined = {line.split()[-1] for line in out.splitlines() if line.strip()}
+    assert defined == set(declared_symbols()), sorted(defined ^ set(declared_symbols()))
+
+
 def base_cfg(**kw):
     v = dict(n_layers=12, d_model=768, n_heads=12, d_ffn=3072, vocab_full=18000, vocab_kept=18000, max_pos=512,
              max_batch=32, max_seq=160, ln_eps=1e-5)

@@ -391,6 +391,25 @@ def test_seeded_random_small_configurations(E, seed):
     eng.close()
 
 
+@pytest.mark.parametrize("d_model,heads,B", [(1280, 20, 3), (1280, 20, 70), (2048, 32, 5), (2048, 32, 66), (4096, 64, 2)])
+def test_model_widths_above_1024(E, d_model, heads, B):
+    """Widths the named configurations do not reach: the row kernels' 4- and 8-chunk instantiations, prefill GEMMs with
+    a contraction above 1024, and small batches on the large-batch decode path (the small-batch paths stop at 1024)."""
+    rng = np.random.default_rng(d_model + B)
+    lengths = [int(x) for x in rng.integers(1, 40, size=B)]
+    n_gen = 3
+    wl = _ragged_workload(lengths, max_pos=64, n_gen=n_gen, vocab_kept=200, n_layers=1, d_model=d_model, n_heads=heads,
+                          d_ffn=256)
+    eng = E.engine_from_workload(wl, max_seq=max(lengths) + n_gen)
+    ids, lens = wl.padded(0)
+    rows = sorted({0, B - 1})
+    _say(f"[parity] width {d_model}, batch {B}")
+    orc = oracle_generate(wl, 0, rows, n_gen)
+    toks, hid, lg = gpu_generate(eng, ids, lens, n_gen, {r: orc[r]["tokens"] for r in orc})
+    check_rows(orc, toks, hid, lg, f"width-{d_model}")
+    eng.close()
+
+
 @pytest.mark.parametrize("seed", [1001, 1002, 1003, 1004])
 def test_seeded_random_wide_configurations(E, seed):
     """As above at widths and lengths of the benchmark models: 8-16 heads, FFN width up to 4096, prompts up to 300
