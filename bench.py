@@ -21,22 +21,29 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 MFMA_F16_PEAK_TFLOPS = 2500.0
 
-# HBM bytes per launch (reads + writes) of each kernel family, from two rocprofv3 --pmc runs (FETCH_SIZE,
-# WRITE_SIZE) of this script, scaled by what the same counters read for a 256 MiB device copy (FETCH_SIZE
-# 2.0, WRITE_SIZE 1.0); summary and commands in profiles/base_b32_hbm_traffic_pmc.txt.  Counters cannot be
-# read from inside the process, so the figures are carried here for the workload they were measured on.
-MEASURED_HBM_BYTES_PER_LAUNCH = {
-    "base": {"gemm_dec": 8.725e+06, "gemm_dec_ln": 1.447e+07, "attn_dec": 1.550e+07, "logits": 3.345e+07, "gemm_prefill": 6.420e+07, "attn_prefill": 2.525e+07},
-}
+# HBM bytes per launch (reads + writes) of each kernel family come from rocprofv3 --pmc runs of this script
+# (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a plain device copy of known size).
+# Counters cannot be read from inside the process, so the figures are kept in one tracked table,
+# profiles/hbm_traffic_per_launch.txt (lines "workload kernel bytes_per_launch", '#' comments), next to the
+# summaries and commands they come from, and are reported for the workload they were measured on.
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
 
-# Some decode kernels carry extra workgroups that fetch the NEXT kernel's operands into L2 ahead of time; the
-# counters book those bytes on the host kernel.
-HOSTED_WARMUP_NOTE = {
-    "gemm_dec_ln": "half of these launches (the QKV GEMMs) also fetch the following attention's cache rows "
-                   "(15.5 MB each) into L2; the instances that host nothing move 7.1 MB per launch",
-    "gemm_dec": "includes the weights of the following LayerNorm-prologue GEMM (4.1 MB on average) fetched into L2",
-    "logits": "includes layer 0's QKV weights (3.5 MB) fetched into L2 for the next step",
-}
+
+def measured_traffic(workload, kernel):
+    try:
+        with open(TRAFFIC_TABLE) as fh:
+            for line in fh:
+                parts = line.split("#")[0].split()
+                if len(parts) == 3 and parts[0] == workload and parts[1] == kernel:
+                    return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
+# The paper's own end-to-end figure, as context only (its weights, data and GPU are not available here).
+PAPER_CONTEXT = ("paper, Table 1: 16.11 -> 144.45 samples/s end to end (8.96x over its baseline), on a GPU the "
+                 "paper does not name; no comparison is claimed")
 
 
 def algorithmic_decode_bytes(sh, B, c_keys):
@@ -70,7 +77,9 @@ def cpu_baseline(wl, rows, n_gen):
         O.generate_cached(p, wl.batches_full[0][r], n_gen, wl.kept_ids)
     dt = time.perf_counter() - t0
     threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
-    return {"value": len(rows) * n_gen / dt, "unit": "generated tokens/s", "cores": int(threads), "kind": "oracle",
+    # `cores` = threads the oracle's BLAS calls actually ran on; `host_cores` = what the box offers this process
+    return {"value": len(rows) * n_gen / dt, "unit": "generated tokens/s", "cores": int(threads),
+            "host_cores": len(os.sched_getaffinity(0)), "blas_threads": int(threads), "kind": "oracle",
             "sample": f"{len(rows)} of {wl.shape.batch} sequences of the same batch, prompt {wl.shape.prompt_len}, "
                       f"{n_gen} tokens each, fp64 cached path, {dt:.1f} s"}
 
@@ -363,6 +372,31 @@ def eos_sweep(args):
                       "useful_tokens": useful, "all_tokens": B * N, "modes": out_modes}), flush=True)
 
 
+def handover_bench(args):
+    """What one phase boundary of the one-launch decode step costs: G persistent workgroups, dependent all-to-all
+    stages, per stage 1-4 KB published and 8-96 KB read per workgroup, with the decode kernel's tagged-pair protocol
+    and with a fence-and-flag protocol; next to it, the cost of a kernel boundary (a graph node).  Prints ONE JSON line."""
+    import torch
+    import paper_2407_04991_amd as E
+    assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
+    E.load_library()
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0")
+    rows = []
+    for G in (64, 128, 256):
+        for pieces, out_units in ((1, 64), (3, 128), (6, 128), (12, 256)):
+            row = {"workgroups": G, "read_kb_per_workgroup": pieces * 8, "published_kb_per_workgroup": out_units // 64}
+            for mode, name in ((0, "tagged_pairs_us"), (1, "fence_and_flag_us")):
+                rc, us, bad = E.ernie_debug_handover(mode, G, 200, pieces, out_units, ws)
+                assert rc == 0, rc
+                assert bad == 0 or mode == 1, "the tagged-pair protocol delivered stale data"
+                row[name] = us
+                row[name.replace("_us", "_stale_units")] = bad
+            rows.append(row)
+    print(json.dumps({"metric": "hand-over between persistent workgroups through device memory (1 GPU)", "unit": "us per stage",
+                      "n_gpus": 1, "data": "synthetic", "stages_per_run": 200, "graph_node_floor_us": graph_node_floor_us(),
+                      "rows": rows}), flush=True)
+
+
 def pipeline_bench(args):
     """The host pipeline on ERNIE-base-shaped requests: the same job with the stages one after another and side
     by side.  Requests are full-vocabulary prompts (Zipf ids, lengths as in the named workload), kept rows and
@@ -429,6 +463,8 @@ def main():
                     "(default workload decode_bound) instead of the headline benchmark")
     ap.add_argument("--pipeline", action="store_true", help="run the host-pipeline comparison (ernie_run_job with the "
                     "stages one after another vs side by side) instead of the headline benchmark")
+    ap.add_argument("--handover", action="store_true", help="measure the hand-over between persistent workgroups (the "
+                    "phase boundary of the one-launch decode step) instead of the headline benchmark")
     ap.add_argument("--requests", type=int, default=512, help="pipeline: number of requests in the job")
     ap.add_argument("--compact-every", type=int, default=16, help="eos sweep: steps between batch compactions")
     ap.add_argument("--corpus-mtok", type=int, default=64, help="trim sweep: corpus size in Mi tokens")
@@ -449,6 +485,8 @@ def main():
         return eos_sweep(args)
     if args.pipeline:
         return pipeline_bench(args)
+    if args.handover:
+        return handover_bench(args)
 
     import numpy as np
     import torch
@@ -464,12 +502,28 @@ def main():
     for kv in args.tune:
         k, v = kv.split("=")
         eng.tune(k, int(v))
-    m = measure_pass(E, eng, ids_np, lens, N, args.steps, args.warmup, args.graph, args.prof_passes)
-    ms_per_step, tokens_per_s, pre, dec_ms_mean, prof = m["ms_per_step"], m["tokens_per_s"], m["prefill_ms"], \
-        m["decode_step_ms"], m["prof"]
+    # A workload with several length-sorted batches (the variable-length configuration) is timed batch by batch and
+    # reported as the aggregate over all of them: one "step" is then one pass over every batch.
+    n_batches = len(wl.batches_trimmed)
+    per_batch, prof = [], {}
+    tot_ms = tot_pre = tot_dec = 0.0
+    for bi in range(n_batches):
+        ids_b, lens_b = wl.padded(bi)
+        m = measure_pass(E, eng, ids_b, lens_b, N, args.steps, args.warmup, args.graph, args.prof_passes)
+        tot_ms += m["ms_per_step"]; tot_pre += m["prefill_ms"]; tot_dec += m["decode_step_ms"]
+        for k, (ms, n, by, fl) in m["prof"].items():
+            o = prof.get(k, (0.0, 0, 0.0, 0.0))
+            prof[k] = (o[0] + ms, o[1] + n, o[2] + by, o[3] + fl)
+        per_batch.append({"batch": bi, "rows": int(len(lens_b)), "prompt_min": int(lens_b.min()), "prompt_max": int(lens_b.max()),
+                          "tokens_per_s": m["tokens_per_s"], "ms": m["ms_per_step"], "prefill_ms": m["prefill_ms"],
+                          "decode_step_ms": m["decode_step_ms"]})
+    lens = np.concatenate([wl.padded(bi)[1] for bi in range(n_batches)])
+    ms_per_step, pre, dec_ms_mean = tot_ms, tot_pre, tot_dec / n_batches
+    tokens_per_s = len(lens) * N / (tot_ms * 1e-3)
     prof_passes = args.prof_passes
     L = int(lens.max())
     step_bytes = np.array([algorithmic_decode_bytes(sh, B, int(np.mean(lens)) + t + 1) for t in range(N - 1)])
+    dec_total_ms = tot_dec * (N - 1)                    # all decode steps of all batches
     dec_gbs = float(np.mean(step_bytes) / (dec_ms_mean * 1e-3) / 1e9)
     pf = prefill_flops(sh, lens)
     bound = {"gemm_dec": "hbm", "gemm_dec_ln": "hbm", "attn_dec": "hbm", "logits": "hbm", "row_dec": "hbm",
@@ -483,7 +537,7 @@ def main():
     tot = {"decode": 0.0, "prefill": 0.0}
     for name, (ms, n, by, fl) in prof.items():
         tot[phase[name]] += ms / prof_passes
-    scale = {"decode": dec_ms_mean * (N - 1) / tot["decode"], "prefill": pre / tot["prefill"]}
+    scale = {"decode": dec_total_ms / tot["decode"], "prefill": pre / tot["prefill"]}
     kernels = {}
     for name, (ms, n, by, fl) in prof.items():
         if n == 0:
@@ -502,27 +556,30 @@ def main():
             "peak": kernels[dom]["peak"], "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"],
             "avg_launch_us": kernels[dom]["avg_us"],
             "algorithmic_per_launch": (prof[dom][2] if kernels[dom]["bound"] == "hbm" else prof[dom][3]) / prof[dom][1],
-            "traffic": MEASURED_HBM_BYTES_PER_LAUNCH.get(args.workload, {}).get(dom)}
-    if roof["traffic"] is not None and dom in HOSTED_WARMUP_NOTE:
-        roof["traffic_note"] = HOSTED_WARMUP_NOTE[dom]
+            "traffic": measured_traffic(args.workload, dom)}
 
     out = {
         "metric": "generated tokens/sec (ERNIE-base FP16, 1 GPU)", "value": tokens_per_s, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{sh.name}: {sh.n_layers} layers d={sh.d_model} heads={sh.n_heads} ffn={sh.d_ffn} "
-                               f"V'={sh.vocab_kept}/{sh.vocab_full}, batch {B}, prompt {L}, generate {N} "
-                               f"(1 prefill + {N - 1} decode steps, greedy, free-running)"},
+                               f"V'={sh.vocab_kept}/{sh.vocab_full}, "
+                               + (f"batch {B}, prompt {L}" if n_batches == 1 else
+                                  f"{n_batches} length-sorted batches of {B}, prompts {int(lens.min())}..{int(lens.max())}")
+                               + f", generate {N} (1 prefill + {N - 1} decode steps per batch, greedy, free-running)"},
         "launch": "hip-graph replay" if args.graph else "eager",
         "roofline": roof,
         "prefill_ms": pre, "prefill_tflops": pf / (pre * 1e-3) / 1e12,
         "prefill_frac_of_mfma_peak": pf / (pre * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS,
         "decode_step_ms": dec_ms_mean, "decode_tokens_per_s": B / (dec_ms_mean * 1e-3),
         "decode_step_algorithmic_gbs": dec_gbs, "decode_step_frac_of_hbm_peak": dec_gbs / HBM_PEAK_GBS,
-        "decode_launches_per_step": sum(k["launches_per_pass"] for n, k in kernels.items() if phase[n] == "decode") / (N - 1),
+        "decode_launches_per_step": sum(k["launches_per_pass"] for n, k in kernels.items() if phase[n] == "decode") / (N - 1) / n_batches,
         "graph_node_floor_us": graph_node_floor_us(),
         "kernels": kernels,
+        "paper_context": PAPER_CONTEXT,
     }
+    if n_batches > 1:
+        out["batches"] = per_batch
     if args.calib_copy_mb > 0:
         n = args.calib_copy_mb * (1 << 20)
         src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -542,3 +599,6 @@ def main():
 
 if __name__ == "__main__":
     main()
+    # leave at once: nothing of this process (BLAS or runtime worker threads) is to outlive the result line
+    sys.stdout.flush(); sys.stderr.flush()
+    os._exit(0)

@@ -97,6 +97,22 @@ ERNIE_API int ernie_profile_read(ErnieHandle* h, int category, double* total_ms,
  */
 ERNIE_API int ernie_debug_tune(ErnieHandle* h, const char* key, int value);
 
+/*
+ * ernie_debug_handover -- measures what it costs to hand data from every workgroup of a persistent kernel to
+ * every other one through device memory, i.e. the price of one phase boundary of the one-launch decode step
+ * (paper: Method, "Processing Optimization" counts kernel launches; this is what replaces a launch).
+ * n_workgroups workgroups of 512 threads run `stages` dependent stages; per stage each publishes out_units
+ * 16-byte units and reads `pieces` (1, 3, 6 or 12) units per thread, spread over all producers.
+ *   mode 0  tagged pairs read and written at agent scope (the protocol of the decode kernel)
+ *   mode 1  plain stores + release fence + one flag per workgroup; acquire fence + plain loads on the other side
+ * ws_dev: caller-owned device workspace, 256-byte aligned, at least 48 * n_workgroups * out_units + 4352 bytes
+ * (n_workgroups * out_units must be a multiple of 64); contents are overwritten.  Synchronises `stream`.
+ * *us_per_stage = best of four runs; *bad_units = units whose payload was not the expected one (0 for a correct
+ * protocol).  Errors: ERNIE_EINVAL (arguments), ERNIE_EHIP (runtime error, or a bounded wait gave up).
+ */
+ERNIE_API int ernie_debug_handover(int mode, int n_workgroups, int stages, int pieces, int out_units, void* ws_dev,
+                                   size_t ws_bytes, void* stream, double* us_per_stage, int64_t* bad_units);
+
 #ifdef __cplusplus
 }
 #endif

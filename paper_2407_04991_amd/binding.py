@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libernie_hip.so")
 ERNIE_OK, ERNIE_EINVAL, ERNIE_ECAPACITY, ERNIE_EARENA, ERNIE_ESEQUENCE, ERNIE_EHIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("ernie_init_weights", "ernie_init_weights_ex", "ernie_prefill", "ernie_decode_step", "ernie_decode_step_static", "ernie_last_error", "ernie_free",
-           "ernie_debug_buffer", "ernie_debug_tune", "ernie_profile", "ernie_profile_read",
+           "ernie_debug_buffer", "ernie_debug_tune", "ernie_debug_handover", "ernie_profile", "ernie_profile_read",
            "ernie_error_string", "ernie_get_config", "ernie_job_workspace_bytes", "ernie_run_job", "ernie_set_eos", "ernie_batch_state", "ernie_compact", "ernie_plan_batches",
            "ernie_vocab_count", "ernie_vocab_select", "ernie_vocab_gather_rows", "ernie_remap_ids")
 
@@ -105,6 +105,9 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
     lib.ernie_debug_buffer.argtypes = [C.c_void_p, C.c_char_p, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]
     lib.ernie_debug_tune.restype = C.c_int
     lib.ernie_debug_tune.argtypes = [C.c_void_p, C.c_char_p, C.c_int]
+    lib.ernie_debug_handover.restype = C.c_int
+    lib.ernie_debug_handover.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p,
+                                         C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.ernie_profile.restype = C.c_int
     lib.ernie_profile.argtypes = [C.c_void_p, C.c_int]
     lib.ernie_profile_read.restype = C.c_int
@@ -204,6 +207,15 @@ def ernie_decode_step_static(handle, tok_in: Optional[torch.Tensor], logits_out:
 
 def ernie_last_error(handle) -> int:
     return load_library().ernie_last_error(handle)
+
+
+def ernie_debug_handover(mode: int, n_workgroups: int, stages: int, pieces: int, out_units: int, ws: torch.Tensor,
+                         stream=None):
+    """Returns (rc, microseconds per stage, units with a wrong payload)."""
+    us, bad = C.c_double(0.0), C.c_int64(0)
+    rc = load_library().ernie_debug_handover(mode, n_workgroups, stages, pieces, out_units, _ptr(ws), ws.numel(),
+                                             _stream_ptr(stream), C.byref(us), C.byref(bad))
+    return rc, us.value, bad.value
 
 
 def ernie_free(handle) -> None:

@@ -22,6 +22,7 @@
 #include "gemm_prefill.h"
 #include "gemm_prefill2.h"
 #include "gemm_skinny.h"
+#include "handover_probe.h"
 #include "rowops.h"
 
 using namespace ernie;
@@ -1292,6 +1293,56 @@ int ernie_profile_read(ErnieHandle* h, int category, double* total_ms, int64_t* 
   *total_ms = ms; *launches = n;
   if (alg_bytes) *alg_bytes = p.bytes[category];
   if (alg_flops) *alg_flops = p.flops[category];
+  return ERNIE_OK;
+}
+
+int ernie_debug_handover(int mode, int n_workgroups, int stages, int pieces, int out_units, void* ws_dev, size_t ws_bytes,
+                         void* stream, double* us_per_stage, int64_t* bad_units) {
+  if ((mode != 0 && mode != 1) || n_workgroups < 8 || n_workgroups > 1024 || stages < 2 || stages > 100000 || out_units < 1 ||
+      !ws_dev || !us_per_stage || !bad_units)
+    return ERNIE_EINVAL;
+  if (pieces != 1 && pieces != 3 && pieces != 6 && pieces != 12) return ERNIE_EINVAL;
+  const size_t units = (size_t)n_workgroups * out_units;
+  if (units % 64 != 0 || units * 16 * 3 > ((size_t)1 << 31)) return ERNIE_EINVAL;
+  const size_t need = units * 16 * 3 + 4096 + 256;
+  if (ws_bytes < need || (uintptr_t)ws_dev % 256 != 0) return ERNIE_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(ws_dev);
+  unsigned* bufs = reinterpret_cast<unsigned*>(ws);
+  unsigned* flags = reinterpret_cast<unsigned*>(ws + units * 16 * 3);
+  int* gave_up = reinterpret_cast<int*>(ws + units * 16 * 3 + 4096);
+  unsigned* bad = reinterpret_cast<unsigned*>(ws + units * 16 * 3 + 4096 + 64);
+  HIP_OK(hipMemsetAsync(ws, 0, need, s));
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+    if (e0) (void)hipEventDestroy(e0);
+    return ERNIE_EHIP;
+  }
+  float best = 1e30f;
+  unsigned epoch0 = 1;
+  bool ok = true;
+  for (int rep = 0; rep < 4 && ok; ++rep) {
+    ok &= hipEventRecord(e0, s) == hipSuccess;
+#define PROBE(M, P) hipLaunchKernelGGL((handover_probe_kernel<M, P>), dim3(n_workgroups), dim3(kProbeThreads), 0, s, bufs, \
+                                       (unsigned)units, flags, stages, out_units, epoch0, 1u << 18, gave_up, bad)
+#define PROBE_BY_P(M) do { if (pieces == 1) PROBE(M, 1); else if (pieces == 3) PROBE(M, 3); else if (pieces == 6) PROBE(M, 6); else PROBE(M, 12); } while (0)
+    if (mode == 0) PROBE_BY_P(0); else PROBE_BY_P(1);
+#undef PROBE_BY_P
+#undef PROBE
+    ok &= hipEventRecord(e1, s) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+    float ms = 0.f;
+    ok &= hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+    if (ms < best) best = ms;
+    epoch0 += (unsigned)stages + 5;
+  }
+  int gave = 0; unsigned nbad = 0;
+  ok &= hipMemcpyAsync(&gave, gave_up, 4, hipMemcpyDeviceToHost, s) == hipSuccess;
+  ok &= hipMemcpyAsync(&nbad, bad, 4, hipMemcpyDeviceToHost, s) == hipSuccess;
+  ok &= hipStreamSynchronize(s) == hipSuccess;
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  if (!ok || launch_status() != ERNIE_OK || gave) return ERNIE_EHIP;
+  *us_per_stage = (double)best * 1000.0 / stages;
+  *bad_units = nbad;
   return ERNIE_OK;
 }
 
