@@ -599,6 +599,9 @@ def main():
 
 if __name__ == "__main__":
     main()
-    # leave at once: nothing of this process (BLAS or runtime worker threads) is to outlive the result line
+    # leave at once: nothing of this process (BLAS or runtime worker threads) is to outlive the result line.  Under a
+    # profiler the normal exit path is kept: its tool library writes its results from an exit handler.
     sys.stdout.flush(); sys.stderr.flush()
-    os._exit(0)
+    profiled = "rocprof" in os.environ.get("LD_PRELOAD", "").lower() or any(k.startswith("ROCPROF") for k in os.environ)
+    if not profiled:
+        os._exit(0)

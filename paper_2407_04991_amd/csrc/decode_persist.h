@@ -843,7 +843,7 @@ __device__ __forceinline__ void persist_helper(const PersistArgs& p, unsigned ta
   const int d = p.d, f = p.f, B = p.B, H = p.H, S = p.S;
   const int zg = (B + R - 1) / R, zg5 = (B + R5 - 1) / R5;
   const int n_streams = B * H, rows = min(S, p.kv_rows);
-  const int lookahead = 3;                         // phases between a touch and its use
+  const int lookahead = (p.dbg >> 4) ? (p.dbg >> 4) : 3;      // phases between a touch and its use (measurement hook: dbg / 16 overrides)
   for (int t = 0; t < 5 * p.n_layers; ++t) {
     const int l = t / 5, ph = t - 5 * l;
     if (t >= lookahead) {                          // stay `lookahead` phases ahead of the publishing front
