@@ -191,16 +191,22 @@ def make_corpus(vocab: int, n_tokens: int, seed: int = 5000, s: float = 1.1, shu
     return ids
 
 
-def full_to_trimmed(ids_full: np.ndarray, kept_ids: np.ndarray) -> np.ndarray:
-    """Re-index full-vocabulary ids into the trimmed table.
+def full_to_trimmed(ids_full: np.ndarray, kept_ids: np.ndarray, unk_full_id: int | None = None) -> np.ndarray:
+    """Re-index full-vocabulary ids into the trimmed table (input preparation only).
 
-    Ids whose row was dropped map to the reserved UNK row, which in synthetic
-    data is trimmed index 0 (the lowest kept id).
+    Ids whose row was dropped map to the trimmed index of the unknown-word id, the rule of the
+    trimming step; the synthetic workloads reserve the lowest kept id as that word, so the
+    default lands on trimmed index 0.
     """
+    kept_ids = np.asarray(kept_ids)
+    unk = int(kept_ids[0]) if unk_full_id is None else int(unk_full_id)
+    unk_pos = int(np.searchsorted(kept_ids, unk))
+    if unk_pos >= len(kept_ids) or int(kept_ids[unk_pos]) != unk:
+        raise ValueError("the unknown-word id must be a kept id")
     pos = np.searchsorted(kept_ids, ids_full)
     pos = np.minimum(pos, len(kept_ids) - 1)
     hit = kept_ids[pos] == ids_full
-    return np.where(hit, pos, 0).astype(np.int32)
+    return np.where(hit, pos, unk_pos).astype(np.int32)
 
 
 def trim_table(tok_emb: np.ndarray, kept_ids: np.ndarray) -> np.ndarray:

@@ -147,6 +147,23 @@ def test_maps_round_trip_and_unknown_routing():
     assert y.shape == x.shape and y[0, 1] == unk_t and y[1, 0] == unk_t and y[0, 0] == m[0] and y[1, 1] == m[5]
 
 
+def test_input_generator_reindexes_by_the_same_rule():
+    """synth.full_to_trimmed prepares the prompts of both sides of the generation parity tests: it must route
+    dropped ids to the unknown-word row exactly like the oracle's map (default: the lowest kept id is that word)."""
+    from synth.ernie_inputs import full_to_trimmed
+    vocab = 400
+    counts = P.count_tokens(make_corpus(vocab, 30000, seed=5), vocab)
+    ids = np.arange(vocab, dtype=np.int32)
+    for unk in (0, 57):
+        kept = P.select_kept(counts, 48, reserved=[unk])
+        m = P.full_to_trimmed_map(kept, vocab, unk)
+        assert np.array_equal(full_to_trimmed(ids, kept, unk_full_id=unk), m)
+    kept = P.select_kept(counts, 48, reserved=[0])
+    assert np.array_equal(full_to_trimmed(ids, kept), P.full_to_trimmed_map(kept, vocab, int(kept[0])))
+    with pytest.raises(ValueError):
+        full_to_trimmed(ids, np.array([1, 2, 3]), unk_full_id=5)
+
+
 def test_trim_rows_is_bitwise_row_selection():
     rng = np.random.default_rng(0)
     tab = rng.standard_normal((40, 16)).astype(np.float16)
