@@ -164,13 +164,53 @@ __device__ __forceinline__ void unpack_h2(unsigned w, float& a, float& b) {
   a = (float)h[0]; b = (float)h[1];
 }
 
+// Cross-lane moves on the vector ALU's data-parallel path (a few cycles each; the LDS crossbar behind __shfl_xor
+// costs a hundred and its own wait).  Lane layouts checked on the device with an in-bounds probe.
+template <int CTRL>
+__device__ __forceinline__ float lane_dpp(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float lane_xor1(float v) { return lane_dpp<0xB1>(v); }     // quad_perm [1, 0, 3, 2]
+__device__ __forceinline__ float lane_xor8(float v) { return lane_dpp<0x128>(v); }    // row_ror 8: lane ^ 8 inside a row of 16
+// Sum over each aligned group of eight lanes, in every lane of the group.
+__device__ __forceinline__ float team8_sum(float v) {
+  v += lane_dpp<0xB1>(v);       // lane ^ 1
+  v += lane_dpp<0x4E>(v);       // lane ^ 2 (quad_perm [2, 3, 0, 1])
+  v += lane_dpp<0x141>(v);      // row_half_mirror: the other quad of the eight
+  return v;
+}
+struct LanePair { float a, b; };
+// Rows of 16 lanes r0..r3 of v: a = {r0, r0, r2, r2}, b = {r1, r1, r3, r3} (every lane sees its own row and the row ^ 1).
+__device__ __forceinline__ LanePair rows_swap16(float v) {
+  const unsigned x = __builtin_bit_cast(unsigned, v);
+  const u32x2 r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+  const unsigned a = r[0], b = r[1];      // (a bit cast applied to a vector element directly reads element 0)
+  return {__builtin_bit_cast(float, a), __builtin_bit_cast(float, b)};
+}
+// Halves of 32 lanes: a = {low, low}, b = {high, high}.
+__device__ __forceinline__ LanePair halves_swap32(float v) {
+  const unsigned x = __builtin_bit_cast(unsigned, v);
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+  const unsigned a = r[0], b = r[1];
+  return {__builtin_bit_cast(float, a), __builtin_bit_cast(float, b)};
+}
+// Sum over the 64 lanes, the same bits in every lane.
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+  v = team8_sum(v);
+  v += lane_dpp<0x140>(v);      // row_mirror: the other eight of the row
+  const LanePair r = rows_swap16(v);
+  v = r.a + r.b;
+  const LanePair h = halves_swap32(v);
+  return h.a + h.b;
+}
+
 enum { PRO_LN = 0, PRO_EMBED = 1, PRO_COPY = 2 };
 enum { PEPI_BIAS = 0, PEPI_RES = 1, PEPI_GELU = 2 };
 
 struct PersistGemm {
   const half_t* Wp; int N, K, B;
   const unsigned char* in; const float* gamma; const float* beta; float eps;     // prologue
-  unsigned char* xout;                 // PRO_LN / PRO_EMBED: normalised rows as pairs (written by strip group 0)
+  unsigned char* xout;                 // PRO_LN / PRO_EMBED: normalised rows as pairs (each strip group writes its share of the columns)
   const float* bias;                   // [N]
   const unsigned char* res;            // PEPI_RES: residual rows [B][N] as pairs
   unsigned char* out;                  // [B][N] as pairs
@@ -248,9 +288,9 @@ __device__ __forceinline__ void persist_w_issue(PersistW<NS, FR>& W, const half_
 }
 
 // First half of a GEMM phase: waits for the unit's input and leaves the A tile [R][K] as fp16 in LDS (PRO_LN /
-// PRO_EMBED: normalised, and published as residual rows by strip group 0; PRO_COPY: copied, plus the
+// PRO_EMBED: normalised, and published as residual rows, a share of the columns per strip group; PRO_COPY: copied, plus the
 // residual tile of the epilogue).  Returns false (uniformly for the workgroup) when a wait gave up.
-template <int R, int NS, int PRO, int EPI, int RC = 2>
+template <int R, int NS, int PRO, int EPI, int PC = 4, int RC = 2>
 __device__ __forceinline__ bool persist_gemm_in(const PersistGemm& g, const PersistArgs& p, unsigned tag,
                                                 unsigned char* smem_raw, half_t* sRes, int* s_fail,
                                                 const PersistUnit<R, NS>& un) {
@@ -271,7 +311,7 @@ __device__ __forceinline__ bool persist_gemm_in(const PersistGemm& g, const Pers
     if constexpr (PRO == PRO_COPY) {
       const int upr = K / 4;                         // 16-byte units (4 values) per row
       const int total = R * upr;
-      constexpr int kPieces = 4;
+      constexpr int kPieces = PC > 8 ? (PC + 1) / 2 : PC;      // PC = 16-byte units per thread of the whole tile: one poll round
       const int n_res = EPI == PEPI_RES ? R * 8 : 0; // residual tile: R rows x 32 columns = R * 8 units
       u32x4 rv = {0, 0, 0, 0};
       const int rr_res = min(row0 + tid / 8, B - 1);
@@ -284,11 +324,13 @@ __device__ __forceinline__ bool persist_gemm_in(const PersistGemm& g, const Pers
         int dst[kPieces];
 #pragma unroll
         for (int q = 0; q < kPieces; ++q) {
-          const int id = min(id0 + q * kPersistThreads, total - 1);     // clamped: a duplicate is loaded, not stored
+          const int id = (int)((unsigned)(id0 + q * kPersistThreads) % (unsigned)total);         // past the tile: a duplicate is loaded, not stored
           const int r = id / upr, c4 = id - r * upr;
           off[q] = ((unsigned)min(row0 + r, B - 1) * K + c4 * 4) * 4;
           dst[q] = r * pitch + c4 * 4;
         }
+        // (Reading only the pieces that were missing in the round before, or waiting on one piece before fetching
+        // the rest, both measured slower than repeating the whole round.)
         unsigned spins = 0;
         while (true) {
           asm volatile("" ::: "memory");
@@ -346,7 +388,7 @@ __device__ __forceinline__ bool persist_gemm_in(const PersistGemm& g, const Pers
           }
         }
       } else {
-        u32x4 a[RPW][RC][2];
+        u32x4 a[RPW][RC][2] = {};
         unsigned off[RPW][RC];
 #pragma unroll
         for (int i = 0; i < RPW; ++i)
@@ -393,9 +435,7 @@ __device__ __forceinline__ bool persist_gemm_in(const PersistGemm& g, const Pers
         mean[i] = sum;
       }
 #pragma unroll
-      for (int o = 32; o > 0; o >>= 1)
-#pragma unroll
-        for (int i = 0; i < RPW; ++i) mean[i] += __shfl_xor(mean[i], o, 64);
+      for (int i = 0; i < RPW; ++i) mean[i] = wave_sum_dpp(mean[i]);
 #pragma unroll
       for (int i = 0; i < RPW; ++i) {
         mean[i] /= (float)K;
@@ -409,14 +449,16 @@ __device__ __forceinline__ bool persist_gemm_in(const PersistGemm& g, const Pers
         rstd[i] = q;
       }
 #pragma unroll
-      for (int o = 32; o > 0; o >>= 1)
-#pragma unroll
-        for (int i = 0; i < RPW; ++i) rstd[i] += __shfl_xor(rstd[i], o, 64);
+      for (int i = 0; i < RPW; ++i) rstd[i] = wave_sum_dpp(rstd[i]);
 #pragma unroll
       for (int i = 0; i < RPW; ++i) {
         const int r = row0 + wave * RPW + i;
         const float rs = rsqrtf(rstd[i] / (float)K + g.eps);
-        const bool writer = sg == 0 && r < B && !fail;
+        // every strip group of the row group holds the whole normalised row: each publishes its share of the
+        // residual copy (one group writing all of it ran a microsecond behind the others in every phase)
+        const int n_sg = (N / 32 + NS - 1) / NS;
+        const int ch_lo = sg * chunks / n_sg, ch_hi = (sg + 1) * chunks / n_sg;
+        const bool writer = r < B && !fail;
 #pragma unroll
         for (int c = 0; c < RC; ++c) {
           const int ch = c * 64 + lane;
@@ -425,7 +467,7 @@ __device__ __forceinline__ bool persist_gemm_in(const PersistGemm& g, const Pers
 #pragma unroll
             for (int j = 0; j < 8; ++j) o[j] = (half_t)((v[i][c][j] - mean[i]) * rs * gm[c][j] + bt[c][j]);
             *reinterpret_cast<half8*>(sA + (wave * RPW + i) * pitch + ch * 8) = o;
-            if (writer) {
+            if (writer && ch >= ch_lo && ch < ch_hi) {
               const u32x4 w = __builtin_bit_cast(u32x4, o);
               const unsigned off = ((unsigned)r * K + ch * 8) * 4;
               xch_store16(r_xout, off, w[0], w[1], tag);
@@ -509,7 +551,7 @@ __device__ __forceinline__ void persist_gemm_out(const PersistGemm& g, unsigned 
       float val = s + un.bias_r[i];
       if constexpr (EPI == PEPI_RES) val += (float)sRes[min(tr_, R - 1) * 32 + (lane & 31)];
       if constexpr (EPI == PEPI_GELU) val = gelu_erf_fast(val);
-      const float nb = __shfl_xor(val, 1, 64);            // the odd neighbour column
+      const float nb = lane_xor1(val);                    // the odd neighbour column
       if (live && (lane & 1) == 0 && !g.withhold)
         xch_store8(r_out, ((unsigned)row * N + col) * 4, pack_h2(val, nb), tag);
     }
@@ -557,7 +599,7 @@ __device__ __forceinline__ bool persist_qkv_wait(PersistQKV& o, const PersistArg
                                                  int h, unsigned tag) {
   const int ec = fresh_tid() & 7, d = p.d;
   const unsigned off = ((unsigned)b * 3 * d + h * 64 + ec * 8) * 4;
-  u32x4 a[3][2];
+  u32x4 a[3][2] = {};
   unsigned spins = 0;
   bool good = true;
   while (true) {
@@ -620,9 +662,7 @@ __device__ __forceinline__ void persist_attn_stream(SoftmaxPart& st, const Persi
       float pr = 0.f;
 #pragma unroll
       for (int j = 0; j < 8; ++j) pr += x.q[j] * (float)kf[u][j];
-      pr += __shfl_xor(pr, 1, 64);
-      pr += __shfl_xor(pr, 2, 64);
-      pr += __shfl_xor(pr, 4, 64);
+      pr = team8_sum(pr);
       sc[u] = valid ? pr : -INFINITY;
       vcur[u] = valid ? vf[u] : z;               // rows past the valid length hold arbitrary bits: weight 0 must meet value 0
       mx = fmaxf(mx, sc[u]);
@@ -652,14 +692,25 @@ __device__ __forceinline__ void persist_attn_stream(SoftmaxPart& st, const Persi
       st.m = mx;
     }
   }
-#pragma unroll
-  for (int off = 8; off < 64; off <<= 1) {
-    const float om = __shfl_xor(st.m, off, 64);
-    const float ol = __shfl_xor(st.l, off, 64);
+  {  // the eight teams of the wave: lane ^ 8, then row ^ 1, then half ^ 1 (each lane keeps its eight features)
     float oa[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) oa[j] = __shfl_xor(st.acc[j], off, 64);
-    softmax_merge(st, om, ol, oa);
+    for (int j = 0; j < 8; ++j) oa[j] = lane_xor8(st.acc[j]);
+    softmax_merge(st, lane_xor8(st.m), lane_xor8(st.l), oa);
+    {
+      const LanePair m = rows_swap16(st.m), l = rows_swap16(st.l);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { const LanePair a = rows_swap16(st.acc[j]); st.acc[j] = a.a; oa[j] = a.b; }
+      st.m = m.a; st.l = l.a;
+      softmax_merge(st, m.b, l.b, oa);
+    }
+    {
+      const LanePair m = halves_swap32(st.m), l = halves_swap32(st.l);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { const LanePair a = halves_swap32(st.acc[j]); st.acc[j] = a.a; oa[j] = a.b; }
+      st.m = m.a; st.l = l.a;
+      softmax_merge(st, m.b, l.b, oa);
+    }
   }
   if (team == 0) {
     sm[w4][ec][0] = st.m; sm[w4][ec][1] = st.l;
@@ -822,17 +873,26 @@ __device__ __forceinline__ void persist_helper_weights(const half_t* Wp, int n_t
   persist_helper_touch(reinterpret_cast<const unsigned char*>(Wp) + (size_t)s_lo * strip + off, min(part, all - off));
 }
 
-// Waits (bounded) until the first pair of an exchange matrix carries this step's tag; false on give-up.
-__device__ __forceinline__ bool persist_helper_wait(const unsigned char* buf, unsigned tag, unsigned limit) {
-  const __amdgpu_buffer_rsrc_t r = xch_rsrc(buf, 16);
-  unsigned spins = 0;
-  while (true) {
-    asm volatile("" ::: "memory");
-    const u32x4 v = xch_load16(r, 0);
-    if (v[1] == tag) return true;
-    if (++spins > limit) return false;
-    __builtin_amdgcn_s_sleep(8);
+// Waits (bounded) until the first pair of an exchange matrix carries this step's tag; false on give-up.  One wave
+// polls for the workgroup (every polling wave is a request to the same address).
+__device__ __forceinline__ bool persist_helper_wait(const unsigned char* buf, unsigned tag, unsigned limit, int* s_flag) {
+  if (threadIdx.x < 64) {
+    const __amdgpu_buffer_rsrc_t r = xch_rsrc(buf, 16);
+    unsigned spins = 0;
+    bool ok = true;
+    while (true) {
+      asm volatile("" ::: "memory");
+      const u32x4 v = xch_load16(r, 0);
+      if (v[1] == tag) break;
+      if (++spins > limit) { ok = false; break; }
+      __builtin_amdgcn_s_sleep(8);
+    }
+    if (threadIdx.x == 0) *s_flag = ok ? 1 : 0;
   }
+  lds_barrier();
+  const bool ok = *s_flag != 0;
+  lds_barrier();          // the flag is free for the next wait
+  return ok;
 }
 
 template <int RPW>
@@ -843,6 +903,7 @@ __device__ __forceinline__ void persist_helper(const PersistArgs& p, unsigned ta
   const int d = p.d, f = p.f, B = p.B, H = p.H, S = p.S;
   const int zg = (B + R - 1) / R, zg5 = (B + R5 - 1) / R5;
   const int n_streams = B * H, rows = min(S, p.kv_rows);
+  __shared__ int s_flag;
   const int lookahead = (p.dbg >> 4) ? (p.dbg >> 4) : 3;      // phases between a touch and its use (measurement hook: dbg / 16 overrides)
   for (int t = 0; t < 5 * p.n_layers; ++t) {
     const int l = t / 5, ph = t - 5 * l;
@@ -850,7 +911,7 @@ __device__ __forceinline__ void persist_helper(const PersistArgs& p, unsigned ta
       const int tw = t - lookahead, lw = tw / 5, pw = tw - 5 * lw;
       const unsigned char* xw = p.xch + (size_t)lw * p.xo.layer_bytes;
       const unsigned off = pw == 0 ? p.xo.qkv : pw == 1 ? p.xo.o : pw == 2 ? p.xo.y1 : pw == 3 ? p.xo.g : p.xo.y2;
-      if (!persist_helper_wait(xw + off, tag, p.spin_limit)) return;
+      if (!persist_helper_wait(xw + off, tag, p.spin_limit, &s_flag)) return;
     }
     const PersistLayer L = p.layers[l];
     if (ph == 0) persist_helper_weights(as_global(L.wqkv), 3 * d / 32, d, 2, zg, grid, x, rank, count);
@@ -971,7 +1032,7 @@ __global__ __launch_bounds__(kPersistThreads) void decode_persist_kernel(Persist
       PersistW<1, FRD> w_o;
       persist_w_issue<R, 1, FRD>(w_o, L.wo, d, d, B, no_w);
       const PersistUnit<R, 1> un = persist_unit<R, 1>(d, B, L.bo);
-      ok = persist_gemm_in<R, 1, PRO_COPY, PEPI_RES>(g, p, tag, smem_raw, sRes, &s_fail, un);
+      ok = persist_gemm_in<R, 1, PRO_COPY, PEPI_RES, RPW * FRD / 2>(g, p, tag, smem_raw, sRes, &s_fail, un);
       if (!ok) break;
       persist_stamp(tr, 7);
       persist_gemm_out<R, 1, FRD, PEPI_RES>(g, tag, smem_raw, red, sRes, un, w_o);
@@ -997,7 +1058,7 @@ __global__ __launch_bounds__(kPersistThreads) void decode_persist_kernel(Persist
       PersistW<1, FR5> w_2;
       persist_w_issue<R5, 1, FR5>(w_2, L.w2, d, f, B, no_w);
       const PersistUnit<R5, 1> un = persist_unit<R5, 1>(d, B, L.b2);
-      ok = persist_gemm_in<R5, 1, PRO_COPY, PEPI_RES>(g, p, tag, smem_raw, sRes, &s_fail, un);
+      ok = persist_gemm_in<R5, 1, PRO_COPY, PEPI_RES, RPW * FR5 / 4>(g, p, tag, smem_raw, sRes, &s_fail, un);
       if (!ok) break;
       persist_stamp(tr, 13);
       persist_gemm_out<R5, 1, FR5, PEPI_RES>(g, tag, smem_raw, red, sRes, un, w_2, tr, 24);
