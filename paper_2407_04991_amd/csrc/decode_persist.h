@@ -132,6 +132,7 @@ struct PersistArgs {
   int helpers_from;                     // workgroups from this id on (a multiple of 8) own no unit and warm the L2; = grid if none
   int kv_rows;                          // upper bound of the cache rows of any stream after this step (L2 warm-up only)
   unsigned red_off;                     // byte offset of the cross-wave reduction buffer in dynamic LDS (behind the largest A tile)
+  const half_t* table_p; int table_strips;   // packed projection table (32-column strips of K = d) that the next kernel streams, or null
   unsigned long long* trace;            // test hook: [workgroup][layer][32] 100 MHz time stamps (entry, input ready, done per phase), or null
 };
 
@@ -914,6 +915,8 @@ __device__ __forceinline__ void persist_helper(const PersistArgs& p, unsigned ta
       if (!persist_helper_wait(xw + off, tag, p.spin_limit, &s_flag)) return;
     }
     const PersistLayer L = p.layers[l];
+    unsigned long long* tr = p.trace ? as_global(p.trace) + ((size_t)blockIdx.x * p.n_layers + l) * 32 : nullptr;
+    persist_stamp(tr, 3 * ph);                     // tracing: the wait for the front ended
     if (ph == 0) persist_helper_weights(as_global(L.wqkv), 3 * d / 32, d, 2, zg, grid, x, rank, count);
     else if (ph == 2) persist_helper_weights(as_global(L.wo), d / 32, d, 1, zg, grid, x, rank, count);
     else if (ph == 3) persist_helper_weights(as_global(L.w1), f / 32, d, 2, zg, grid, x, rank, count);
@@ -932,6 +935,16 @@ __device__ __forceinline__ void persist_helper(const PersistArgs& p, unsigned ta
         persist_helper_touch(reinterpret_cast<const unsigned char*>(base), (size_t)rows * 128);
       }
     }
+    persist_stamp(tr, 3 * ph + 2);                 // tracing: this phase's lines have arrived in the L2
+  }
+  // The projection kernel that follows on the stream reads strip s of the table in workgroup s, i.e. on XCD s mod 8:
+  // with the last layer's operands in place, this XCD's helpers pull its strips (an eighth of the table, most of
+  // what an L2 holds) while the others finish the layer.
+  if (p.table_p && !(p.dbg & 4)) {
+    const half_t* tp = as_global(p.table_p);
+    const size_t strip = (size_t)d * 64;           // bytes
+    for (int j = rank; x + 8 * j < p.table_strips; j += count)
+      persist_helper_touch(reinterpret_cast<const unsigned char*>(tp) + (size_t)(x + 8 * j) * strip, strip);
   }
 }
 
@@ -947,6 +960,7 @@ __global__ __launch_bounds__(kPersistThreads) void decode_persist_kernel(Persist
   p.emb_g = as_global(p.emb_g); p.emb_b = as_global(p.emb_b); p.finished = as_global(p.finished);
   p.slot = as_global(p.slot); p.xch = as_global(p.xch); p.epoch = as_global(p.epoch); p.X = as_global(p.X);
   p.hidden_out = as_global(p.hidden_out); p.err = as_global(p.err); p.trace = as_global(p.trace);
+  p.table_p = as_global(p.table_p);
   extern __shared__ __align__(16) unsigned char smem_raw[];      // the A tile, then `red` behind it (p.red_off)
   __shared__ __align__(16) half_t sRes[16 * 32];
   __shared__ float sm[2][4][8][10];

@@ -659,6 +659,7 @@ int decode_layers_persist(ErnieHandle* h, const int* tok, float* logits_out, flo
   a.dbg = h->persist_dbg;
   a.trace = (h->persist_trace && h->cu_count <= kPersistTraceGroups)
                 ? reinterpret_cast<unsigned long long*>(h->arena + h->plan.trace) : nullptr;
+  a.table_p = h->tok_p; a.table_strips = c.vocab_kept / 32;      // whole strips only
   a.err = h->err_host; a.spin_limit = h->persist_spin; a.stall = h->persist_stall; a.attn_nt = h->attn_nt;
   const int rpw = B > 32 ? 2 : 1;
   // dynamic LDS: the largest A tile ([8 or 16 rows][d + 8], [4 or 8 rows][f + 8] fp16), then the cross-wave
