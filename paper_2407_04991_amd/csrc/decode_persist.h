@@ -580,18 +580,27 @@ __device__ __forceinline__ void persist_kv_issue(PersistKV<U>& F, const PersistA
   const int cb = p.slot ? p.slot[b] : b;
   const half_t* Kb = L.kc + ((size_t)cb * H + h) * S * 64 + ec * 8;
   const half_t* Vb = L.vc + ((size_t)cb * H + h) * S * 64 + ec * 8;
+  // Rows past the cached length are not requested (their lane repeats the last written row and gives it weight
+  // zero): what a lane holds is always data some step has written, never arbitrary bits.
+  const int len = min(ld_global(p.cache_len + b), S);
+  const int last = max(len - 1, 0);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const size_t row = (size_t)min((w4 * U + u) * 8 + team, S - 1) * 64;     // clamped to the capacity, masked later
+    const size_t row = (size_t)min((w4 * U + u) * 8 + team, last) * 64;
     F.k[u] = ld_kv<NT>(Kb + row);
     F.v[u] = ld_kv<NT>(Vb + row);
   }
-  F.len = p.cache_len[b];
+  F.len = len;
+}
+
+__device__ __forceinline__ half2_t half_pair(const half8& v, int j) {
+  const half2_t r = {v[2 * j], v[2 * j + 1]};
+  return r;
 }
 
 // q (scaled), k, v of the new token of one stream, as the attention uses them.
 struct PersistQKV {
-  float q[8];
+  half2_t q[4];           // scaled by 1/8 (exact in fp16)
   half8 knew, vnew;
 };
 
@@ -616,11 +625,10 @@ __device__ __forceinline__ bool persist_qkv_wait(PersistQKV& o, const PersistArg
     if (__all(ok)) break;
     if (++spins > p.spin_limit) { good = false; break; }
   }
-  float qq[8];
-  unpack_h2(a[0][0][0], qq[0], qq[1]); unpack_h2(a[0][0][2], qq[2], qq[3]);
-  unpack_h2(a[0][1][0], qq[4], qq[5]); unpack_h2(a[0][1][2], qq[6], qq[7]);
-#pragma unroll
-  for (int j = 0; j < 8; ++j) o.q[j] = qq[j] * 0.125f;
+  const half2_t eighth = {(half_t)0.125f, (half_t)0.125f};
+  const unsigned q01 = a[0][0][0], q23 = a[0][0][2], q45 = a[0][1][0], q67 = a[0][1][2];   // (scalars first: a bit cast applied to a vector element directly reads element 0)
+  o.q[0] = __builtin_bit_cast(half2_t, q01) * eighth; o.q[1] = __builtin_bit_cast(half2_t, q23) * eighth;
+  o.q[2] = __builtin_bit_cast(half2_t, q45) * eighth; o.q[3] = __builtin_bit_cast(half2_t, q67) * eighth;
   const u32x4 kw = {a[1][0][0], a[1][0][2], a[1][1][0], a[1][1][2]};
   const u32x4 vw = {a[2][0][0], a[2][0][2], a[2][1][0], a[2][1][2]};
   o.knew = __builtin_bit_cast(half8, kw);
@@ -643,42 +651,64 @@ __device__ __forceinline__ void persist_attn_stream(SoftmaxPart& st, const Persi
   int g0 = w4 * U;
 #pragma unroll
   for (int u = 0; u < U; ++u) { key[u] = (g0 + u) * 8 + team; kf[u] = F.k[u]; vf[u] = F.v[u]; }
-  const int len = F.len;
+  const int len = F.len;                        // cached rows (at most S)
   const bool has_new = len < S;                 // a replayed step past capacity appends nothing
-  const int c = has_new ? len + 1 : S;
-  const int newest = has_new ? len : -1;        // this key comes from registers, not from the cache
+  const int last = max(len - 1, 0);
+  if (len == 0) {                               // nothing cached yet: the repeated "last row" is unwritten memory
+    const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int u = 0; u < U; ++u) vf[u] = z;
+  }
   if (has_new && w4 == 0 && team == 0) {
     st_global(reinterpret_cast<half8*>(Kb + (size_t)len * 64), x.knew);
     st_global(reinterpret_cast<half8*>(Vb + (size_t)len * 64), x.vnew);
   }
-  while (g0 * 8 < c) {
+  // the new token's own key and value come from registers: one team of one wave takes them as an extra term
+  const bool mine_new = has_new && w4 == 0 && team == 0;
+  float sc_new;
+  {
+    float pr = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) pr = __builtin_amdgcn_fdot2(x.q[j], half_pair(x.knew, j), pr, false);
+    pr = team8_sum(pr);
+    sc_new = mine_new ? pr : -INFINITY;
+  }
+  bool first = true;
+  // One running maximum for the whole wave (every lane holds the same st.m): the eight teams' partial sums then
+  // share a scale and are simply added at the end, instead of merged pairwise with their own maxima.
+  while (first || g0 * 8 < len) {
     float sc[U];
-    float mx = st.m;
-    half8 vcur[U];
+    float mx = first ? sc_new : -INFINITY;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const bool valid = key[u] < c;
-      const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (key[u] == newest) { kf[u] = x.knew; vf[u] = x.vnew; }
       float pr = 0.f;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) pr += x.q[j] * (float)kf[u][j];
+      for (int j = 0; j < 4; ++j) pr = __builtin_amdgcn_fdot2(x.q[j], half_pair(kf[u], j), pr, false);
       pr = team8_sum(pr);
-      sc[u] = valid ? pr : -INFINITY;
-      vcur[u] = valid ? vf[u] : z;               // rows past the valid length hold arbitrary bits: weight 0 must meet value 0
+      sc[u] = key[u] < len ? pr : -INFINITY;
       mx = fmaxf(mx, sc[u]);
     }
+    half8 vcur[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) vcur[u] = vf[u];
     g0 += NW * U;
-    if (g0 * 8 < c) {                            // next batch in flight during the softmax update
+    if (g0 * 8 < len) {                          // next batch in flight during the softmax update
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         key[u] = (g0 + u) * 8 + team;
-        const size_t row = (size_t)min(key[u], S - 1) * 64;
+        const size_t row = (size_t)min(key[u], last) * 64;
         kf[u] = ld_kv<NT>(Kb + row);
         vf[u] = ld_kv<NT>(Vb + row);
       }
     }
-    if (mx != -INFINITY) {
+    {  // maximum over the eight teams (the lanes of a team agree already)
+      mx = fmaxf(mx, lane_xor8(mx));
+      const LanePair r = rows_swap16(mx);
+      mx = fmaxf(r.a, r.b);
+      const LanePair hh = halves_swap32(mx);
+      mx = fmaxf(st.m, fmaxf(hh.a, hh.b));
+    }
+    if (mx != -INFINITY) {                       // uniform for the wave
       const float alpha = (st.m == -INFINITY) ? 0.f : __expf(st.m - mx);
       st.l *= alpha;
 #pragma unroll
@@ -690,27 +720,31 @@ __device__ __forceinline__ void persist_attn_stream(SoftmaxPart& st, const Persi
 #pragma unroll
         for (int j = 0; j < 8; ++j) st.acc[j] += pr * (float)vcur[u][j];
       }
+      if (first) {
+        const float pr = __expf(sc_new - mx);    // zero except in the one team that owns the new token
+        st.l += pr;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) st.acc[j] += pr * (float)x.vnew[j];
+      }
       st.m = mx;
     }
+    first = false;
   }
-  {  // the eight teams of the wave: lane ^ 8, then row ^ 1, then half ^ 1 (each lane keeps its eight features)
-    float oa[8];
+  {  // sums over the eight teams: lane ^ 8, then row ^ 1, then half ^ 1 (each lane keeps its eight features)
+    st.l += lane_xor8(st.l);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) oa[j] = lane_xor8(st.acc[j]);
-    softmax_merge(st, lane_xor8(st.m), lane_xor8(st.l), oa);
+    for (int j = 0; j < 8; ++j) st.acc[j] += lane_xor8(st.acc[j]);
     {
-      const LanePair m = rows_swap16(st.m), l = rows_swap16(st.l);
+      const LanePair l = rows_swap16(st.l);
+      st.l = l.a + l.b;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) { const LanePair a = rows_swap16(st.acc[j]); st.acc[j] = a.a; oa[j] = a.b; }
-      st.m = m.a; st.l = l.a;
-      softmax_merge(st, m.b, l.b, oa);
+      for (int j = 0; j < 8; ++j) { const LanePair a = rows_swap16(st.acc[j]); st.acc[j] = a.a + a.b; }
     }
     {
-      const LanePair m = halves_swap32(st.m), l = halves_swap32(st.l);
+      const LanePair l = halves_swap32(st.l);
+      st.l = l.a + l.b;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) { const LanePair a = halves_swap32(st.acc[j]); st.acc[j] = a.a; oa[j] = a.b; }
-      st.m = m.a; st.l = l.a;
-      softmax_merge(st, m.b, l.b, oa);
+      for (int j = 0; j < 8; ++j) { const LanePair a = halves_swap32(st.acc[j]); st.acc[j] = a.a + a.b; }
     }
   }
   if (team == 0) {
@@ -730,11 +764,15 @@ __device__ __forceinline__ void persist_attn_publish(SoftmaxPart& st, float (*sm
 #pragma unroll
     for (int j = 0; j < 8; ++j) o8[j] = 0.f;
   } else {
+    // the four waves' partial sums in one level: a common maximum, four independent scales
+    const float m1 = sm[1][ec][0], m2 = sm[2][ec][0], m3 = sm[3][ec][0];
+    const float mx = fmaxf(fmaxf(st.m, m1), fmaxf(m2, m3));
+    const float s0 = __expf(st.m - mx), s1 = __expf(m1 - mx), s2 = __expf(m2 - mx), s3 = __expf(m3 - mx);   // a wave without keys has m = -inf: scale 0
+    const float l = st.l * s0 + sm[1][ec][1] * s1 + sm[2][ec][1] * s2 + sm[3][ec][1] * s3;
+    const float inv = __builtin_amdgcn_rcpf(l);
 #pragma unroll
-    for (int w = 1; w < 4; ++w) softmax_merge(st, sm[w][ec][0], sm[w][ec][1], &sm[w][ec][2]);
-    const float inv = 1.0f / st.l;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) o8[j] = st.acc[j] * inv;
+    for (int j = 0; j < 8; ++j)
+      o8[j] = (st.acc[j] * s0 + sm[1][ec][2 + j] * s1 + sm[2][ec][2 + j] * s2 + sm[3][ec][2 + j] * s3) * inv;
   }
   if (!withhold) {
     const unsigned off = ((unsigned)b * d + h * 64 + ec * 8) * 4;
