@@ -397,6 +397,81 @@ def handover_bench(args):
                       "rows": rows}), flush=True)
 
 
+def phase_trace_bench(args):
+    """Where the time of the one-launch decode step goes: every workgroup of decode_persist_kernel stamps a 100 MHz
+    counter at the entry of each phase, when its input has arrived and when its output is published (test hook
+    `persist_trace`; helper workgroups stamp when their L2 warm-up of a phase has landed).  Prints ONE JSON line with
+    the length of each phase along the chain, the lateness of each XCD's workgroups and the lead of the helpers."""
+    import ctypes as C
+    import numpy as np
+    import torch
+    import paper_2407_04991_amd as E
+    from synth import make_workload
+    assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
+    wl = make_workload(args.workload, **{kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.shape})
+    sh = wl.shape
+    assert sh.batch <= 64, "the one-launch decode kernel runs at batch <= 64"
+    eng = E.engine_from_workload(wl)
+    for kv in args.tune:
+        k, v = kv.split("=")
+        eng.tune(k, int(v))
+    ids, lens = wl.padded(0)
+    eng.prefill(torch.as_tensor(ids), lens)
+    for _ in range(5):
+        eng.decode_step(None)
+    reps = []
+    hip = C.CDLL("libamdhip64.so")
+    for _ in range(max(1, args.steps)):
+        eng.tune("persist_trace", 1)
+        eng.decode_step(None)
+        torch.cuda.synchronize()
+        ptr, nbytes = eng.debug_buffer("persist_trace")
+        host = np.zeros(nbytes // 8, dtype=np.uint64)
+        rc = hip.hipMemcpy(host.ctypes.data_as(C.c_void_p), C.c_void_p(ptr), C.c_size_t(nbytes), 2)
+        assert rc == 0, rc
+        eng.tune("persist_trace", 0)
+        G = nbytes // 8 // (sh.n_layers * 32)
+        raw = host.reshape(G, sh.n_layers, 32)
+        tr = raw.astype(np.float64) / 100.0            # microseconds
+        B, d, f, H = sh.batch, sh.d_model, sh.d_ffn, sh.n_heads
+        rpw = 2 if B > 32 else 1
+        zg, zg5 = -(-B // (8 * rpw)), -(-B // (4 * rpw))
+        units = [((3 * d // 32 + 1) // 2) * zg, min(-(-(B * H) // 2), G), (d // 32) * zg, ((f // 32 + 1) // 2) * zg, (d // 32) * zg5]
+        names = ["qkv", "attention", "attention_output", "ffn1", "ffn2"]
+        t0 = tr[:, 0, 0][tr[:, 0, 0] > 0].min()
+        ends = np.array([[tr[:units[ph], l, 3 * ph + 2].max() - t0 for ph in range(5)] for l in range(sh.n_layers)])
+        chain = np.diff(np.concatenate([[0.0], ends.reshape(-1)])).reshape(sh.n_layers, 5)
+        rep = {"kernel_us": float(tr[:max(units), sh.n_layers - 1, 14].max() - t0),
+               "phase_us_along_the_chain": {names[i]: round(float(chain[1:, i].mean()), 2) for i in range(5)},
+               "layer_us": round(float(chain[1:].sum(1).mean()), 2), "phases": {}}
+        hf = (max(units) + 7) // 8 * 8
+        for ph in range(5):
+            n = units[ph]
+            e, r, dn = tr[:n, 1:, 3 * ph], tr[:n, 1:, 3 * ph + 1], tr[:n, 1:, 3 * ph + 2]
+            late = (r - r.min(axis=0, keepdims=True)).mean(axis=1)
+            by_xcd = [round(float(late[np.arange(n) % 8 == x].mean()), 2) for x in range(8)]
+            row = {"workgroups": int(n), "input_wait_us_mean": round(float((r - e).mean()), 2),
+                   "compute_us_mean": round(float((dn - r).mean()), 2),
+                   "ready_spread_us": round(float((r.max(axis=0) - r.min(axis=0)).mean()), 2),
+                   "ready_lateness_by_xcd_us": by_xcd}
+            if G >= hf + 8:
+                lead = []
+                for x in range(8):
+                    hs = np.array([w for w in range(hf, G) if w % 8 == x])
+                    lead.append(round(float((r.min(axis=0) - tr[hs, 1:, 3 * ph + 2].max(axis=0)).mean()), 2))
+                row["helper_lead_before_first_ready_by_xcd_us"] = lead
+            rep["phases"][names[ph]] = row
+        cyc = raw[:max(units), sh.n_layers - 1, 15].astype(np.float64) - raw[:max(units), 0, 15].astype(np.float64)
+        dur = tr[:max(units), sh.n_layers - 1, 14] - tr[:max(units), 0, 0]
+        ghz = cyc / np.maximum(dur, 1e-9) / 1000.0
+        rep["shader_clock_ghz_by_xcd"] = [round(float(ghz[np.arange(max(units)) % 8 == x].mean()), 3) for x in range(8)]
+        reps.append(rep)
+    eng.close()
+    print(json.dumps({"metric": "phases of the one-launch decode step (1 GPU)", "unit": "us", "n_gpus": 1, "data": "synthetic",
+                      "config": {"workload": f"{args.workload}: {sh.n_layers} layers d={sh.d_model} batch {sh.batch}, the sixth decode step after the prefill",
+                                 "tune": args.tune}, "traced_steps": reps}), flush=True)
+
+
 def pipeline_bench(args):
     """The host pipeline on ERNIE-base-shaped requests: the same job with the stages one after another and side
     by side.  Requests are full-vocabulary prompts (Zipf ids, lengths as in the named workload), kept rows and
@@ -465,6 +540,8 @@ def main():
                     "stages one after another vs side by side) instead of the headline benchmark")
     ap.add_argument("--handover", action="store_true", help="measure the hand-over between persistent workgroups (the "
                     "phase boundary of the one-launch decode step) instead of the headline benchmark")
+    ap.add_argument("--phase-trace", action="store_true", help="time stamps from inside the one-launch decode kernel: phase "
+                    "lengths, per-XCD lateness, helper lead (prints one JSON line; --steps = decode steps traced)")
     ap.add_argument("--requests", type=int, default=512, help="pipeline: number of requests in the job")
     ap.add_argument("--compact-every", type=int, default=16, help="eos sweep: steps between batch compactions")
     ap.add_argument("--corpus-mtok", type=int, default=64, help="trim sweep: corpus size in Mi tokens")
@@ -487,6 +564,8 @@ def main():
         return pipeline_bench(args)
     if args.handover:
         return handover_bench(args)
+    if args.phase_trace:
+        return phase_trace_bench(args)
 
     import numpy as np
     import torch
