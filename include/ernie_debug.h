@@ -18,7 +18,8 @@ extern "C" {
  * internal buffer, for layer-by-layer comparison with a reference.  `name`
  * is one of "x" (layer input/output activations [T, d] fp16), "kv" (the
  * key/value cache [n_layers][2][max_batch][n_heads][max_seq][64] fp16),
- * "lens" ([max_batch] int32 cached lengths).  Returns ERNIE_EINVAL for an
+ * "lens" ([max_batch] int32 cached lengths), "persist_trace" (the time stamps of the
+ * one-launch decode kernel, see the "persist_trace" knob below).  Returns ERNIE_EINVAL for an
  * unknown name.  Not part of the hot path.
  */
 ERNIE_API int ernie_debug_buffer(ErnieHandle* h, const char* name, void** ptr_dev, size_t* bytes);
@@ -92,6 +93,20 @@ ERNIE_API int ernie_profile_read(ErnieHandle* h, int category, double* total_ms,
  *                       3 = 64 x 64.  Does not change any result.
  *   "attn_nt" 0/1       decode attention reads the cache with the non-temporal (streaming) hint, so that the
  *                       once-per-step cache stream does not displace the weights from the caches (default 1)
+ *   "persist" 0/1       batch <= 64: all layers of a decode step in one persistent kernel (default 1 where it fits), or
+ *                       five kernels per layer
+ *   "persist_helpers" 0/1  workgroups of that kernel that own no unit run ahead and pull weights and cache rows into
+ *                       the L2 of the XCD that will read them (default 1).  Does not change any result.
+ *   "persist_spin" >= 1 polls after which a workgroup of that kernel gives up a wait (default 2^17); the step then
+ *                       ends by itself and the next call on the handle returns ERNIE_EHIP
+ *   "persist_stall" 0..5  test hook: withhold the output of phase 1..5 (QKV, attention, attention output, FFN1, FFN2)
+ *                       of layer 0, so that its consumers' bounded waits give up (0 = off)
+ *   "persist_trace" 0/1 every workgroup of that kernel writes 100 MHz time stamps (phase entry, input arrived, output
+ *                       published; helpers: wait ended, warm-up landed) into the buffer "persist_trace",
+ *                       [workgroup][layer][32] uint64 (see ernie_debug_buffer); for at most 512 workgroups
+ *   "persist_dbg"       measurement hook, bit mask: 1 = helper workgroups idle, 2 = no weight loads (results are
+ *                       wrong), 4 = helpers leave the projection table alone; value / 16 = phases the helpers stay
+ *                       ahead of the publishing front (0 = default, 3)
  * Splits are 1, 2 or 4.  Results are deterministic for any fixed setting.  Returns ERNIE_EINVAL for an
  * unknown key or a split that is not supported or does not divide the k-tile count.
  */
