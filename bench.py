@@ -433,10 +433,8 @@ def phase_trace_bench(args):
         G = nbytes // 8 // (sh.n_layers * 32)
         raw = host.reshape(G, sh.n_layers, 32)
         tr = raw.astype(np.float64) / 100.0            # microseconds
-        B, d, f, H = sh.batch, sh.d_model, sh.d_ffn, sh.n_heads
-        rpw = 2 if B > 32 else 1
-        zg, zg5 = -(-B // (8 * rpw)), -(-B // (4 * rpw))
-        units = [((3 * d // 32 + 1) // 2) * zg, min(-(-(B * H) // 2), G), (d // 32) * zg, ((f // 32 + 1) // 2) * zg, (d // 32) * zg5]
+        # slot 31 of a layer: bit mask of the phases the workgroup owned a unit of (units are the first workgroups of a phase)
+        units = [int(((raw[:, 1, 31] >> ph) & 1).sum()) for ph in range(5)]
         names = ["qkv", "attention", "attention_output", "ffn1", "ffn2"]
         t0 = tr[:, 0, 0][tr[:, 0, 0] > 0].min()
         ends = np.array([[tr[:units[ph], l, 3 * ph + 2].max() - t0 for ph in range(5)] for l in range(sh.n_layers)])

@@ -103,7 +103,8 @@ ERNIE_API int ernie_profile_read(ErnieHandle* h, int category, double* total_ms,
  *                       of layer 0, so that its consumers' bounded waits give up (0 = off)
  *   "persist_trace" 0/1 every workgroup of that kernel writes 100 MHz time stamps (phase entry, input arrived, output
  *                       published; helpers: wait ended, warm-up landed) into the buffer "persist_trace",
- *                       [workgroup][layer][32] uint64 (see ernie_debug_buffer); for at most 512 workgroups
+ *                       [workgroup][layer][32] uint64 (see ernie_debug_buffer; slot 31 = bit mask of the phases the workgroup owned
+ *                       a unit of); for at most 512 workgroups
  *   "persist_dbg"       measurement hook, bit mask: 1 = helper workgroups idle, 2 = no weight loads (results are
  *                       wrong), 4 = helpers leave the projection table alone; value / 16 = phases the helpers stay
  *                       ahead of the publishing front (0 = default, 3)

@@ -1033,6 +1033,7 @@ __global__ __launch_bounds__(kPersistThreads) void decode_persist_kernel(Persist
     const bool hook = l == 0;
     unsigned long long* tr = p.trace ? p.trace + ((size_t)blockIdx.x * p.n_layers + l) * 32 : nullptr;
     persist_stamp(tr, 0);
+    unsigned owned = 0;
     if (tr && l == 0 && threadIdx.x == 0) tr[15] = clock64();      // shader clock at the start (slot 15 of layer 0)
     {  // phase 1: QKV = LayerNorm(previous layer's sum, or the embedding) x Wqkv^T + bqkv
       PersistGemm g{};
@@ -1041,6 +1042,7 @@ __global__ __launch_bounds__(kPersistThreads) void decode_persist_kernel(Persist
       PersistW<2, FRD> w_qkv;
       persist_w_issue<R, 2, FRD>(w_qkv, L.wqkv, 3 * d, d, B, no_w);
       const PersistUnit<R, 2> un = persist_unit<R, 2>(3 * d, B, L.bqkv);
+      if (un.has) owned |= 1u;
       if (l == 0) {
         g.gamma = p.emb_g; g.beta = p.emb_b;
         ok = persist_gemm_in<R, 2, PRO_EMBED, PEPI_BIAS>(g, p, tag, smem_raw, sRes, &s_fail, un);
@@ -1068,6 +1070,7 @@ __global__ __launch_bounds__(kPersistThreads) void decode_persist_kernel(Persist
       }
       persist_stamp(tr, 4);
       const bool wh = hook && p.stall == 2;
+      if (me * 2 < n_streams) owned |= 2u;
       if (me * 2 < n_streams)
         ok = p.attn_nt ? persist_attn_pair<U, true>(p, L, xl, tag, wh, me, kv, true, x, true, good, sm, &s_fail, tr)
                        : persist_attn_pair<U, false>(p, L, xl, tag, wh, me, kv, true, x, true, good, sm, &s_fail, tr);
@@ -1084,6 +1087,7 @@ __global__ __launch_bounds__(kPersistThreads) void decode_persist_kernel(Persist
       PersistW<1, FRD> w_o;
       persist_w_issue<R, 1, FRD>(w_o, L.wo, d, d, B, no_w);
       const PersistUnit<R, 1> un = persist_unit<R, 1>(d, B, L.bo);
+      if (un.has) owned |= 4u;
       ok = persist_gemm_in<R, 1, PRO_COPY, PEPI_RES, RPW * FRD / 2>(g, p, tag, smem_raw, sRes, &s_fail, un);
       if (!ok) break;
       persist_stamp(tr, 7);
@@ -1097,6 +1101,7 @@ __global__ __launch_bounds__(kPersistThreads) void decode_persist_kernel(Persist
       PersistW<2, FRD> w_1;
       persist_w_issue<R, 2, FRD>(w_1, L.w1, f, d, B, no_w);
       const PersistUnit<R, 2> un = persist_unit<R, 2>(f, B, L.b1);
+      if (un.has) owned |= 8u;
       ok = persist_gemm_in<R, 2, PRO_LN, PEPI_GELU>(g, p, tag, smem_raw, sRes, &s_fail, un);
       if (!ok) break;
       persist_stamp(tr, 10);
@@ -1110,12 +1115,14 @@ __global__ __launch_bounds__(kPersistThreads) void decode_persist_kernel(Persist
       PersistW<1, FR5> w_2;
       persist_w_issue<R5, 1, FR5>(w_2, L.w2, d, f, B, no_w);
       const PersistUnit<R5, 1> un = persist_unit<R5, 1>(d, B, L.b2);
+      if (un.has) owned |= 16u;
       ok = persist_gemm_in<R5, 1, PRO_COPY, PEPI_RES, RPW * FR5 / 4>(g, p, tag, smem_raw, sRes, &s_fail, un);
       if (!ok) break;
       persist_stamp(tr, 13);
       persist_gemm_out<R5, 1, FR5, PEPI_RES>(g, tag, smem_raw, red, sRes, un, w_2, tr, 24);
     }
     persist_stamp(tr, 14);
+    if (tr && threadIdx.x == 0) tr[31] = owned;      // tracing: the phases (bit 0 = QKV .. bit 4 = FFN2) this workgroup owned a unit of
   }
   if (ok) {
     const int last = p.n_layers - 1;
