@@ -463,6 +463,8 @@ def phase_trace_bench(args):
         dur = tr[:max(units), sh.n_layers - 1, 14] - tr[:max(units), 0, 0]
         ghz = cyc / np.maximum(dur, 1e-9) / 1000.0
         rep["shader_clock_ghz_by_xcd"] = [round(float(ghz[np.arange(max(units)) % 8 == x].mean()), 3) for x in range(8)]
+        start = tr[:max(units), 0, 0]
+        rep["kernel_start_by_xcd_us"] = [round(float(start[np.arange(max(units)) % 8 == x].mean() - t0), 2) for x in range(8)]
         reps.append(rep)
     eng.close()
     print(json.dumps({"metric": "phases of the one-launch decode step (1 GPU)", "unit": "us", "n_gpus": 1, "data": "synthetic",
